@@ -1,0 +1,170 @@
+/*
+ * tier.h -- C ABI of the data-tiering hot path for mini-batch GNN training
+ *           on one MI355X (gfx950).
+ *
+ * The library keeps frequently read node-feature rows in GPU memory (HBM) and
+ * the rest in pinned host memory that GPU threads read directly ("zero-copy"),
+ * after the method of "Graph Neural Network Training with Data Tiering"
+ * (Min et al., MLSys 2022).  Its four steps:
+ *
+ *   tier_presample          access count of every node over sampled mini-batches
+ *                           (the measured access frequency of Sec. 3.1 / Sec. 5.2)
+ *   tier_place              order nodes by count, keep the top rows in HBM
+ *                           (Sec. 3.2 ordering and old-id -> rank map, Sec. 4.1 placement)
+ *   tier_sample_minibatch   uniform fixed-fanout neighbour sampling and the
+ *                           sub-graph of the sampled nodes (Sec. 2.2)
+ *   tier_gather_features    dense rows for a list of node ids, each row read
+ *                           from HBM when placed there and from host memory
+ *                           otherwise (Sec. 4.1; Listing 1 without peer GPUs)
+ *
+ * Conventions
+ *   - Every pointer is marked (device) or (host).  "device" means memory the GPU
+ *     can address: hipMalloc memory, or pinned host memory for the feature table.
+ *   - The caller owns every buffer it passes in; the library owns the context,
+ *     the HBM cache, the node->slot map and its scratch memory.
+ *   - All work is enqueued on the HIP stream given to tier_create.  A call that
+ *     returns host-side results (sizes, counters) waits for that stream; the
+ *     others return once the work is enqueued.
+ *   - Return value: TIER_OK (0) or a negative tier_status.  Nothing is thrown and
+ *     nothing is printed.  tier_strerror names a status; tier_last_hip_error gives
+ *     the HIP error behind a TIER_EHIP.
+ *   - A context must not be used from two threads at once.
+ *   - Node ids are int32 in [0, n_nodes); adjacency lists hold no duplicates;
+ *     every degree is below 2^31.
+ */
+#ifndef TIER_H
+#define TIER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TIER_MAX_LAYERS 8    /* hops per mini-batch                              */
+#define TIER_MAX_FANOUT 64   /* neighbours drawn per node per hop (one wavefront) */
+
+typedef enum {
+    TIER_OK = 0,
+    TIER_EINVAL = -1,     /* bad argument: null pointer, size < 0, row_bytes not a multiple of 16,
+                             fanout outside [1, TIER_MAX_FANOUT], layers outside [1, TIER_MAX_LAYERS] */
+    TIER_ENOMEM = -2,     /* host or device allocation failed                                      */
+    TIER_EHIP = -3,       /* a HIP call failed; see tier_last_hip_error                            */
+    TIER_ECAPACITY = -4,  /* a caller-provided output buffer is smaller than the upper bound       */
+    TIER_ESTATE = -5      /* call out of order (gather before place)                               */
+} tier_status;
+
+typedef struct tier_ctx tier_ctx;
+
+/* Graph in compressed sparse rows (Sec. 3.2: node list + edge list).  Row v lists
+ * the nodes that are sampled for v, i.e. the sources of the edges into v. */
+typedef struct {
+    int64_t n_nodes;
+    int64_t n_edges;
+    const void *indptr;       /* (device) n_nodes + 1 offsets, int32 or int64       */
+    int32_t indptr_is_i64;    /* 0: int32 offsets, 1: int64 offsets                 */
+    const int32_t *indices;   /* (device) n_edges neighbour ids                      */
+} tier_csr;
+
+/* Node feature table, one row per node (Sec. 2.1: N x D matrix; rows of 512 B - 4 KB). */
+typedef struct {
+    const void *host_rows;    /* (device-visible pinned host) n_nodes * row_bytes bytes,
+                                 e.g. from tier_host_alloc or hipHostMalloc            */
+    int64_t row_bytes;        /* bytes per row, a multiple of 16                       */
+} tier_feat;
+
+/* Sub-graph of one mini-batch: one block per hop (Sec. 2.2).
+ * frontier_0 = the seeds; frontier_{l+1} = frontier_l followed by the nodes first
+ * reached at hop l in ascending id order.  nodes[] holds frontier_L, and frontier_l
+ * is its first n_nodes[l] entries.  Block l: dst = frontier_l, src = frontier_{l+1};
+ * the sampled neighbours of dst i are entries row_ptr[l][i] .. row_ptr[l][i+1]-1 of
+ * col[l] (index into nodes[]) and eid[l] (position in the graph's indices[]).
+ * The caller allocates the device buffers to the sizes tier_blocks_bounds reports
+ * and fills the cap_* fields; the library fills n_nodes / n_edges. */
+typedef struct {
+    int32_t *nodes;                       /* (device) cap_nodes entries                  */
+    int64_t cap_nodes;
+    int32_t *row_ptr[TIER_MAX_LAYERS];    /* (device) cap_dst[l] + 1 entries             */
+    int32_t *col[TIER_MAX_LAYERS];        /* (device) cap_edges[l] entries               */
+    int64_t *eid[TIER_MAX_LAYERS];        /* (device) cap_edges[l] entries               */
+    int64_t cap_dst[TIER_MAX_LAYERS];
+    int64_t cap_edges[TIER_MAX_LAYERS];
+    int64_t n_nodes[TIER_MAX_LAYERS + 1]; /* (host, out) |frontier_l|, l = 0..n_layers   */
+    int64_t n_edges[TIER_MAX_LAYERS];     /* (host, out) edges of block l                */
+} tier_blocks;
+
+typedef struct {
+    int64_t hit_rows;    /* rows read from the HBM cache   */
+    int64_t miss_rows;   /* rows read from host memory     */
+} tier_gather_stats;
+
+/* Pinned, GPU-mapped host memory for a feature table (the zero-copy space of
+ * Sec. 4.1).  *ptr is valid on the host and on the GPU.  Free with tier_host_free. */
+int tier_host_alloc(void **ptr, size_t bytes);
+int tier_host_free(void *ptr);
+
+/* Upper bounds of the sizes of one mini-batch's blocks: frontier sizes
+ * cap_nodes[0..n_layers] and per-hop edge counts cap_edges[0..n_layers-1], both
+ * (host, out).  Block l needs cap_dst = cap_nodes[l]; nodes[] needs cap_nodes[n_layers]. */
+int tier_blocks_bounds(int64_t n_graph_nodes, int64_t n_seeds, const int32_t *fanouts /* host */,
+                       int32_t n_layers, int64_t *cap_nodes, int64_t *cap_edges);
+
+/* Create a context for one graph and one feature table on the current device.
+ * The graph arrays and the feature table are referenced, not copied, and must
+ * outlive the context.  stream is a hipStream_t (NULL = the default stream).
+ * Allocates scratch proportional to n_nodes (about 4.2 bytes per node). */
+int tier_create(tier_ctx **out, const tier_csr *csr, const tier_feat *feat, void *stream);
+void tier_destroy(tier_ctx *ctx);
+
+/* Access counts (Sec. 3.1, Sec. 5.2).  train_ids (device, n_train ids, distinct) is
+ * cut into consecutive mini-batches of batch_size seeds in the given order; batch b
+ * of epoch e is sampled exactly as tier_sample_minibatch would with the seed
+ * tier_batch_seed(seed, e, b); counts[v] (device, n_nodes entries, overwritten) is
+ * the number of (epoch, batch) pairs whose sampled sub-graph contains v, i.e. the
+ * number of feature rows of v a gather per mini-batch would read.  Asynchronous.
+ * total_rows / total_edges (host, optional): sums over all batches of the frontier
+ * size and of the sampled edges; asking for either makes the call wait. */
+int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
+                   const int32_t *fanouts /* host */, int32_t n_layers, int32_t epochs, uint64_t seed,
+                   uint32_t *counts, int64_t *total_rows, int64_t *total_edges);
+
+/* Seed of mini-batch `batch` of epoch `epoch` derived from a run seed (host only). */
+uint64_t tier_batch_seed(uint64_t seed, uint32_t epoch, uint32_t batch);
+
+/* Placement (Sec. 3.2, Sec. 4.1).  Nodes are ordered by descending count, equal
+ * counts by ascending id; rank = position in that order (the old-id -> rank map of
+ * Sec. 3.2).  The first n_hot = min(n_nodes, budget_bytes / row_bytes) rows are
+ * copied into an HBM cache owned by the context (cache row = rank) and the
+ * node->slot map becomes slot[v] = rank[v] if rank[v] < n_hot, else -1.  Replaces
+ * any earlier placement.  counts: (device) n_nodes entries.  slot_map (device,
+ * optional): receives a copy of the map.  n_hot (host, optional).  Waits. */
+int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes,
+               int32_t *slot_map, int64_t *n_hot);
+
+/* One mini-batch (Sec. 2.2).  seeds: (device) n_seeds distinct node ids.  At hop l
+ * every node of frontier_l draws min(fanouts[l], degree) distinct neighbours
+ * uniformly at random (all of them, in adjacency order, when degree <= fanouts[l]);
+ * draws are a pure function of (seed, node, hop, draw index), so a mini-batch is
+ * reproducible.  Buffers in *out must reach the bounds of tier_blocks_bounds, else
+ * TIER_ECAPACITY.  Waits (it returns the block sizes). */
+int tier_sample_minibatch(tier_ctx *ctx, const int32_t *seeds, int32_t n_seeds,
+                          const int32_t *fanouts /* host */, int32_t n_layers, uint64_t seed,
+                          tier_blocks *out);
+
+/* Tiered gather (Sec. 4.1, Listing 1).  out[i, :] = feature row of ids[i], read from
+ * the HBM cache when slot[ids[i]] >= 0 and from host memory otherwise; the result
+ * does not depend on the placement.  ids: (device) n ids, repeats allowed.
+ * out: (device) n * row_bytes bytes, 16-byte aligned.  stats (host, optional): row
+ * counts per tier; asking for them makes the call wait, otherwise asynchronous. */
+int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n, void *out,
+                         tier_gather_stats *stats);
+
+const char *tier_strerror(int status);
+/* hipError_t value of the last failing HIP call seen by this context (0 if none). */
+int tier_last_hip_error(const tier_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIER_H */

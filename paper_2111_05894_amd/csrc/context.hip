@@ -1,0 +1,218 @@
+// Context life cycle, pinned host memory, size bounds and error strings.
+#include <new>
+#include "rng.h"
+#include "tier_internal.h"
+
+namespace {
+
+// One pass over the graph at context creation: offsets non-decreasing and inside
+// [0, n_edges], neighbour ids inside [0, n_nodes).  The sampler indexes with
+// these values unchecked afterwards.
+template <typename OffT>
+__global__ void k_validate_csr(const OffT *__restrict__ indptr, const int32_t *__restrict__ indices,
+                               int64_t n_nodes, int64_t n_edges, int *__restrict__ bad)
+{
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int flag = 0;
+    for (int64_t v = t; v < n_nodes; v += stride) {
+        int64_t a = (int64_t)indptr[v], b = (int64_t)indptr[v + 1];
+        if (a < 0 || b < a || b > n_edges || b - a > 0x7fffffffLL) flag = 1;
+    }
+    if (t == 0 && (int64_t)indptr[0] != 0) flag = 1;
+    if (t == 0 && (int64_t)indptr[n_nodes] != n_edges) flag = 1;
+    for (int64_t e = t; e < n_edges; e += stride) {
+        uint32_t u = (uint32_t)indices[e];
+        if (u >= (uint64_t)n_nodes) flag = 1;
+    }
+    if (flag) atomicOr(bad, 1);
+}
+
+__global__ void k_fill_i32(int32_t *__restrict__ p, int64_t n, int32_t value)
+{
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = value;
+}
+
+__global__ void k_clear_error(int64_t *meta) { meta[META_ERROR] = 0; }
+
+int grid_for(int64_t n, int block, int cap)
+{
+    int64_t g = (n + block - 1) / block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+}  // namespace
+
+// Copy the bookkeeping array to the host and wait; a pending id error is
+// reported once and cleared.
+int tier_sync_meta(tier_ctx *c)
+{
+    TIER_HIP(c, hipMemcpyAsync(c->meta_host, c->meta, META_WORDS * sizeof(int64_t), hipMemcpyDeviceToHost, c->stream));
+    TIER_HIP(c, hipStreamSynchronize(c->stream));
+    if (c->meta_host[META_ERROR] != 0) {
+        k_clear_error<<<1, 1, 0, c->stream>>>(c->meta);
+        return TIER_EINVAL;
+    }
+    return TIER_OK;
+}
+
+extern "C" {
+
+int tier_host_alloc(void **ptr, size_t bytes)
+{
+    if (!ptr) return TIER_EINVAL;
+    *ptr = nullptr;
+    if (bytes == 0) return TIER_OK;
+    hipError_t e = hipHostMalloc(ptr, bytes, hipHostMallocMapped | hipHostMallocPortable);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        *ptr = nullptr;
+        return e == hipErrorOutOfMemory ? TIER_ENOMEM : TIER_EHIP;
+    }
+    return TIER_OK;
+}
+
+int tier_host_free(void *ptr)
+{
+    if (!ptr) return TIER_OK;
+    hipError_t e = hipHostFree(ptr);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return TIER_EHIP;
+    }
+    return TIER_OK;
+}
+
+int tier_blocks_bounds(int64_t n_graph_nodes, int64_t n_seeds, const int32_t *fanouts, int32_t n_layers,
+                       int64_t *cap_nodes, int64_t *cap_edges)
+{
+    if (!fanouts || !cap_nodes || !cap_edges || n_graph_nodes < 0 || n_seeds < 0) return TIER_EINVAL;
+    if (n_layers < 1 || n_layers > TIER_MAX_LAYERS) return TIER_EINVAL;
+    int64_t n = n_seeds < n_graph_nodes ? n_seeds : n_graph_nodes;
+    cap_nodes[0] = n;
+    for (int l = 0; l < n_layers; ++l) {
+        int64_t k = fanouts[l];
+        if (k < 1 || k > TIER_MAX_FANOUT) return TIER_EINVAL;
+        cap_edges[l] = n * k;
+        if (cap_edges[l] > 0x7fffffffLL) return TIER_EINVAL;   // block offsets are int32
+        n = n * (1 + k);
+        if (n > n_graph_nodes) n = n_graph_nodes;
+        cap_nodes[l + 1] = n;
+    }
+    return TIER_OK;
+}
+
+uint64_t tier_batch_seed(uint64_t seed, uint32_t epoch, uint32_t batch)
+{
+    return tier::philox_r64((uint32_t)seed, (uint32_t)(seed >> 32), epoch, batch, 0u, tier::kTagBatch);
+}
+
+void tier_destroy(tier_ctx *ctx)
+{
+    if (!ctx) return;
+    (void)hipStreamSynchronize(ctx->stream);
+    (void)hipFree(ctx->local_idx);
+    (void)hipFree(ctx->bitmap);
+    (void)hipFree(ctx->slot);
+    (void)hipFree(ctx->cache);
+    (void)hipFree(ctx->meta);
+    (void)hipHostFree(ctx->meta_host);
+    (void)hipFree(ctx->partial_hop);
+    (void)hipFree(ctx->partial_bm);
+    (void)hipFree(ctx->src_tmp);
+    (void)hipFree(ctx->ps_nodes);
+    (void)hipGetLastError();
+    delete ctx;
+}
+
+static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
+{
+    TIER_HIP(c, hipGetDevice(&c->device));
+    // the feature table must be memory the GPU can read in place
+    hipPointerAttribute_t attr;
+    TIER_HIP(c, hipPointerGetAttributes(&attr, feat->host_rows));
+    if (attr.type != hipMemoryTypeHost && attr.type != hipMemoryTypeDevice &&
+        attr.type != hipMemoryTypeManaged)
+        return TIER_EINVAL;
+    void *dev_view = nullptr;
+    if (attr.type == hipMemoryTypeHost) {
+        TIER_HIP(c, hipHostGetDevicePointer(&dev_view, const_cast<void *>(feat->host_rows), 0));
+    } else {
+        dev_view = const_cast<void *>(feat->host_rows);
+    }
+    c->host_rows = (const uint8_t *)dev_view;
+    if (((uintptr_t)c->host_rows & 15u) != 0) return TIER_EINVAL;
+
+    const int64_t n = c->n_nodes;
+    c->n_words = (n + 31) / 32;
+    TIER_HIP(c, hipMalloc(&c->local_idx, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
+    TIER_HIP(c, hipMalloc(&c->bitmap, (size_t)(c->n_words > 0 ? c->n_words : 1) * sizeof(uint32_t)));
+    TIER_HIP(c, hipMalloc(&c->slot, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
+    TIER_HIP(c, hipMalloc(&c->meta, META_WORDS * sizeof(int64_t)));
+    TIER_HIP(c, hipHostMalloc((void **)&c->meta_host, META_WORDS * sizeof(int64_t), hipHostMallocDefault));
+    TIER_HIP(c, hipMalloc(&c->partial_hop, TIER_SCAN_BLOCKS * sizeof(int32_t)));
+    TIER_HIP(c, hipMalloc(&c->partial_bm, TIER_SCAN_BLOCKS * sizeof(int32_t)));
+    k_fill_i32<<<grid_for(n, 256, 4096), 256, 0, c->stream>>>(c->local_idx, n, -1);
+    k_fill_i32<<<grid_for(c->n_words, 256, 4096), 256, 0, c->stream>>>((int32_t *)c->bitmap, c->n_words, 0);
+    k_fill_i32<<<1, 64, 0, c->stream>>>((int32_t *)c->meta, META_WORDS * 2, 0);
+    TIER_HIP(c, hipGetLastError());
+
+    // validate the graph once
+    int *bad = (int *)&c->meta[META_ERROR];
+    int g = grid_for(c->n_edges > n ? c->n_edges : n, 256, 8192);
+    if (c->indptr_i64)
+        k_validate_csr<int64_t><<<g, 256, 0, c->stream>>>((const int64_t *)c->indptr, c->indices, n, c->n_edges, bad);
+    else
+        k_validate_csr<int32_t><<<g, 256, 0, c->stream>>>((const int32_t *)c->indptr, c->indices, n, c->n_edges, bad);
+    TIER_HIP(c, hipGetLastError());
+    TIER_HIP(c, hipMemcpyAsync(c->meta_host, c->meta, META_WORDS * sizeof(int64_t), hipMemcpyDeviceToHost, c->stream));
+    TIER_HIP(c, hipStreamSynchronize(c->stream));
+    if (c->meta_host[META_ERROR] != 0) return TIER_EINVAL;
+    return TIER_OK;
+}
+
+int tier_create(tier_ctx **out, const tier_csr *csr, const tier_feat *feat, void *stream)
+{
+    if (!out) return TIER_EINVAL;
+    *out = nullptr;
+    if (!csr || !feat || !csr->indptr || (!csr->indices && csr->n_edges > 0) || !feat->host_rows) return TIER_EINVAL;
+    if (csr->n_nodes < 0 || csr->n_nodes > 0x7fffffffLL || csr->n_edges < 0) return TIER_EINVAL;
+    if (!csr->indptr_is_i64 && csr->n_edges > 0x7fffffffLL) return TIER_EINVAL;
+    if (feat->row_bytes <= 0 || (feat->row_bytes & 15) != 0) return TIER_EINVAL;
+    tier_ctx *c = new (std::nothrow) tier_ctx();
+    if (!c) return TIER_ENOMEM;
+    c->stream = (hipStream_t)stream;
+    c->n_nodes = csr->n_nodes;
+    c->n_edges = csr->n_edges;
+    c->indptr = csr->indptr;
+    c->indptr_i64 = csr->indptr_is_i64 != 0;
+    c->indices = csr->indices;
+    c->row_bytes = feat->row_bytes;
+    int rc = create_impl(c, csr, feat);
+    if (rc != TIER_OK) {
+        tier_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return TIER_OK;
+}
+
+const char *tier_strerror(int status)
+{
+    switch (status) {
+    case TIER_OK: return "ok";
+    case TIER_EINVAL: return "invalid argument";
+    case TIER_ENOMEM: return "out of memory";
+    case TIER_EHIP: return "HIP call failed";
+    case TIER_ECAPACITY: return "output buffer smaller than the upper bound";
+    case TIER_ESTATE: return "call out of order";
+    default: return "unknown status";
+    }
+}
+
+int tier_last_hip_error(const tier_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+}  // extern "C"

@@ -1,0 +1,124 @@
+// Tiered feature gather (Sec. 4.1; Listing 1 without peer GPUs).
+//
+// For every requested id the row comes from the HBM cache when the node->slot
+// map places it there, and from pinned host memory (read in place over the
+// host link) otherwise.  A group of LPR lanes copies one row in 16-byte pieces,
+// so a row is read and written with full-width coalesced accesses; several rows
+// per group are in flight to cover the host link's latency.
+#include "tier_internal.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kRowsInFlight = 4;
+
+template <int LPR>
+__global__ __launch_bounds__(kBlock) void k_gather(const int32_t *__restrict__ ids, int64_t n,
+                                                   const int32_t *__restrict__ slot,
+                                                   const uint4 *__restrict__ cache,
+                                                   const uint4 *__restrict__ host,
+                                                   uint4 *__restrict__ out, int cpr, int64_t n_nodes,
+                                                   int64_t *__restrict__ meta, int count_hits)
+{
+    constexpr int kGroups = kBlock / LPR;
+    const int lane = threadIdx.x % LPR;
+    const int64_t group = (int64_t)blockIdx.x * kGroups + threadIdx.x / LPR;
+    const int64_t n_groups = (int64_t)gridDim.x * kGroups;
+    int hits = 0;
+    int bad = 0;
+
+    for (int64_t r0 = group * kRowsInFlight; r0 < n; r0 += n_groups * kRowsInFlight) {
+        const uint4 *src[kRowsInFlight];
+#pragma unroll
+        for (int j = 0; j < kRowsInFlight; ++j) {
+            int64_t r = r0 + j;
+            src[j] = nullptr;
+            if (r < n) {
+                int32_t id = ids[r];
+                if ((uint32_t)id >= (uint64_t)n_nodes) {
+                    bad = 1;                       // row of zeros, error reported by the host
+                } else {
+                    int32_t s = slot ? slot[id] : -1;
+                    if (s >= 0) {
+                        src[j] = cache + (int64_t)s * cpr;
+                        hits += (lane == 0);
+                    } else {
+                        src[j] = host + (int64_t)id * cpr;
+                    }
+                }
+            }
+        }
+        for (int c = lane; c < cpr; c += LPR) {
+            uint4 v[kRowsInFlight];
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j) {
+                v[j] = make_uint4(0, 0, 0, 0);
+                if (src[j]) v[j] = src[j][c];
+            }
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j)
+                if (r0 + j < n) out[(r0 + j) * cpr + c] = v[j];
+        }
+    }
+    if (bad) atomicOr((int *)&meta[META_ERROR], 1);
+    if (count_hits) {
+        // one atomic per wavefront
+        for (int off = 32; off > 0; off >>= 1) hits += __shfl_down(hits, off);
+        if ((threadIdx.x & 63) == 0 && hits) atomicAdd((unsigned long long *)&meta[META_HIT_ROWS], (unsigned long long)hits);
+    }
+}
+
+__global__ void k_clear_hits(int64_t *meta) { meta[META_HIT_ROWS] = 0; }
+
+}  // namespace
+
+int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, const int32_t *slot,
+                       const uint8_t *cache, void *out, bool count_hits)
+{
+    if (n <= 0) return TIER_OK;
+    const int cpr = (int)(ctx->row_bytes / 16);
+    int lpr = 8;
+    while (lpr < cpr && lpr < 64) lpr *= 2;
+    const int groups = kBlock / lpr;
+    int64_t blocks = (n + (int64_t)groups * kRowsInFlight - 1) / ((int64_t)groups * kRowsInFlight);
+    const int64_t max_blocks = 256 * 64;
+    if (blocks > max_blocks) blocks = max_blocks;
+    if (count_hits) k_clear_hits<<<1, 1, 0, ctx->stream>>>(ctx->meta);
+#define GATHER_CASE(L)                                                                              \
+    case L:                                                                                         \
+        k_gather<L><<<(int)blocks, kBlock, 0, ctx->stream>>>(ids, n, slot, (const uint4 *)cache,    \
+                                                              (const uint4 *)ctx->host_rows,        \
+                                                              (uint4 *)out, cpr, ctx->n_nodes,      \
+                                                              ctx->meta, count_hits ? 1 : 0);       \
+        break;
+    switch (lpr) {
+        GATHER_CASE(8)
+        GATHER_CASE(16)
+        GATHER_CASE(32)
+        GATHER_CASE(64)
+    }
+#undef GATHER_CASE
+    TIER_HIP(ctx, hipGetLastError());
+    return TIER_OK;
+}
+
+extern "C" int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n, void *out,
+                                    tier_gather_stats *stats)
+{
+    if (!ctx || n < 0 || (n > 0 && (!ids || !out))) return TIER_EINVAL;
+    if (((uintptr_t)out & 15u) != 0) return TIER_EINVAL;
+    if (!ctx->placed) return TIER_ESTATE;
+    int rc = tier_launch_gather(ctx, ids, n, ctx->slot, ctx->cache, out, stats != nullptr);
+    if (rc != TIER_OK) return rc;
+    if (stats) {
+        stats->hit_rows = 0;
+        stats->miss_rows = 0;
+        if (n > 0) {
+            rc = tier_sync_meta(ctx);
+            if (rc != TIER_OK) return rc;
+            stats->hit_rows = ctx->meta_host[META_HIT_ROWS];
+            stats->miss_rows = n - stats->hit_rows;
+        }
+    }
+    return TIER_OK;
+}

@@ -1,0 +1,71 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "tier.h"
+
+// Slots of the device-side bookkeeping array (int64 each).  Kernels read the
+// sizes of the current mini-batch from here, so a chain of launches needs no
+// host round trip.
+enum {
+    META_NFRONT = 0,                          // [0 .. TIER_MAX_LAYERS]   |frontier_l|
+    META_NEDGES = TIER_MAX_LAYERS + 1,        // [.. + TIER_MAX_LAYERS)   edges of block l
+    META_TOTAL_ROWS = META_NEDGES + TIER_MAX_LAYERS,
+    META_TOTAL_EDGES,
+    META_ERROR,                               // != 0: a kernel saw an id outside [0, n_nodes)
+    META_HIT_ROWS,
+    META_WORDS
+};
+
+#define TIER_SCAN_BLOCKS 1024                 // upper limit of blocks in a two-phase scan
+
+struct tier_ctx {
+    hipStream_t stream;
+    int device;
+    int last_hip;
+    // graph and features (referenced, caller-owned)
+    int64_t n_nodes, n_edges;
+    const void *indptr;
+    bool indptr_i64;
+    const int32_t *indices;
+    const uint8_t *host_rows;
+    int64_t row_bytes;
+    // per-node scratch
+    int32_t *local_idx;      // n_nodes; -1 = not in the current frontier
+    uint32_t *bitmap;        // ceil(n_nodes / 32) words; all zero between hops
+    int64_t n_words;
+    // placement
+    int32_t *slot;           // n_nodes
+    uint8_t *cache;          // n_hot * row_bytes
+    int64_t n_hot;
+    bool placed;
+    // sampler scratch
+    int64_t *meta;           // device, META_WORDS
+    int64_t *meta_host;      // pinned mirror
+    int32_t *partial_hop;    // TIER_SCAN_BLOCKS
+    int32_t *partial_bm;     // TIER_SCAN_BLOCKS
+    int32_t *src_tmp;        // sampled neighbour ids of the current hop
+    int64_t cap_src_tmp;
+    int32_t *ps_nodes;       // frontier buffer used by tier_presample
+    int64_t cap_ps_nodes;
+};
+
+#define TIER_HIP(ctx, call)                                              \
+    do {                                                                 \
+        hipError_t e_ = (call);                                          \
+        if (e_ != hipSuccess) {                                          \
+            if (ctx) (ctx)->last_hip = (int)e_;                          \
+            (void)hipGetLastError();                                     \
+            return e_ == hipErrorOutOfMemory ? TIER_ENOMEM : TIER_EHIP;  \
+        }                                                                \
+    } while (0)
+
+// gather.hip: row copy used by tier_gather_features and by the cache fill of tier_place.
+// slot == nullptr reads every row from host_rows.
+int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, const int32_t *slot,
+                       const uint8_t *cache, void *out, bool count_hits);
+
+// context.hip: copy the bookkeeping array into ctx->meta_host and wait for the
+// stream.  Returns TIER_EINVAL once (and clears the flag) when a kernel met an id
+// outside [0, n_nodes).
+int tier_sync_meta(tier_ctx *ctx);

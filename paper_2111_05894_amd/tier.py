@@ -1,0 +1,259 @@
+"""ctypes binding of the C-ABI library (``include/tier.h``), same names.
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch supplies device memory (tensors) and the stream.  There is no
+fallback: a missing library raises at load time.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+MAX_LAYERS = 8
+MAX_FANOUT = 64
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtier.so")
+_lib = None
+
+EXPORTS = (
+    "tier_host_alloc", "tier_host_free", "tier_blocks_bounds", "tier_create", "tier_destroy",
+    "tier_presample", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
+    "tier_gather_features", "tier_strerror", "tier_last_hip_error",
+)
+
+
+class TierError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {_load().tier_strerror(status).decode()} ({status})")
+
+
+class _Csr(C.Structure):
+    _fields_ = [("n_nodes", C.c_int64), ("n_edges", C.c_int64), ("indptr", C.c_void_p),
+                ("indptr_is_i64", C.c_int32), ("indices", C.c_void_p)]
+
+
+class _Feat(C.Structure):
+    _fields_ = [("host_rows", C.c_void_p), ("row_bytes", C.c_int64)]
+
+
+class _Blocks(C.Structure):
+    _fields_ = [("nodes", C.c_void_p), ("cap_nodes", C.c_int64),
+                ("row_ptr", C.c_void_p * MAX_LAYERS), ("col", C.c_void_p * MAX_LAYERS),
+                ("eid", C.c_void_p * MAX_LAYERS),
+                ("cap_dst", C.c_int64 * MAX_LAYERS), ("cap_edges", C.c_int64 * MAX_LAYERS),
+                ("n_nodes", C.c_int64 * (MAX_LAYERS + 1)), ("n_edges", C.c_int64 * MAX_LAYERS)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("hit_rows", C.c_int64), ("miss_rows", C.c_int64)]
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2111_05894_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        i64p = C.POINTER(C.c_int64); i32p = C.POINTER(C.c_int32)
+        lib.tier_host_alloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t]
+        lib.tier_host_free.argtypes = [C.c_void_p]
+        lib.tier_blocks_bounds.argtypes = [C.c_int64, C.c_int64, i32p, C.c_int32, i64p, i64p]
+        lib.tier_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(_Csr), C.POINTER(_Feat), C.c_void_p]
+        lib.tier_destroy.argtypes = [C.c_void_p]; lib.tier_destroy.restype = None
+        lib.tier_presample.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, i32p, C.c_int32, C.c_int32,
+                                       C.c_uint64, C.c_void_p, i64p, i64p]
+        lib.tier_batch_seed.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]; lib.tier_batch_seed.restype = C.c_uint64
+        lib.tier_place.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, i64p]
+        lib.tier_sample_minibatch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, i32p, C.c_int32, C.c_uint64,
+                                              C.POINTER(_Blocks)]
+        lib.tier_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(_Stats)]
+        lib.tier_strerror.argtypes = [C.c_int]; lib.tier_strerror.restype = C.c_char_p
+        lib.tier_last_hip_error.argtypes = [C.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise TierError(rc, what)
+
+
+def _fan(fanouts):
+    arr = (C.c_int32 * len(fanouts))(*[int(k) for k in fanouts])
+    return arr, len(fanouts)
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous {dtype} tensor on the GPU")
+    return C.c_void_p(t.data_ptr())
+
+
+# ------------------------------------------------------------------------------
+# pinned host memory
+# ------------------------------------------------------------------------------
+class HostTable:
+    """A (n_rows, dim) feature table in pinned, GPU-mapped host memory obtained
+    from tier_host_alloc; ``tensor`` is a CPU view of it."""
+
+    def __init__(self, n_rows: int, dim: int, dtype: torch.dtype):
+        self.nbytes = n_rows * dim * torch.empty((), dtype=dtype).element_size()
+        p = C.c_void_p()
+        _check(_load().tier_host_alloc(C.byref(p), self.nbytes), "tier_host_alloc")
+        self.ptr = p.value
+        buf = (C.c_uint8 * self.nbytes).from_address(self.ptr) if self.nbytes else bytearray()
+        self.tensor = torch.frombuffer(buf, dtype=dtype).view(n_rows, dim) if self.nbytes else torch.empty((n_rows, dim), dtype=dtype)
+
+    def free(self):
+        if self.ptr:
+            self.tensor = None
+            _check(_load().tier_host_free(C.c_void_p(self.ptr)), "tier_host_free")
+            self.ptr = None
+
+
+def tier_host_alloc(n_rows: int, dim: int, dtype: torch.dtype) -> HostTable:
+    return HostTable(n_rows, dim, dtype)
+
+
+def tier_host_free(table: HostTable):
+    table.free()
+
+
+# ------------------------------------------------------------------------------
+# context
+# ------------------------------------------------------------------------------
+class Context:
+    def __init__(self, handle, indptr, indices, feat, row_bytes, dim, dtype):
+        self.handle = handle
+        self._keep = (indptr, indices, feat)        # the library references these
+        self.n_nodes = indptr.numel() - 1
+        self.row_bytes = row_bytes
+        self.dim = dim
+        self.dtype = dtype
+
+    def close(self):
+        if self.handle:
+            _load().tier_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def tier_create(indptr: torch.Tensor, indices: torch.Tensor, feat, stream=None) -> Context:
+    """indptr (int32/int64) and indices (int32) on the GPU; feat: a pinned CPU tensor
+    (n_nodes, dim) or a HostTable."""
+    table = feat.tensor if isinstance(feat, HostTable) else feat
+    if indptr.dtype not in (torch.int32, torch.int64):
+        raise TypeError("indptr: int32 or int64")
+    if not isinstance(feat, HostTable) and not (table.is_pinned() or table.is_cuda):
+        raise TypeError("feat: pinned host memory (or device memory) required")
+    if table.dim() != 2 or not table.is_contiguous():
+        raise TypeError("feat: contiguous (n_nodes, dim)")
+    csr = _Csr(indptr.numel() - 1, indices.numel(), _dev(indptr, indptr.dtype, "indptr"),
+               1 if indptr.dtype == torch.int64 else 0, _dev(indices, torch.int32, "indices"))
+    row_bytes = table.shape[1] * table.element_size()
+    if table.shape[0] != csr.n_nodes:
+        raise ValueError("feat rows != graph nodes")
+    ft = _Feat(C.c_void_p(table.data_ptr()), row_bytes)
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    h = C.c_void_p()
+    _check(_load().tier_create(C.byref(h), C.byref(csr), C.byref(ft), C.c_void_p(stream)), "tier_create")
+    return Context(h, indptr, indices, feat, row_bytes, table.shape[1], table.dtype)
+
+
+def tier_destroy(ctx: Context):
+    ctx.close()
+
+
+def tier_blocks_bounds(n_graph_nodes: int, n_seeds: int, fanouts):
+    fan, L = _fan(fanouts)
+    cn = (C.c_int64 * (MAX_LAYERS + 1))(); ce = (C.c_int64 * MAX_LAYERS)()
+    _check(_load().tier_blocks_bounds(n_graph_nodes, n_seeds, fan, L, cn, ce), "tier_blocks_bounds")
+    return list(cn[: L + 1]), list(ce[:L])
+
+
+def tier_batch_seed(seed: int, epoch: int, batch: int) -> int:
+    return int(_load().tier_batch_seed(seed, epoch, batch))
+
+
+def tier_presample(ctx: Context, train_ids: torch.Tensor, batch_size: int, fanouts, epochs: int, seed: int,
+                   counts: torch.Tensor = None, want_totals: bool = False):
+    """Returns counts (uint32 values in an int32 tensor), or (counts, rows, edges)."""
+    fan, L = _fan(fanouts)
+    if counts is None:
+        counts = torch.empty(ctx.n_nodes, dtype=torch.int32, device=train_ids.device)
+    tr = C.c_int64(0); te = C.c_int64(0)
+    rc = _load().tier_presample(ctx.handle, _dev(train_ids, torch.int32, "train_ids"), train_ids.numel(),
+                                batch_size, fan, L, epochs, seed, _dev(counts, torch.int32, "counts"),
+                                C.byref(tr) if want_totals else None, C.byref(te) if want_totals else None)
+    _check(rc, "tier_presample")
+    return (counts, tr.value, te.value) if want_totals else counts
+
+
+def tier_place(ctx: Context, counts: torch.Tensor, budget_bytes: int, want_slot_map: bool = True):
+    slot = torch.empty(ctx.n_nodes, dtype=torch.int32, device=counts.device) if want_slot_map else None
+    n_hot = C.c_int64(0)
+    rc = _load().tier_place(ctx.handle, _dev(counts, torch.int32, "counts"), budget_bytes,
+                            _dev(slot, torch.int32, "slot_map") if want_slot_map else None, C.byref(n_hot))
+    _check(rc, "tier_place")
+    return slot, n_hot.value
+
+
+class Blocks:
+    """Device buffers of one mini-batch's blocks, sized to the upper bounds, plus
+    the sizes the last tier_sample_minibatch call wrote."""
+
+    def __init__(self, n_graph_nodes: int, n_seeds: int, fanouts, device):
+        self.fanouts = tuple(int(k) for k in fanouts)
+        L = len(self.fanouts)
+        cn, ce = tier_blocks_bounds(n_graph_nodes, n_seeds, self.fanouts)
+        self.cap_nodes, self.cap_edges = cn, ce
+        self.nodes = torch.empty(max(cn[L], 1), dtype=torch.int32, device=device)
+        self.row_ptr = [torch.empty(cn[l] + 1, dtype=torch.int32, device=device) for l in range(L)]
+        self.col = [torch.empty(max(ce[l], 1), dtype=torch.int32, device=device) for l in range(L)]
+        self.eid = [torch.empty(max(ce[l], 1), dtype=torch.int64, device=device) for l in range(L)]
+        self.n_nodes = [0] * (L + 1)
+        self.n_edges = [0] * L
+        s = _Blocks()
+        s.nodes = self.nodes.data_ptr(); s.cap_nodes = cn[L]
+        for l in range(L):
+            s.row_ptr[l] = self.row_ptr[l].data_ptr(); s.col[l] = self.col[l].data_ptr()
+            s.eid[l] = self.eid[l].data_ptr(); s.cap_dst[l] = cn[l]; s.cap_edges[l] = ce[l]
+        self._c = s
+
+    def frontier(self, l: int = None) -> torch.Tensor:
+        l = len(self.fanouts) if l is None else l
+        return self.nodes[: self.n_nodes[l]]
+
+
+def tier_sample_minibatch(ctx: Context, seeds: torch.Tensor, fanouts, seed: int, blocks: Blocks = None) -> Blocks:
+    if blocks is None:
+        blocks = Blocks(ctx.n_nodes, seeds.numel(), fanouts, seeds.device)
+    fan, L = _fan(fanouts)
+    rc = _load().tier_sample_minibatch(ctx.handle, _dev(seeds, torch.int32, "seeds"), seeds.numel(), fan, L, seed,
+                                       C.byref(blocks._c))
+    _check(rc, "tier_sample_minibatch")
+    blocks.n_nodes = list(blocks._c.n_nodes[: L + 1])
+    blocks.n_edges = list(blocks._c.n_edges[:L])
+    return blocks
+
+
+def tier_gather_features(ctx: Context, ids: torch.Tensor, out: torch.Tensor = None, want_stats: bool = False):
+    n = ids.numel()
+    if out is None:
+        out = torch.empty((n, ctx.dim), dtype=ctx.dtype, device=ids.device)
+    if not (out.is_cuda and out.is_contiguous() and out.numel() * out.element_size() >= n * ctx.row_bytes):
+        raise TypeError("out: contiguous device tensor of n * row_bytes bytes")
+    st = _Stats()
+    rc = _load().tier_gather_features(ctx.handle, _dev(ids, torch.int32, "ids"), n, C.c_void_p(out.data_ptr()),
+                                      C.byref(st) if want_stats else None)
+    _check(rc, "tier_gather_features")
+    return (out, st.hit_rows, st.miss_rows) if want_stats else out

@@ -1,0 +1,297 @@
+"""GPU-vs-oracle parity through the C-ABI library: bit-exact blocks, counts,
+slot map and gathered rows on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2111_05894_amd import synth, tier
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+class World:
+    """A graph, a pinned feature table and a library context, with numpy views
+    for the oracle."""
+
+    def __init__(self, indptr, indices, dim=32, dtype=torch.float32, feat_seed=3):
+        self.indptr_d = indptr.to(DEV); self.indices_d = indices.to(DEV)
+        self.indptr = indptr.cpu().numpy().astype(np.int64); self.indices = indices.cpu().numpy()
+        self.n = self.indptr.shape[0] - 1
+        self.feat = torch.empty((self.n, dim), dtype=dtype, pin_memory=True)
+        synth.fill_features(self.feat, "uniform", feat_seed, "cpu")
+        self.feat_bytes = self.feat.view(torch.uint8).numpy().reshape(self.n, -1)
+        self.row_bytes = self.feat_bytes.shape[1]
+        self.ctx = tier.tier_create(self.indptr_d, self.indices_d, self.feat)
+        self.local_idx = np.full(self.n, -1, np.int32)
+
+    def close(self):
+        self.ctx.close()
+
+
+def rmat_world(n, m, seed=2111, i64=True, **kw):
+    ip, ix = synth.rmat_csr(n, m, seed, "cpu", i64_offsets=i64)
+    return World(ip, ix, **kw)
+
+
+def compare_blocks(w: World, seeds_np, fanouts, seed, blocks=None):
+    seeds_d = torch.from_numpy(seeds_np).to(DEV)
+    got = tier.tier_sample_minibatch(w.ctx, seeds_d, fanouts, seed, blocks)
+    want = orc.sample_minibatch(w.indptr, w.indices, seeds_np, fanouts, seed, local_idx=w.local_idx)
+    L = len(fanouts)
+    assert got.n_nodes == want["n_nodes"].tolist(), (got.n_nodes, want["n_nodes"])
+    assert got.n_edges == want["n_edges"].tolist()
+    assert np.array_equal(got.frontier().cpu().numpy(), want["nodes"])
+    for l in range(L):
+        nd, ne = got.n_nodes[l], got.n_edges[l]
+        assert np.array_equal(got.row_ptr[l][: nd + 1].cpu().numpy(), want["row_ptr"][l]), f"row_ptr layer {l}"
+        assert np.array_equal(got.eid[l][:ne].cpu().numpy(), want["eid"][l]), f"eid layer {l}"
+        assert np.array_equal(got.col[l][:ne].cpu().numpy(), want["col"][l]), f"col layer {l}"
+    return got, want
+
+
+@pytest.fixture(scope="module")
+def small():
+    w = rmat_world(5000, 60_000, dim=32)
+    yield w
+    w.close()
+
+
+@pytest.fixture(scope="module")
+def small_i32():
+    w = rmat_world(3001, 40_000, seed=77, i64=False, dim=100)      # 400-byte rows, ragged sizes
+    yield w
+    w.close()
+
+
+# ------------------------------------------------------------------------------
+# sampling
+# ------------------------------------------------------------------------------
+@pytest.mark.parametrize("fanouts", [(3,), (4, 2), (5, 5), (10, 5), (15, 10, 5), (25, 15), (33, 2), (64, 1), (2, 2, 2, 2, 2)])
+def test_blocks_match_oracle(small, fanouts):
+    say("blocks", fanouts)
+    rng = np.random.default_rng(len(fanouts) * 100 + fanouts[0])
+    for n_seeds in (1, 63, 257, 1024):
+        seeds = rng.choice(small.n, n_seeds, replace=False).astype(np.int32)
+        compare_blocks(small, seeds, fanouts, 1000 + n_seeds)
+
+
+def test_blocks_match_oracle_int32_offsets(small_i32):
+    rng = np.random.default_rng(5)
+    for fanouts in ((10, 5), (7, 3, 2)):
+        seeds = rng.choice(small_i32.n, 300, replace=False).astype(np.int32)
+        compare_blocks(small_i32, seeds, fanouts, 99)
+
+
+def test_blocks_reuse_buffers_and_are_reproducible(small):
+    rng = np.random.default_rng(9)
+    blocks = tier.Blocks(small.n, 512, (10, 5), DEV)
+    first = None
+    for rep in range(3):
+        seeds = rng.choice(small.n, 512, replace=False).astype(np.int32) if rep < 2 else first
+        if rep == 0:
+            first = seeds
+        got, _ = compare_blocks(small, seeds, (10, 5), 4242, blocks)
+        if rep == 0:
+            keep = [t.clone() for t in got.eid]
+        if rep == 2:
+            assert all(torch.equal(a[: got.n_edges[l]], b[: got.n_edges[l]]) for l, (a, b) in enumerate(zip(keep, got.eid)))
+
+
+def test_blocks_edge_cases(small):
+    got = tier.tier_sample_minibatch(small.ctx, torch.zeros(0, dtype=torch.int32, device=DEV), (3, 2), 1)
+    assert got.n_nodes == [0, 0, 0] and got.n_edges == [0, 0]
+    iso = np.flatnonzero(np.diff(small.indptr) == 0)[:5].astype(np.int32)   # no neighbours at all
+    got, _ = compare_blocks(small, iso, (4, 4), 8)
+    assert got.n_nodes == [5, 5, 5] and got.n_edges == [0, 0]
+    hub = np.array([int(np.argmax(np.diff(small.indptr)))], np.int32)        # the largest degree
+    compare_blocks(small, hub, (64, 64), 8)
+    compare_blocks(small, np.arange(small.n, dtype=np.int32), (2,), 8)        # every node is a seed
+
+
+def test_blocks_bad_arguments(small):
+    seeds = torch.arange(10, dtype=torch.int32, device=DEV)
+    with pytest.raises(tier.TierError):
+        tier.tier_sample_minibatch(small.ctx, seeds, (65,), 1)
+    with pytest.raises(tier.TierError):
+        tier.tier_sample_minibatch(small.ctx, seeds, (3,) * 9, 1)
+    tiny = tier.Blocks(small.n, 5, (3,), DEV)
+    with pytest.raises(tier.TierError) as e:
+        tier.tier_sample_minibatch(small.ctx, seeds, (3,), 1, tiny)
+    assert e.value.status == -4
+    bad = torch.tensor([1, small.n], dtype=torch.int32, device=DEV)           # id out of range: reported, no fault
+    with pytest.raises(tier.TierError):
+        tier.tier_sample_minibatch(small.ctx, bad, (3,), 1)
+    compare_blocks(small, np.arange(10, dtype=np.int32), (3,), 1)             # context still good
+
+
+def test_blocks_large_frontier_spans_many_tiles():
+    """Frontier above 1024 blocks x 256 nodes, so blocks walk several tiles."""
+    say("large frontier")
+    ip, ix = synth.erdos_renyi_csr(1_500_000, 30_000_000, 5, DEV)
+    w = World(ip, ix, dim=4)
+    try:
+        rng = np.random.default_rng(1)
+        seeds = rng.choice(w.n, 8192, replace=False).astype(np.int32)
+        got, _ = compare_blocks(w, seeds, (12, 8, 3), 31337)
+        say("frontier sizes", got.n_nodes, "edges", got.n_edges)
+        assert got.n_nodes[2] > 1024 * 256
+    finally:
+        w.close()
+
+
+# ------------------------------------------------------------------------------
+# access counts
+# ------------------------------------------------------------------------------
+@pytest.mark.parametrize("fanouts,batch,epochs", [((10, 5), 100, 1), ((4, 3, 2), 64, 2), ((15,), 333, 1)])
+def test_counts_match_oracle(small, fanouts, batch, epochs):
+    train = synth.train_set(small.n, 0.2, 11).numpy()
+    want, wrows, wedges = orc.presample(small.indptr, small.indices, train, batch, fanouts, epochs, 5894, threads=4)
+    got, rows, edges = tier.tier_presample(small.ctx, torch.from_numpy(train).to(DEV), batch, fanouts, epochs, 5894,
+                                           want_totals=True)
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want)
+    assert rows == wrows == int(want.sum()) and edges == wedges
+    # sampler state is clean afterwards: a mini-batch still matches
+    compare_blocks(small, train[:50], fanouts, 1)
+
+
+def test_counts_empty_training_set(small):
+    got, rows, edges = tier.tier_presample(small.ctx, torch.zeros(0, dtype=torch.int32, device=DEV), 8, (3,), 1, 1,
+                                           want_totals=True)
+    assert int(got.sum()) == 0 and rows == 0 and edges == 0
+
+
+# ------------------------------------------------------------------------------
+# placement and gather
+# ------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,max_count", [(1, 3), (64, 0), (1000, 1), (4097, 200), (100_003, 300), (250_000, 70_000),
+                                         (70_001, 2**24 + 5)])
+def test_slot_map_matches_oracle(n, max_count):
+    say("place", n, max_count)
+    rng = np.random.default_rng(n)
+    counts = (rng.integers(0, max_count + 1, n) * (rng.random(n) < 0.6)).astype(np.uint32)   # ties and zeros
+    if max_count:
+        counts[rng.integers(0, n)] = max_count
+    ip = torch.zeros(n + 1, dtype=torch.int64); ix = torch.zeros(0, dtype=torch.int32)
+    w = World(ip, ix, dim=4)
+    try:
+        cd = torch.from_numpy(counts.view(np.int32)).to(DEV)
+        for rows in (0, 1, n // 3, n, n + 10):
+            budget = rows * w.row_bytes + 7
+            slot, n_hot = tier.tier_place(w.ctx, cd, budget)
+            rank, want, want_hot = orc.place(counts, w.row_bytes, budget)
+            assert n_hot == want_hot == min(rows, n)
+            assert np.array_equal(slot.cpu().numpy(), want)
+    finally:
+        w.close()
+
+
+def test_rank_example_from_paper():
+    ip = torch.zeros(5, dtype=torch.int64); ix = torch.zeros(0, dtype=torch.int32)
+    w = World(ip, ix, dim=4)
+    try:
+        cd = torch.tensor([1, 4, 2, 3], dtype=torch.int32, device=DEV)
+        slot, n_hot = tier.tier_place(w.ctx, cd, 4 * w.row_bytes)
+        assert slot.tolist() == [3, 0, 2, 1] and n_hot == 4          # Sec. 3.2 worked example
+    finally:
+        w.close()
+
+
+@pytest.mark.parametrize("dim,dtype", [(4, torch.float32), (100, torch.float32), (128, torch.float32),
+                                       (256, torch.float32), (768, torch.float16), (8, torch.float16), (1000, torch.float32)])
+def test_gather_matches_oracle(dim, dtype):
+    say("gather", dim, dtype)
+    n = 20_011
+    ip = torch.zeros(n + 1, dtype=torch.int64); ix = torch.zeros(0, dtype=torch.int32)
+    w = World(ip, ix, dim=dim, dtype=dtype)
+    try:
+        rng = np.random.default_rng(dim)
+        counts = rng.integers(0, 40, n).astype(np.uint32)
+        cd = torch.from_numpy(counts.view(np.int32)).to(DEV)
+        with pytest.raises(tier.TierError) as e:                     # gather before place
+            tier.tier_gather_features(w.ctx, torch.zeros(1, dtype=torch.int32, device=DEV))
+        assert e.value.status == -5
+        for frac in (0.0, 0.1, 0.5, 1.0):
+            budget = int(frac * n) * w.row_bytes
+            slot, n_hot = tier.tier_place(w.ctx, cd, budget)
+            rank, oslot, _ = orc.place(counts, w.row_bytes, budget)
+            cache = orc.fill_cache(w.feat_bytes, oslot, n_hot)
+            for m in (0, 1, 5, 1023, 30_001):
+                ids = rng.integers(0, n, m).astype(np.int32)         # repeats allowed
+                want, whit, wmiss = orc.gather(w.feat_bytes, cache, oslot, ids)
+                out, hit, miss = tier.tier_gather_features(w.ctx, torch.from_numpy(ids).to(DEV), want_stats=True)
+                assert (hit, miss) == (whit, wmiss)
+                got = out.view(torch.uint8).cpu().numpy().reshape(m, w.row_bytes)
+                assert np.array_equal(got, want)
+                assert np.array_equal(got, w.feat_bytes[ids])        # transparent to the model
+        bad = torch.tensor([0, n, 3], dtype=torch.int32, device=DEV)
+        with pytest.raises(tier.TierError):
+            tier.tier_gather_features(w.ctx, bad, want_stats=True)
+    finally:
+        w.close()
+
+
+def test_hot_rows_come_from_the_cache():
+    """After placement, change the host copy of the hot rows: the gather must still
+    return the original bytes for them (read from HBM) and the new bytes for cold rows."""
+    n, dim = 5000, 32
+    ip = torch.zeros(n + 1, dtype=torch.int64); ix = torch.zeros(0, dtype=torch.int32)
+    w = World(ip, ix, dim=dim)
+    try:
+        counts = np.arange(n, dtype=np.uint32)[::-1].copy()          # node 0 hottest
+        slot, n_hot = tier.tier_place(w.ctx, torch.from_numpy(counts.view(np.int32)).to(DEV), 1000 * w.row_bytes)
+        orig = w.feat.clone()
+        w.feat += 1.0                                                # host copy changes after placement
+        ids = torch.arange(n, dtype=torch.int32, device=DEV)
+        out = tier.tier_gather_features(w.ctx, ids).cpu()
+        assert torch.equal(out[:1000], orig[:1000]) and torch.equal(out[1000:], w.feat[1000:])
+    finally:
+        w.close()
+
+
+# ------------------------------------------------------------------------------
+# the whole path on the smallest benchmark configuration, full size
+# ------------------------------------------------------------------------------
+def test_whole_path_cfg1_full_size():
+    wl = synth.WORKLOADS["cfg1"]
+    say("cfg1: graph")
+    ip, ix, train = synth.make_graph(wl, "cpu")
+    w = World(ip, ix, dim=wl.dim)
+    try:
+        train_np = train.numpy()
+        say("cfg1: presample")
+        want_counts, wrows, wedges = orc.presample(w.indptr, w.indices, train_np, wl.batch_size, wl.fanouts, 1,
+                                                   synth.PRESAMPLE_SEED, threads=8)
+        counts, rows, edges = tier.tier_presample(w.ctx, train.to(DEV), wl.batch_size, wl.fanouts, 1,
+                                                  synth.PRESAMPLE_SEED, want_totals=True)
+        assert np.array_equal(counts.cpu().numpy().view(np.uint32), want_counts) and (rows, edges) == (wrows, wedges)
+        say("cfg1: place")
+        budget = wl.budget_bytes()
+        slot, n_hot = tier.tier_place(w.ctx, counts, budget)
+        rank, oslot, ohot = orc.place(want_counts, w.row_bytes, budget)
+        assert n_hot == ohot == 13107 and np.array_equal(slot.cpu().numpy(), oslot)
+        cache = orc.fill_cache(w.feat_bytes, oslot, ohot)
+        say("cfg1: epoch")
+        order = synth.random_order(train.numel(), synth.EPOCH_SEED, 1, "cpu").numpy()
+        epoch_ids = train_np[order]
+        blocks = tier.Blocks(w.n, wl.batch_size, wl.fanouts, DEV)
+        n_batches = -(-len(epoch_ids) // wl.batch_size)
+        assert n_batches == 13
+        hits = 0; total = 0
+        for b in range(n_batches):
+            seeds = epoch_ids[b * wl.batch_size:(b + 1) * wl.batch_size]
+            bseed = tier.tier_batch_seed(synth.EPOCH_SEED, 0, b)
+            got, want = compare_blocks(w, seeds, wl.fanouts, bseed, blocks)
+            out, hit, miss = tier.tier_gather_features(w.ctx, got.frontier(), want_stats=True)
+            wout, whit, wmiss = orc.gather(w.feat_bytes, cache, oslot, want["nodes"])
+            assert (hit, miss) == (whit, wmiss)
+            assert np.array_equal(out.view(torch.uint8).cpu().numpy().reshape(len(want["nodes"]), -1), wout)
+            hits += hit; total += hit + miss
+        say(f"cfg1: hit fraction {hits / total:.3f} over {total} rows")
+    finally:
+        w.close()
