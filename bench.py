@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the data-tiering hot path on one MI355X.
+
+One *step* is one pass of the whole path over one synthetic workload: a
+presampling epoch (access counts), placement under the HBM budget, then one
+measured epoch of mini-batches, each sampled (tier_sample_minibatch) and then
+gathered (tier_gather_features).  The measured epoch uses another seed and
+another order of the training nodes than the presampling epoch.
+
+Prints ONE JSON line.  ``value`` is gathered feature bytes per second of step
+wall time (everything above included); the per-kernel figures, the roofline of
+the dominant kernel (the tiered gather, timed per launch with events on its
+stream) and a CPU baseline (the tests' oracle on the host cores, on a bounded
+sample of the same workload) ride along.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+LINK_PEAK_GBPS = 64.0           # PCIe Gen5 x16, one direction, nominal
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--budget", type=float, default=None, help="override: fraction of feature bytes kept in HBM")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-batches", type=int, default=192, help="mini-batches in the CPU baseline's sample")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2111_05894_amd import synth, tier
+
+    tier._load()                                   # fail loudly when the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = synth.WORKLOADS[args.workload]
+    t0 = time.time()
+    indptr, indices, train = synth.make_graph(wl, dev)
+    torch.cuda.synchronize()
+    n = indptr.numel() - 1
+    log(f"[bench] {wl.name}: {n} nodes, {indices.numel()} edges, {train.numel()} train nodes "
+        f"({time.time() - t0:.1f}s to generate)")
+    dtype = torch.float32 if wl.dtype == "float32" else torch.float16
+    table = tier.tier_host_alloc(n, wl.dim, dtype)
+    synth.fill_features(table.tensor, wl.dist, synth.GRAPH_SEED + 2, dev)
+    torch.cuda.synchronize()
+    log(f"[bench] features: {table.nbytes / 1e9:.2f} GB pinned ({time.time() - t0:.1f}s)")
+
+    ctx = tier.tier_create(indptr, indices, table)
+    R = ctx.row_bytes
+    budget = wl.budget_bytes(args.budget)
+    n_train = train.numel()
+    bs = wl.batch_size
+    n_batches = -(-n_train // bs)
+    order = synth.random_order(n_train, synth.EPOCH_SEED, 1, dev)
+    epoch_ids = train[order].contiguous()
+    seeds_of = [epoch_ids[b * bs:(b + 1) * bs] for b in range(n_batches)]
+    bseed = [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in range(n_batches)]
+    blocks = tier.Blocks(n, bs, wl.fanouts, dev)
+    out = torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=dev)
+    counts = torch.empty(n, dtype=torch.int32, device=dev)
+    L = len(wl.fanouts)
+
+    def step(record):
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        e_begin, e_pre, e_place = ev(), ev(), ev()
+        e_begin.record()
+        tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
+        e_pre.record()
+        _, n_hot = tier.tier_place(ctx, counts, budget, want_slot_map=False)
+        e_place.record()
+        rows = edges = 0
+        pairs = []
+        for b in range(n_batches):
+            s0, s1, g1 = ev(), ev(), ev()
+            s0.record()
+            blk = tier.tier_sample_minibatch(ctx, seeds_of[b], wl.fanouts, bseed[b], blocks)
+            s1.record()
+            tier.tier_gather_features(ctx, blk.frontier(), out)
+            g1.record()
+            rows += blk.n_nodes[L]; edges += sum(blk.n_edges)
+            pairs.append((s0, s1, g1, blk.n_nodes[L]))
+        torch.cuda.synchronize()
+        if record is not None:
+            record["presample_ms"].append(e_begin.elapsed_time(e_pre))
+            record["place_ms"].append(e_pre.elapsed_time(e_place))
+            record["sample_ms"].append(sum(a.elapsed_time(b_) for a, b_, _, _ in pairs))
+            record["gather_ms"].append(sum(b_.elapsed_time(c) for _, b_, c, _ in pairs))
+            record["rows"] = rows; record["edges"] = edges; record["n_hot"] = n_hot
+            record["gather_launches"] = len(pairs)
+        return rows, edges
+
+    for _ in range(args.warmup):
+        step(None)
+    rec = {"presample_ms": [], "place_ms": [], "sample_ms": [], "gather_ms": []}
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        step(rec)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+    ms_per_step = wall * 1e3 / max(args.steps, 1)
+
+    # hit / miss rows of the measured epoch (outside the timed region: asking for them waits per batch)
+    hit_rows = 0
+    for b in range(n_batches):
+        blk = tier.tier_sample_minibatch(ctx, seeds_of[b], wl.fanouts, bseed[b], blocks)
+        _, h, m = tier.tier_gather_features(ctx, blk.frontier(), out, want_stats=True)
+        hit_rows += h
+    rows, edges = rec["rows"], rec["edges"]
+    h = hit_rows / rows if rows else 0.0
+    mean = lambda xs: sum(xs) / len(xs) if xs else 0.0
+    gather_ms, sample_ms = mean(rec["gather_ms"]), mean(rec["sample_ms"])
+    gathered_bytes = rows * R
+    value = gathered_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: the gather.  Algorithmic bytes per row: the row read once (HBM or
+    # host link) and written once (HBM), plus the 4-byte id and the 4-byte slot lookup.
+    alg_bytes_row = 2 * R + 8
+    launches = rec["gather_launches"]
+    avg_launch_ms = gather_ms / launches if launches else 0.0
+    alg_per_launch = alg_bytes_row * rows / launches if launches else 0.0
+    achieved = alg_per_launch / (avg_launch_ms * 1e-3) / 1e9 if avg_launch_ms else 0.0
+    hbm_b = (1 + h) * R + 8            # per row through HBM
+    link_b = (1 - h) * R               # per row over the host link
+    peak_time_additive = alg_bytes_row / (hbm_b / HBM_PEAK_GBPS + link_b / LINK_PEAK_GBPS)
+    peak_arithmetic = h * HBM_PEAK_GBPS + (1 - h) * LINK_PEAK_GBPS
+    roofline = {
+        "bound": "hbm", "kernel": "k_gather", "achieved": round(achieved, 2),
+        "peak": round(peak_time_additive, 2), "unit": "GB/s",
+        "frac": round(achieved / peak_time_additive, 4) if peak_time_additive else None,
+        "traffic": None,
+        "peak_model": "time-additive blend: (2R+8) / (((1+h)R+8)/HBM + (1-h)R/link), HBM 8000 GB/s, host link 64 GB/s",
+        "hit_fraction": round(h, 4),
+        "avg_launch_ms": round(avg_launch_ms, 4), "launches_per_step": launches,
+        "alg_bytes_per_launch": round(alg_per_launch),
+        "feature_read_GBps": round(gathered_bytes / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
+        "host_link_GBps": round((rows - hit_rows) * R / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
+        "arithmetic_blend_peak": round(peak_arithmetic, 1),
+        "arithmetic_blend_frac": round(gathered_bytes / (gather_ms * 1e-3) / 1e9 / peak_arithmetic, 4) if gather_ms else None,
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(args, wl, indptr, indices, train, epoch_ids, table, budget, bseed)
+
+    result = {
+        "metric": "gathered feature GB/s (whole pass: presample + place + sampled and gathered epoch)",
+        "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.graph} graph, {n} nodes, {indices.numel()} edges, "
+                               f"{wl.dim} x {wl.dtype} features, fanout {list(wl.fanouts)}, batch {bs}, "
+                               f"{n_batches} mini-batches per epoch, HBM budget {budget} B ({rec['n_hot']} rows)"},
+        "sampled_edges_per_s": round(edges / (sample_ms * 1e-3)) if sample_ms else None,
+        "gather_GBps": round(gathered_bytes / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
+        "rows_per_epoch": rows, "edges_per_epoch": edges, "hit_fraction": round(h, 4),
+        "host_link_bytes_tiered": (rows - hit_rows) * R, "host_link_bytes_untiered": rows * R,
+        "host_link_reduction": round(h, 4),
+        "phase_ms": {"presample": round(mean(rec["presample_ms"]), 3), "place": round(mean(rec["place_ms"]), 3),
+                     "sample": round(sample_ms, 3), "gather": round(gather_ms, 3)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(result), flush=True)
+    ctx.close()
+
+
+def cpu_baseline(args, wl, indptr, indices, train, epoch_ids, table, budget, bseed):
+    """The oracle as it stands, on the host cores, on the first few mini-batches of
+    the same workload: their presampling share, the placement (all nodes), then
+    sampling and gathering them.  Threads run whole mini-batches side by side."""
+    import numpy as np
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import oracle as orc
+
+    cores = len(os.sched_getaffinity(0))
+    nb = max(1, args.cpu_batches)
+    bs = wl.batch_size
+    ip = indptr.cpu().numpy().astype(np.int64); ix = indices.cpu().numpy()
+    tr = train.cpu().numpy(); ep = epoch_ids.cpu().numpy()
+    n = ip.shape[0] - 1
+    feat = table.tensor.view(-1).view(torch.uint8).numpy().reshape(n, -1)
+    R = feat.shape[1]
+    nb = min(nb, -(-len(tr) // bs))
+    threads = min(cores, nb)
+    t0 = time.perf_counter()
+    counts, _, _ = orc.presample(ip, ix, tr[: nb * bs], bs, wl.fanouts, 1, synth_seed("pre"), threads=threads)
+    _, slot, n_hot = orc.place(counts, R, budget)
+    cache = orc.fill_cache(feat, slot, n_hot)
+
+    def one(b):
+        blk = orc.sample_minibatch(ip, ix, ep[b * bs:(b + 1) * bs], wl.fanouts, bseed[b])
+        rows, _, _ = orc.gather(feat, cache, slot, blk["nodes"])
+        return rows.shape[0]
+
+    with ThreadPoolExecutor(threads) as ex:
+        rows = sum(ex.map(one, range(nb)))
+    dt = time.perf_counter() - t0
+    return {"value": round(rows * R / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {nb} of the mini-batches: presample of {nb} batches, placement of all {n} nodes, "
+                      f"then sample + gather of {nb} batches; {dt:.1f} s wall on {threads} threads",
+            "seconds": round(dt, 2)}
+
+
+def synth_seed(which):
+    from paper_2111_05894_amd import synth
+    return synth.PRESAMPLE_SEED if which == "pre" else synth.EPOCH_SEED
+
+
+if __name__ == "__main__":
+    main()

@@ -12,7 +12,9 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kRowsInFlight = 4;
 
-template <int LPR>
+// TIERED = false is the untiered copy (every row from host memory) that fills the
+// HBM cache at placement time.
+template <int LPR, bool TIERED>
 __global__ __launch_bounds__(kBlock) void k_gather(const int32_t *__restrict__ ids, int64_t n,
                                                    const int32_t *__restrict__ slot,
                                                    const uint4 *__restrict__ cache,
@@ -38,7 +40,7 @@ __global__ __launch_bounds__(kBlock) void k_gather(const int32_t *__restrict__ i
                 if ((uint32_t)id >= (uint64_t)n_nodes) {
                     bad = 1;                       // row of zeros, error reported by the host
                 } else {
-                    int32_t s = slot ? slot[id] : -1;
+                    int32_t s = TIERED ? slot[id] : -1;
                     if (s >= 0) {
                         src[j] = cache + (int64_t)s * cpr;
                         hits += (lane == 0);
@@ -86,10 +88,14 @@ int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, const int32
     if (count_hits) k_clear_hits<<<1, 1, 0, ctx->stream>>>(ctx->meta);
 #define GATHER_CASE(L)                                                                              \
     case L:                                                                                         \
-        k_gather<L><<<(int)blocks, kBlock, 0, ctx->stream>>>(ids, n, slot, (const uint4 *)cache,    \
-                                                              (const uint4 *)ctx->host_rows,        \
-                                                              (uint4 *)out, cpr, ctx->n_nodes,      \
-                                                              ctx->meta, count_hits ? 1 : 0);       \
+        if (slot)                                                                                   \
+            k_gather<L, true><<<(int)blocks, kBlock, 0, ctx->stream>>>(                             \
+                ids, n, slot, (const uint4 *)cache, (const uint4 *)ctx->host_rows, (uint4 *)out,    \
+                cpr, ctx->n_nodes, ctx->meta, count_hits ? 1 : 0);                                  \
+        else                                                                                        \
+            k_gather<L, false><<<(int)blocks, kBlock, 0, ctx->stream>>>(                            \
+                ids, n, nullptr, nullptr, (const uint4 *)ctx->host_rows, (uint4 *)out, cpr,         \
+                ctx->n_nodes, ctx->meta, 0);                                                        \
         break;
     switch (lpr) {
         GATHER_CASE(8)
