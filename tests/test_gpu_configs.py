@@ -1,0 +1,138 @@
+"""Parity at the benchmark configurations' full sizes, in the launch configuration
+bench.py times: access counts and slot map compared in full, then a sample of the
+measured epoch's mini-batches compared element by element (blocks and gathered rows)."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2111_05894_amd import synth, tier
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def run_config(name, check_batches, budget_fraction=None, host_threads=16, fallback_scale=None):
+    wl = synth.WORKLOADS[name]
+    t0 = time.time()
+    dtype = torch.float32 if wl.dtype == "float32" else torch.float16
+    scale = 1.0
+    try:
+        table = tier.tier_host_alloc(wl.n_nodes, wl.dim, dtype)
+    except tier.TierError as e:
+        # this pool pins at most ~64 GiB of host memory per process: shrink nodes, edges
+        # and budget alike, keep row size, fanouts and batch size
+        if fallback_scale is None:
+            raise
+        scale = fallback_scale
+        say(f"{name}: {wl.feature_bytes / 2**30:.1f} GiB of pinned host memory refused ({e}); running at scale {scale}")
+        table = tier.tier_host_alloc(int(wl.n_nodes * scale), wl.dim, dtype)
+    try:
+        indptr, indices, train = synth.make_graph(wl, DEV, scale)
+        torch.cuda.synchronize()
+        n = indptr.numel() - 1
+        say(f"{name}: graph {n} nodes {indices.numel()} edges ({time.time() - t0:.0f}s)")
+        synth.fill_features(table.tensor, wl.dist, synth.GRAPH_SEED + 2, DEV)
+        torch.cuda.synchronize()
+        say(f"{name}: features {table.nbytes / 1e9:.1f} GB ({time.time() - t0:.0f}s)")
+        ip = indptr.cpu().numpy().astype(np.int64); ix = indices.cpu().numpy(); tr = train.cpu().numpy()
+        feat = table.tensor.view(-1).view(torch.uint8).numpy().reshape(n, -1)
+        ctx = tier.tier_create(indptr, indices, table)
+        bs, fan, R = wl.batch_size, wl.fanouts, wl.row_bytes
+
+        # access counts, in full
+        t1 = time.time()
+        counts, rows, edges = tier.tier_presample(ctx, train, bs, fan, 1, synth.PRESAMPLE_SEED, want_totals=True)
+        t2 = time.time()
+        want_counts, wrows, wedges = orc.presample(ip, ix, tr, bs, fan, 1, synth.PRESAMPLE_SEED, threads=host_threads)
+        say(f"{name}: presample gpu {t2 - t1:.2f}s oracle {time.time() - t2:.1f}s rows {rows} edges {edges}")
+        assert (rows, edges) == (wrows, wedges)
+        assert np.array_equal(counts.cpu().numpy().view(np.uint32), want_counts)
+
+        # placement, in full
+        budget = int(wl.budget_bytes(budget_fraction) * scale)
+        slot, n_hot = tier.tier_place(ctx, counts, budget)
+        _, oslot, ohot = orc.place(want_counts, R, budget)
+        assert n_hot == ohot == min(n, budget // R)
+        assert np.array_equal(slot.cpu().numpy(), oslot)
+        say(f"{name}: placement of {n_hot} rows matches ({time.time() - t0:.0f}s)")
+
+        # measured epoch: some mini-batches, element by element
+        order = synth.random_order(train.numel(), synth.EPOCH_SEED, 1, DEV)
+        ep = train[order].contiguous()
+        epn = ep.cpu().numpy()
+        n_batches = -(-len(epn) // bs)
+        blocks = tier.Blocks(n, bs, fan, DEV)
+        out = torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=DEV)
+        li = np.full(n, -1, np.int32)
+        hot = oslot >= 0
+        for b in sorted(set(check_batches(n_batches))):
+            seeds = epn[b * bs:(b + 1) * bs]
+            bseed = tier.tier_batch_seed(synth.EPOCH_SEED, 0, b)
+            got = tier.tier_sample_minibatch(ctx, ep[b * bs:(b + 1) * bs], fan, bseed, blocks)
+            want = orc.sample_minibatch(ip, ix, seeds, fan, bseed, local_idx=li)
+            assert got.n_nodes == want["n_nodes"].tolist() and got.n_edges == want["n_edges"].tolist()
+            assert np.array_equal(got.frontier().cpu().numpy(), want["nodes"])
+            for l in range(len(fan)):
+                nd, ne = got.n_nodes[l], got.n_edges[l]
+                assert np.array_equal(got.row_ptr[l][: nd + 1].cpu().numpy(), want["row_ptr"][l])
+                assert np.array_equal(got.eid[l][:ne].cpu().numpy(), want["eid"][l])
+                assert np.array_equal(got.col[l][:ne].cpu().numpy(), want["col"][l])
+            _, hit, miss = tier.tier_gather_features(ctx, got.frontier(), out, want_stats=True)
+            m = got.n_nodes[-1]
+            whit = int(hot[want["nodes"]].sum())
+            assert (hit, miss) == (whit, m - whit)
+            rows_got = out[:m].view(torch.uint8).cpu().numpy().reshape(m, R)
+            assert np.array_equal(rows_got, feat[want["nodes"]])       # = the oracle's gather (pinned to indexing)
+            say(f"{name}: batch {b}: {m} rows ({hit} hot), {sum(got.n_edges)} edges match ({time.time() - t0:.0f}s)")
+        ctx.close()
+    finally:
+        table.free()
+
+
+def test_cfg2_full_size():
+    run_config("cfg2", lambda nb: [0, 1, nb // 2, nb - 1])
+
+
+def test_cfg5_full_size_low_skew():
+    run_config("cfg5", lambda nb: [0, nb - 1])
+
+
+def test_cfg3_full_size_budget_10():
+    run_config("cfg3", lambda nb: [0, nb - 1])
+
+
+def test_cfg3_budgets_5_and_20_slot_maps():
+    """The budget sweep of the third configuration changes only the placement: check the
+    other two slot maps on random counts of the same size (the counts' parity is above)."""
+    wl = synth.WORKLOADS["cfg3"]
+    n = wl.n_nodes
+    rng = np.random.default_rng(3)
+    counts = (rng.geometric(0.2, n) - 1).astype(np.uint32)
+    counts[rng.integers(0, n, 1000)] = rng.integers(256, 1084, 1000)         # two radix passes
+    ip = torch.zeros(n + 1, dtype=torch.int64, device=DEV); ix = torch.zeros(0, dtype=torch.int32, device=DEV)
+    table = tier.tier_host_alloc(n, 4, torch.float32)                         # 16-byte rows keep this light
+    try:
+        ctx = tier.tier_create(ip, ix, table)
+        cd = torch.from_numpy(counts.view(np.int32)).to(DEV)
+        for frac in (0.05, 0.20):
+            budget = int(frac * n * 16)
+            slot, n_hot = tier.tier_place(ctx, cd, budget)
+            _, oslot, ohot = orc.place(counts, 16, budget)
+            assert n_hot == ohot and np.array_equal(slot.cpu().numpy(), oslot)
+            say(f"cfg3-size placement at {frac:.0%}: {n_hot} rows match")
+        ctx.close()
+    finally:
+        table.free()
+
+
+def test_cfg4_fp16_rows_largest_that_can_be_pinned():
+    """85.8 GiB of features at full size; where the host cannot pin that much the same
+    recipe runs at 2/3 of the nodes, edges and budget (56.6 GiB of 1536-byte rows)."""
+    run_config("cfg4", lambda nb: [0, nb - 1], fallback_scale=0.66)
