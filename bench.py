@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--budget", type=float, default=None, help="override: fraction of feature bytes kept in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for profiler byte counters)")
     ap.add_argument("--cpu-batches", type=int, default=192, help="mini-batches in the CPU baseline's sample")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -75,12 +77,18 @@ def main():
     n_batches = -(-n_train // bs)
     order = synth.random_order(n_train, synth.EPOCH_SEED, 1, dev)
     epoch_ids = train[order].contiguous()
-    seeds_of = [epoch_ids[b * bs:(b + 1) * bs] for b in range(n_batches)]
+    B = tier.tier_max_batches(ctx)                 # mini-batches sampled side by side per call
+    groups = [list(range(g, min(g + B, n_batches))) for g in range(0, n_batches, B)]
     bseed = [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in range(n_batches)]
-    blocks = tier.Blocks(n, bs, wl.fanouts, dev)
+    blocks = tier.BlocksBatch(n, bs, wl.fanouts, B, dev)
     out = torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=dev)
     counts = torch.empty(n, dtype=torch.int32, device=dev)
     L = len(wl.fanouts)
+
+    def sample_group(g):
+        lo = g[0] * bs
+        hi = min(n_train, (g[-1] + 1) * bs)
+        return tier.tier_sample_minibatches(ctx, epoch_ids[lo:hi], bs, [bseed[b] for b in g], wl.fanouts, blocks)
 
     def step(record):
         ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -91,24 +99,28 @@ def main():
         _, n_hot = tier.tier_place(ctx, counts, budget, want_slot_map=False)
         e_place.record()
         rows = edges = 0
-        pairs = []
-        for b in range(n_batches):
-            s0, s1, g1 = ev(), ev(), ev()
+        s_pairs, g_pairs = [], []
+        for g in groups:
+            s0, s1 = ev(), ev()
             s0.record()
-            blk = tier.tier_sample_minibatch(ctx, seeds_of[b], wl.fanouts, bseed[b], blocks)
+            blk = sample_group(g)
             s1.record()
-            tier.tier_gather_features(ctx, blk.frontier(), out)
-            g1.record()
-            rows += blk.n_nodes[L]; edges += sum(blk.n_edges)
-            pairs.append((s0, s1, g1, blk.n_nodes[L]))
+            s_pairs.append((s0, s1))
+            for i, b in enumerate(g):
+                g0, g1 = ev(), ev()
+                g0.record()
+                tier.tier_gather_features(ctx, blk.frontier(i), out)
+                g1.record()
+                g_pairs.append((g0, g1))
+                rows += blk.n_nodes[i][L]; edges += sum(blk.n_edges[i])
         torch.cuda.synchronize()
         if record is not None:
             record["presample_ms"].append(e_begin.elapsed_time(e_pre))
             record["place_ms"].append(e_pre.elapsed_time(e_place))
-            record["sample_ms"].append(sum(a.elapsed_time(b_) for a, b_, _, _ in pairs))
-            record["gather_ms"].append(sum(b_.elapsed_time(c) for _, b_, c, _ in pairs))
+            record["sample_ms"].append(sum(a.elapsed_time(b_) for a, b_ in s_pairs))
+            record["gather_ms"].append(sum(a.elapsed_time(b_) for a, b_ in g_pairs))
             record["rows"] = rows; record["edges"] = edges; record["n_hot"] = n_hot
-            record["gather_launches"] = len(pairs)
+            record["gather_launches"] = len(g_pairs)
         return rows, edges
 
     for _ in range(args.warmup):
@@ -124,10 +136,11 @@ def main():
 
     # hit / miss rows of the measured epoch (outside the timed region: asking for them waits per batch)
     hit_rows = 0
-    for b in range(n_batches):
-        blk = tier.tier_sample_minibatch(ctx, seeds_of[b], wl.fanouts, bseed[b], blocks)
-        _, h, m = tier.tier_gather_features(ctx, blk.frontier(), out, want_stats=True)
-        hit_rows += h
+    for g in groups:
+        blk = sample_group(g)
+        for i in range(len(g)):
+            _, h, m = tier.tier_gather_features(ctx, blk.frontier(i), out, want_stats=True)
+            hit_rows += h
     rows, edges = rec["rows"], rec["edges"]
     h = hit_rows / rows if rows else 0.0
     mean = lambda xs: sum(xs) / len(xs) if xs else 0.0
@@ -172,7 +185,7 @@ def main():
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.graph} graph, {n} nodes, {indices.numel()} edges, "
                                f"{wl.dim} x {wl.dtype} features, fanout {list(wl.fanouts)}, batch {bs}, "
-                               f"{n_batches} mini-batches per epoch, HBM budget {budget} B ({rec['n_hot']} rows)"},
+                               f"{n_batches} mini-batches per epoch sampled {B} per call, HBM budget {budget} B ({rec['n_hot']} rows)"},
         "sampled_edges_per_s": round(edges / (sample_ms * 1e-3)) if sample_ms else None,
         "gather_GBps": round(gathered_bytes / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
         "rows_per_epoch": rows, "edges_per_epoch": edges, "hit_fraction": round(h, 4),

@@ -44,6 +44,7 @@ extern "C" {
 
 #define TIER_MAX_LAYERS 8    /* hops per mini-batch                              */
 #define TIER_MAX_FANOUT 64   /* neighbours drawn per node per hop (one wavefront) */
+#define TIER_MAX_BATCHES 16  /* mini-batches one tier_sample_minibatches call can take  */
 
 typedef enum {
     TIER_OK = 0,
@@ -94,6 +95,23 @@ typedef struct {
     int64_t n_edges[TIER_MAX_LAYERS];     /* (host, out) edges of block l                */
 } tier_blocks;
 
+/* Blocks of several mini-batches sampled by one call, each array strided by
+ * mini-batch: mini-batch s has its frontier at nodes + s * nodes_stride, its block l
+ * at row_ptr[l] + s * row_ptr_stride[l], col[l] + s * edge_stride[l] and
+ * eid[l] + s * edge_stride[l], laid out as in tier_blocks.  Strides must reach the
+ * bounds of tier_blocks_bounds for one mini-batch (row_ptr: bound + 1). */
+typedef struct {
+    int32_t *nodes;                           /* (device) n_batches * nodes_stride entries          */
+    int64_t nodes_stride;
+    int32_t *row_ptr[TIER_MAX_LAYERS];        /* (device) n_batches * row_ptr_stride[l] entries     */
+    int32_t *col[TIER_MAX_LAYERS];            /* (device) n_batches * edge_stride[l] entries        */
+    int64_t *eid[TIER_MAX_LAYERS];            /* (device) n_batches * edge_stride[l] entries        */
+    int64_t row_ptr_stride[TIER_MAX_LAYERS];
+    int64_t edge_stride[TIER_MAX_LAYERS];
+    int64_t *n_nodes;   /* (host, out) n_batches x (TIER_MAX_LAYERS + 1): |frontier_l| of batch s at [s*(TIER_MAX_LAYERS+1) + l] */
+    int64_t *n_edges;   /* (host, out) n_batches x TIER_MAX_LAYERS: edges of block l of batch s at [s*TIER_MAX_LAYERS + l]      */
+} tier_blocks_batch;
+
 typedef struct {
     int64_t hit_rows;    /* rows read from the HBM cache   */
     int64_t miss_rows;   /* rows read from host memory     */
@@ -113,7 +131,9 @@ int tier_blocks_bounds(int64_t n_graph_nodes, int64_t n_seeds, const int32_t *fa
 /* Create a context for one graph and one feature table on the current device.
  * The graph arrays and the feature table are referenced, not copied, and must
  * outlive the context.  stream is a hipStream_t (NULL = the default stream).
- * Allocates scratch proportional to n_nodes (about 4.2 bytes per node). */
+ * Allocates scratch proportional to n_nodes: 4 bytes per node for the slot map and
+ * about 4.2 bytes per node for each mini-batch that can be sampled at once (as many,
+ * up to TIER_MAX_BATCHES, as fit in 4 GiB). */
 int tier_create(tier_ctx **out, const tier_csr *csr, const tier_feat *feat, void *stream);
 void tier_destroy(tier_ctx *ctx);
 
@@ -151,6 +171,20 @@ int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes,
 int tier_sample_minibatch(tier_ctx *ctx, const int32_t *seeds, int32_t n_seeds,
                           const int32_t *fanouts /* host */, int32_t n_layers, uint64_t seed,
                           tier_blocks *out);
+
+/* Several mini-batches at once (Sec. 2.2; one mini-batch alone cannot fill the GPU,
+ * so a training loop that prefetches samples them together).  seeds: (device)
+ * n_seeds_total ids; mini-batch s takes seeds[s*batch_size .. (s+1)*batch_size) (the
+ * last one what is left, possibly nothing) and samples with batch_seeds[s] (host,
+ * n_batches entries), giving exactly what tier_sample_minibatch gives for those seeds
+ * and that seed.  1 <= n_batches <= tier_max_batches(ctx);
+ * n_seeds_total <= n_batches * batch_size.  Waits. */
+int tier_sample_minibatches(tier_ctx *ctx, const int32_t *seeds, int64_t n_seeds_total, int32_t batch_size,
+                            int32_t n_batches, const int32_t *fanouts /* host */, int32_t n_layers,
+                            const uint64_t *batch_seeds /* host */, tier_blocks_batch *out);
+
+/* Mini-batches one call can take with this context's scratch memory (1..TIER_MAX_BATCHES). */
+int tier_max_batches(const tier_ctx *ctx);
 
 /* Tiered gather (Sec. 4.1, Listing 1).  out[i, :] = feature row of ids[i], read from
  * the HBM cache when slot[ids[i]] >= 0 and from host memory otherwise; the result

@@ -50,7 +50,8 @@ int grid_for(int64_t n, int block, int cap)
 // reported once and cleared.
 int tier_sync_meta(tier_ctx *c)
 {
-    TIER_HIP(c, hipMemcpyAsync(c->meta_host, c->meta, META_WORDS * sizeof(int64_t), hipMemcpyDeviceToHost, c->stream));
+    TIER_HIP(c, hipMemcpyAsync(c->meta_host, c->meta, (size_t)c->n_slots * META_WORDS * sizeof(int64_t),
+                               hipMemcpyDeviceToHost, c->stream));
     TIER_HIP(c, hipStreamSynchronize(c->stream));
     if (c->meta_host[META_ERROR] != 0) {
         k_clear_error<<<1, 1, 0, c->stream>>>(c->meta);
@@ -122,7 +123,6 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipHostFree(ctx->meta_host);
     (void)hipFree(ctx->partial_hop);
     (void)hipFree(ctx->partial_bm);
-    (void)hipFree(ctx->src_tmp);
     (void)hipFree(ctx->ps_nodes);
     (void)hipGetLastError();
     delete ctx;
@@ -148,16 +148,22 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
 
     const int64_t n = c->n_nodes;
     c->n_words = (n + 31) / 32;
-    TIER_HIP(c, hipMalloc(&c->local_idx, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
-    TIER_HIP(c, hipMalloc(&c->bitmap, (size_t)(c->n_words > 0 ? c->n_words : 1) * sizeof(uint32_t)));
+    // as many mini-batch slots as fit in 4 GiB of per-node scratch
+    const int64_t per_slot = (n + c->n_words + 1) * 4;
+    int64_t slots = (4LL << 30) / per_slot;
+    c->n_slots = (int)(slots < 1 ? 1 : (slots > TIER_MAX_BATCHES ? TIER_MAX_BATCHES : slots));
+    const size_t S = (size_t)c->n_slots;
+    TIER_HIP(c, hipMalloc(&c->local_idx, S * (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
+    TIER_HIP(c, hipMalloc(&c->bitmap, S * (size_t)(c->n_words > 0 ? c->n_words : 1) * sizeof(uint32_t)));
     TIER_HIP(c, hipMalloc(&c->slot, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
-    TIER_HIP(c, hipMalloc(&c->meta, META_WORDS * sizeof(int64_t)));
-    TIER_HIP(c, hipHostMalloc((void **)&c->meta_host, META_WORDS * sizeof(int64_t), hipHostMallocDefault));
-    TIER_HIP(c, hipMalloc(&c->partial_hop, TIER_SCAN_BLOCKS * sizeof(int32_t)));
-    TIER_HIP(c, hipMalloc(&c->partial_bm, TIER_SCAN_BLOCKS * sizeof(int32_t)));
-    k_fill_i32<<<grid_for(n, 256, 4096), 256, 0, c->stream>>>(c->local_idx, n, -1);
-    k_fill_i32<<<grid_for(c->n_words, 256, 4096), 256, 0, c->stream>>>((int32_t *)c->bitmap, c->n_words, 0);
-    k_fill_i32<<<1, 64, 0, c->stream>>>((int32_t *)c->meta, META_WORDS * 2, 0);
+    TIER_HIP(c, hipMalloc(&c->meta, S * META_WORDS * sizeof(int64_t)));
+    TIER_HIP(c, hipHostMalloc((void **)&c->meta_host, S * META_WORDS * sizeof(int64_t), hipHostMallocDefault));
+    TIER_HIP(c, hipMalloc(&c->partial_hop, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
+    TIER_HIP(c, hipMalloc(&c->partial_bm, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
+    k_fill_i32<<<grid_for(n * (int64_t)S, 256, 8192), 256, 0, c->stream>>>(c->local_idx, n * (int64_t)S, -1);
+    k_fill_i32<<<grid_for(c->n_words * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->bitmap,
+                                                                                  c->n_words * (int64_t)S, 0);
+    k_fill_i32<<<4, 256, 0, c->stream>>>((int32_t *)c->meta, (int64_t)S * META_WORDS * 2, 0);
     TIER_HIP(c, hipGetLastError());
 
     // validate the graph once

@@ -1,12 +1,17 @@
-// Neighbour sampling of one mini-batch (Sec. 2.2) and the access counts built on
+// Neighbour sampling of mini-batches (Sec. 2.2) and the access counts built on
 // it (Sec. 3.1, Sec. 5.2).
 //
-// One hop over the current frontier runs as a short chain of kernels on the
-// context's stream; all sizes stay on the device (tier_internal.h, META_*):
+// A mini-batch of ~1000 seeds is far too small to fill 256 compute units, so the
+// sampler works on up to TIER_MAX_BATCHES mini-batches side by side: every
+// kernel below is launched on a (blocks, slots) grid, blockIdx.y naming the slot
+// (one mini-batch with its own frontier, its own `local_idx` and bitmap scratch
+// and its own size bookkeeping).  One hop over the current frontiers is a short
+// chain of kernels on the context's stream; all sizes stay on the device
+// (tier_internal.h, META_*):
 //
 //   k_hop_partial   per-block sums of min(fanout, degree) over the frontier
-//   k_hop_sample    offsets of every dst's edges (scan of the sums above), then a
-//                   group of G lanes per dst draws its neighbours: lane i owns
+//   k_hop_rowptr    offsets of every dst's edges (scan of the sums above)
+//   k_hop_sample    a group of G lanes per dst draws its neighbours: lane i owns
 //                   draw i, the Floyd collision rule is resolved with in-group
 //                   shuffles; every neighbour not yet in the frontier sets its
 //                   bit in a bitmap over all nodes
@@ -14,19 +19,75 @@
 //   k_bm_emit       bitmap -> ascending list of new nodes appended to the
 //                   frontier (dedup and sort in one pass), their frontier index
 //                   recorded in local_idx[], bitmap cleared
-//   k_relabel       col[e] = frontier index of the sampled neighbour
+//   k_relabel       once per mini-batch, all hops: col[e] = frontier index of
+//                   the sampled neighbour (col[] held its node id until then)
 //
 // tier_presample runs the same chain without materialising blocks (no offsets,
 // no edge ids, no relabel) and ends every mini-batch with one atomic increment
 // per frontier node.  Within a mini-batch the frontier nodes are distinct, so
-// increments of one launch never collide; concurrent launches of one stream do
-// not overlap either, hence plain global atomics (no LDS staging) suffice.
+// only mini-batches of different slots can meet on one counter; global atomics
+// handle that (the counters are spread over all nodes, there is no hot spot an
+// LDS staging could absorb).
 #include "rng.h"
 #include "tier_internal.h"
 
 namespace {
 
 constexpr int kBlock = 256;
+
+// What every sampler kernel needs to find its slot's data (passed by value).
+struct wide_t {
+    const int32_t *seeds;        // slot s reads seeds + s * batch_size
+    int64_t n_seeds_total;
+    int32_t batch_size;
+    int32_t n_slots;
+    int64_t n_nodes;             // graph nodes
+    int64_t n_words;             // bitmap words per slot
+    int32_t *nodes;              // slot s: nodes + s * nodes_stride
+    int64_t nodes_stride;
+    int32_t *local_idx;          // [slot][n_nodes]
+    uint32_t *bitmap;            // [slot][n_words]
+    int64_t *meta;               // [slot][META_WORDS]; totals and the error flag live in slot 0
+    int32_t *partial_hop;        // [slot][TIER_SCAN_BLOCKS]
+    int32_t *partial_bm;         // [slot][TIER_SCAN_BLOCKS]
+    uint32_t key0[TIER_MAX_BATCHES], key1[TIER_MAX_BATCHES];   // halves of each slot's seed
+};
+
+struct layer_out_t {             // one hop's outputs, slot-strided
+    int32_t *row_ptr;
+    int64_t row_ptr_stride;
+    int32_t *col;
+    int64_t *eid;
+    int64_t edge_stride;
+};
+
+struct relabel_t {
+    int32_t *col[TIER_MAX_LAYERS];
+    int64_t stride[TIER_MAX_LAYERS];
+    int32_t n_layers;
+};
+
+struct slot_view {
+    int32_t *nodes;
+    int32_t *local_idx;
+    uint32_t *bitmap;
+    int64_t *meta;
+    int32_t *partial_hop;
+    int32_t *partial_bm;
+};
+
+__device__ inline slot_view view_of(const wide_t &w)
+{
+    const int64_t s = blockIdx.y;
+    slot_view v;
+    v.nodes = w.nodes + s * w.nodes_stride;
+    v.local_idx = w.local_idx + s * w.n_nodes;
+    v.bitmap = w.bitmap + s * w.n_words;
+    v.meta = w.meta + s * META_WORDS;
+    v.partial_hop = w.partial_hop + s * TIER_SCAN_BLOCKS;
+    v.partial_bm = w.partial_bm + s * TIER_SCAN_BLOCKS;
+    return v;
+}
 
 __device__ inline int wave_incl_scan(int x)
 {
@@ -96,40 +157,73 @@ __device__ inline void partial_prefix(const int32_t *partial, int &before, int &
     all = block_sum(a, s_wave);
 }
 
-__global__ void k_init_seeds(const int32_t *__restrict__ seeds, int32_t n_seeds, int64_t n_nodes,
-                             int32_t *__restrict__ nodes, int32_t *__restrict__ local_idx,
-                             int64_t *__restrict__ meta)
+__global__ void k_init_seeds(wide_t w)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) meta[META_NFRONT] = n_seeds;
-    if (i < n_seeds) {
-        int32_t v = seeds[i];
-        if ((uint32_t)v >= (uint64_t)n_nodes) {
-            atomicOr((int *)&meta[META_ERROR], 1);
-            v = 0;                                  // keep every later index in range
+    const slot_view v = view_of(w);
+    const int64_t first = (int64_t)blockIdx.y * w.batch_size;
+    int64_t n = w.n_seeds_total - first;
+    n = n < 0 ? 0 : (n > w.batch_size ? w.batch_size : n);
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) v.meta[META_NFRONT] = n;
+    if (i < n) {
+        int32_t u = w.seeds[first + i];
+        if ((uint32_t)u >= (uint64_t)w.n_nodes) {
+            atomicOr((int *)&w.meta[META_ERROR], 1);
+            u = 0;                                   // keep every later index in range
         }
-        nodes[i] = v;
-        local_idx[v] = i;
+        v.nodes[i] = u;
+        v.local_idx[u] = (int32_t)i;
     }
 }
 
 template <typename OffT>
-__global__ __launch_bounds__(kBlock) void k_hop_partial(const OffT *__restrict__ indptr,
-                                                        const int32_t *__restrict__ nodes,
-                                                        const int64_t *__restrict__ meta, int layer, int k,
-                                                        int32_t *__restrict__ partial)
+__global__ __launch_bounds__(kBlock) void k_hop_partial(wide_t w, const OffT *__restrict__ indptr, int layer, int k)
 {
     __shared__ int s_wave[kBlock / 64];
+    const slot_view v = view_of(w);
     int64_t lo, hi;
-    block_range(meta[META_NFRONT + layer], lo, hi);
+    block_range(v.meta[META_NFRONT + layer], lo, hi);
     int sum = 0;
     for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
-        int32_t v = nodes[i];
-        int64_t d = (int64_t)(indptr[v + 1] - indptr[v]);
+        int32_t u = v.nodes[i];
+        int64_t d = (int64_t)(indptr[u + 1] - indptr[u]);
         sum += d < k ? (int)d : k;
     }
     int tot = block_sum(sum, s_wave);
-    if (threadIdx.x == 0) partial[blockIdx.x] = tot;
+    if (threadIdx.x == 0) v.partial_hop[blockIdx.x] = tot;
+}
+
+// Offsets of every dst's edges: row_ptr[i] = sum of min(k, degree) over dst 0..i-1.
+// Same grid as k_hop_partial; block b owns the same contiguous share of the frontier.
+template <typename OffT>
+__global__ __launch_bounds__(kBlock) void k_hop_rowptr(wide_t w, const OffT *__restrict__ indptr, int layer, int k,
+                                                       layer_out_t o)
+{
+    __shared__ int s_wave[kBlock / 64];
+    const slot_view v = view_of(w);
+    int32_t *row_ptr = o.row_ptr + (int64_t)blockIdx.y * o.row_ptr_stride;
+    const int64_t n = v.meta[META_NFRONT + layer];
+    int64_t lo, hi;
+    block_range(n, lo, hi);
+    int carry, all;
+    partial_prefix(v.partial_hop, carry, all, s_wave);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        v.meta[META_NEDGES + layer] = all;
+        row_ptr[n] = all;
+    }
+    for (int64_t tile = lo; tile < hi; tile += kBlock) {
+        const int64_t i = tile + threadIdx.x;
+        int cnt = 0;
+        if (i < hi) {
+            int32_t u = v.nodes[i];
+            int64_t d = (int64_t)(indptr[u + 1] - indptr[u]);
+            cnt = d < k ? (int)d : k;
+        }
+        int tot;
+        int rp = carry + block_excl_scan(cnt, tot, s_wave);
+        if (i < hi) row_ptr[i] = rp;
+        carry += tot;
+    }
 }
 
 // One dst node, handled by a group of G consecutive lanes (G a power of two, k <= G).
@@ -140,7 +234,7 @@ template <int G, bool BLOCKS, typename OffT>
 __device__ inline void sample_one(int lane, int32_t v, OffT beg, int32_t d, int k, int layer, uint32_t key0,
                                   uint32_t key1, const int32_t *__restrict__ indices,
                                   const int32_t *__restrict__ local_idx, uint32_t *__restrict__ bitmap,
-                                  int64_t *__restrict__ eid, int32_t *__restrict__ src_tmp, int32_t rp)
+                                  int64_t *__restrict__ eid, int32_t *__restrict__ col, int32_t rp)
 {
     const bool draw = d > k;
     const int cnt = draw ? k : d;
@@ -165,147 +259,117 @@ __device__ inline void sample_one(int lane, int32_t v, OffT beg, int32_t d, int 
         int32_t u = indices[e];
         if (BLOCKS) {
             eid[rp + lane] = (int64_t)e;
-            src_tmp[rp + lane] = u;
+            col[rp + lane] = u;                     // node id for now; k_relabel turns it into an index
         }
         if (local_idx[u] < 0) atomicOr(&bitmap[u >> 5], 1u << (u & 31));
     }
 }
 
+// One group of G lanes per dst node, all dst nodes of the frontier side by side.
 template <typename OffT, int G, bool BLOCKS>
-__global__ __launch_bounds__(kBlock) void k_hop_sample(
-    const OffT *__restrict__ indptr, const int32_t *__restrict__ indices, const int32_t *__restrict__ nodes,
-    int64_t *__restrict__ meta, int layer, int k, uint32_t key0, uint32_t key1,
-    const int32_t *__restrict__ partial, const int32_t *__restrict__ local_idx, uint32_t *__restrict__ bitmap,
-    int32_t *__restrict__ row_ptr, int64_t *__restrict__ eid, int32_t *__restrict__ src_tmp)
+__global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, const OffT *__restrict__ indptr,
+                                                       const int32_t *__restrict__ indices, int layer, int k,
+                                                       layer_out_t o)
 {
     __shared__ int s_wave[kBlock / 64];
-    __shared__ int32_t s_v[kBlock];
-    __shared__ OffT s_beg[kBlock];
-    __shared__ int32_t s_deg[kBlock];
-    __shared__ int32_t s_rp[kBlock];
     constexpr int kGroups = kBlock / G;
+    const slot_view v = view_of(w);
+    const int s = blockIdx.y;
+    const int32_t *row_ptr = BLOCKS ? o.row_ptr + (int64_t)s * o.row_ptr_stride : nullptr;
+    int32_t *col = BLOCKS ? o.col + (int64_t)s * o.edge_stride : nullptr;
+    int64_t *eid = BLOCKS ? o.eid + (int64_t)s * o.edge_stride : nullptr;
+    const uint32_t key0 = w.key0[s], key1 = w.key1[s];
     const int lane = threadIdx.x % G;
-    const int group = threadIdx.x / G;
-
-    const int64_t n = meta[META_NFRONT + layer];
-    int64_t lo, hi;
-    block_range(n, lo, hi);
-    int carry = 0;
-    if (BLOCKS) {
-        int all;
-        partial_prefix(partial, carry, all, s_wave);
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            meta[META_NEDGES + layer] = all;
-            row_ptr[n] = all;
-        }
-    }
+    const int64_t n = v.meta[META_NFRONT + layer];
+    const int64_t stride = (int64_t)gridDim.x * kGroups;
     int edges = 0;
-    for (int64_t tile = lo; tile < hi; tile += kBlock) {
-        const int64_t i = tile + threadIdx.x;
-        int32_t v = 0, d = 0, cnt = 0;
-        OffT beg = 0;
-        if (i < hi) {
-            v = nodes[i];
-            beg = indptr[v];
-            d = (int32_t)(indptr[v + 1] - beg);
-            cnt = d < k ? d : k;
-        }
-        int rp = 0;
-        if (BLOCKS) {
-            int tot;
-            rp = carry + block_excl_scan(cnt, tot, s_wave);
-            if (i < hi) row_ptr[i] = rp;
-            carry += tot;
-        } else {
-            edges += cnt;
-            __syncthreads();
-        }
-        s_v[threadIdx.x] = v;
-        s_beg[threadIdx.x] = beg;
-        s_deg[threadIdx.x] = d;
-        s_rp[threadIdx.x] = rp;
-        __syncthreads();
-        const int tile_n = (int)((hi - tile) < kBlock ? (hi - tile) : kBlock);
-        for (int jj = group; jj < tile_n; jj += kGroups)
-            sample_one<G, BLOCKS, OffT>(lane, s_v[jj], s_beg[jj], s_deg[jj], k, layer, key0, key1, indices,
-                                        local_idx, bitmap, eid, src_tmp, s_rp[jj]);
-        __syncthreads();
+    for (int64_t i = (int64_t)blockIdx.x * kGroups + threadIdx.x / G; i < n; i += stride) {
+        const int32_t u = v.nodes[i];
+        const OffT beg = indptr[u];
+        const int32_t d = (int32_t)(indptr[u + 1] - beg);
+        int32_t rp = 0;
+        if (BLOCKS) rp = row_ptr[i];
+        else if (lane == 0) edges += d < k ? d : k;
+        sample_one<G, BLOCKS, OffT>(lane, u, beg, d, k, layer, key0, key1, indices, v.local_idx, v.bitmap, eid, col,
+                                    rp);
     }
     if (!BLOCKS) {
         int tot = block_sum(edges, s_wave);
         if (threadIdx.x == 0 && tot)
-            atomicAdd((unsigned long long *)&meta[META_TOTAL_EDGES], (unsigned long long)tot);
+            atomicAdd((unsigned long long *)&w.meta[META_TOTAL_EDGES], (unsigned long long)tot);
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_bm_partial(const uint32_t *__restrict__ bitmap, int64_t n_words,
-                                                       int32_t *__restrict__ partial)
+__global__ __launch_bounds__(kBlock) void k_bm_partial(wide_t w)
 {
     __shared__ int s_wave[kBlock / 64];
+    const slot_view v = view_of(w);
     int64_t lo, hi;
-    block_range(n_words, lo, hi);
+    block_range(w.n_words, lo, hi);
     int sum = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) sum += __popc(bitmap[i]);
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) sum += __popc(v.bitmap[i]);
     int tot = block_sum(sum, s_wave);
-    if (threadIdx.x == 0) partial[blockIdx.x] = tot;
+    if (threadIdx.x == 0) v.partial_bm[blockIdx.x] = tot;
 }
 
-__global__ __launch_bounds__(kBlock) void k_bm_emit(uint32_t *__restrict__ bitmap, int64_t n_words,
-                                                    const int32_t *__restrict__ partial,
-                                                    int64_t *__restrict__ meta, int layer,
-                                                    int32_t *__restrict__ nodes, int32_t *__restrict__ local_idx)
+__global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int layer)
 {
     __shared__ int s_wave[kBlock / 64];
+    const slot_view v = view_of(w);
     int64_t lo, hi;
-    block_range(n_words, lo, hi);
+    block_range(w.n_words, lo, hi);
     int carry, all;
-    partial_prefix(partial, carry, all, s_wave);
-    const int64_t base = meta[META_NFRONT + layer];
-    if (blockIdx.x == 0 && threadIdx.x == 0) meta[META_NFRONT + layer + 1] = base + all;
+    partial_prefix(v.partial_bm, carry, all, s_wave);
+    const int64_t base = v.meta[META_NFRONT + layer];
+    if (blockIdx.x == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all;
     for (int64_t tile = lo; tile < hi; tile += kBlock) {
         const int64_t i = tile + threadIdx.x;
-        uint32_t w = i < hi ? bitmap[i] : 0u;
+        uint32_t bits = i < hi ? v.bitmap[i] : 0u;
         int tot;
-        int64_t pos = base + carry + block_excl_scan(__popc(w), tot, s_wave);
+        int64_t pos = base + carry + block_excl_scan(__popc(bits), tot, s_wave);
         carry += tot;
-        if (w) {
-            bitmap[i] = 0u;
-            while (w) {
-                int b = __ffs(w) - 1;
-                w &= w - 1;
+        if (bits) {
+            v.bitmap[i] = 0u;
+            while (bits) {
+                int b = __ffs(bits) - 1;
+                bits &= bits - 1;
                 int32_t u = (int32_t)(i * 32 + b);
-                nodes[pos] = u;
-                local_idx[u] = (int32_t)pos;
+                v.nodes[pos] = u;
+                v.local_idx[u] = (int32_t)pos;
                 ++pos;
             }
         }
     }
 }
 
-__global__ void k_relabel(const int32_t *__restrict__ src_tmp, const int32_t *__restrict__ local_idx,
-                          const int64_t *__restrict__ meta, int layer, int32_t *__restrict__ col)
+__global__ void k_relabel(wide_t w, relabel_t r)
 {
-    const int64_t n = meta[META_NEDGES + layer];
+    const slot_view v = view_of(w);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride)
-        col[e] = local_idx[src_tmp[e]];
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int l = 0; l < r.n_layers; ++l) {
+        int32_t *col = r.col[l] + (int64_t)blockIdx.y * r.stride[l];
+        const int64_t n = v.meta[META_NEDGES + l];
+        for (int64_t e = t; e < n; e += stride) col[e] = v.local_idx[col[e]];
+    }
 }
 
 // End of a mini-batch: take its nodes out of local_idx[]; with COUNT, one access
 // per node of the final frontier (the rows a gather for this mini-batch reads).
 template <bool COUNT>
-__global__ void k_finish(const int32_t *__restrict__ nodes, int64_t *__restrict__ meta, int n_layers,
-                         int32_t *__restrict__ local_idx, uint32_t *__restrict__ counts)
+__global__ void k_finish(wide_t w, int n_layers, uint32_t *__restrict__ counts)
 {
-    const int64_t n = meta[META_NFRONT + n_layers];
+    const slot_view v = view_of(w);
+    const int64_t n = v.meta[META_NFRONT + n_layers];
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t i = t; i < n; i += stride) {
-        int32_t v = nodes[i];
-        local_idx[v] = -1;
-        if (COUNT) atomicAdd(&counts[v], 1u);
+        int32_t u = v.nodes[i];
+        v.local_idx[u] = -1;
+        if (COUNT) atomicAdd(&counts[u], 1u);
     }
-    if (COUNT && t == 0) meta[META_TOTAL_ROWS] += n;
+    if (COUNT && t == 0 && n)
+        atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)n);
 }
 
 __global__ void k_fill_u32(uint32_t *__restrict__ p, int64_t n, uint32_t value)
@@ -328,68 +392,88 @@ int clamp_grid(int64_t items, int per_block, int cap)
     return (int)g;
 }
 
-struct batch_out {            // where one mini-batch's results go
-    int32_t *nodes;
-    int32_t *row_ptr[TIER_MAX_LAYERS];
-    int32_t *col[TIER_MAX_LAYERS];
-    int64_t *eid[TIER_MAX_LAYERS];
-    bool blocks;              // false: frontier only (access counting)
-    uint32_t *counts;         // non-null: count the final frontier
+struct wide_out {             // where the mini-batches' results go
+    layer_out_t layer[TIER_MAX_LAYERS];
+    bool blocks;              // false: frontiers only (access counting)
+    uint32_t *counts;         // non-null: count the final frontiers
 };
 
 template <typename OffT, int G>
-void launch_hop_sample(tier_ctx *c, int grid, int layer, int k, uint64_t seed, const batch_out &o)
+void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, const wide_out &o)
 {
     const OffT *ip = (const OffT *)c->indptr;
+    const dim3 grid(clamp_grid(cap_dst, kBlock / G, 16384), w.n_slots);
     if (o.blocks)
-        k_hop_sample<OffT, G, true><<<grid, kBlock, 0, c->stream>>>(
-            ip, c->indices, o.nodes, c->meta, layer, k, (uint32_t)seed, (uint32_t)(seed >> 32), c->partial_hop,
-            c->local_idx, c->bitmap, o.row_ptr[layer], o.eid[layer], c->src_tmp);
+        k_hop_sample<OffT, G, true><<<grid, kBlock, 0, c->stream>>>(w, ip, c->indices, layer, k, o.layer[layer]);
     else
-        k_hop_sample<OffT, G, false><<<grid, kBlock, 0, c->stream>>>(
-            ip, c->indices, o.nodes, c->meta, layer, k, (uint32_t)seed, (uint32_t)(seed >> 32), c->partial_hop,
-            c->local_idx, c->bitmap, nullptr, nullptr, nullptr);
+        k_hop_sample<OffT, G, false><<<grid, kBlock, 0, c->stream>>>(w, ip, c->indices, layer, k, layer_out_t{});
 }
 
 template <typename OffT>
-void launch_hop(tier_ctx *c, int grid, int layer, int k, uint64_t seed, const batch_out &o)
+void launch_hop(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, const wide_out &o)
 {
-    if (o.blocks)
-        k_hop_partial<OffT><<<grid, kBlock, 0, c->stream>>>((const OffT *)c->indptr, o.nodes, c->meta, layer, k,
-                                                            c->partial_hop);
-    if (k <= 4) launch_hop_sample<OffT, 4>(c, grid, layer, k, seed, o);
-    else if (k <= 8) launch_hop_sample<OffT, 8>(c, grid, layer, k, seed, o);
-    else if (k <= 16) launch_hop_sample<OffT, 16>(c, grid, layer, k, seed, o);
-    else if (k <= 32) launch_hop_sample<OffT, 32>(c, grid, layer, k, seed, o);
-    else launch_hop_sample<OffT, 64>(c, grid, layer, k, seed, o);
+    if (o.blocks) {
+        const dim3 grid(clamp_grid(cap_dst, kBlock, TIER_SCAN_BLOCKS), w.n_slots);
+        k_hop_partial<OffT><<<grid, kBlock, 0, c->stream>>>(w, (const OffT *)c->indptr, layer, k);
+        k_hop_rowptr<OffT><<<grid, kBlock, 0, c->stream>>>(w, (const OffT *)c->indptr, layer, k, o.layer[layer]);
+    }
+    if (k <= 4) launch_hop_sample<OffT, 4>(c, w, cap_dst, layer, k, o);
+    else if (k <= 8) launch_hop_sample<OffT, 8>(c, w, cap_dst, layer, k, o);
+    else if (k <= 16) launch_hop_sample<OffT, 16>(c, w, cap_dst, layer, k, o);
+    else if (k <= 32) launch_hop_sample<OffT, 32>(c, w, cap_dst, layer, k, o);
+    else launch_hop_sample<OffT, 64>(c, w, cap_dst, layer, k, o);
 }
 
-// Enqueue one mini-batch.  cap_nodes / cap_edges: the bounds of tier_blocks_bounds.
-int enqueue_batch(tier_ctx *c, const int32_t *seeds, int32_t n_seeds, const int32_t *fanouts, int n_layers,
-                  uint64_t seed, const int64_t *cap_nodes, const int64_t *cap_edges, const batch_out &o)
+// Enqueue w.n_slots mini-batches.  cap_nodes / cap_edges: the bounds of tier_blocks_bounds
+// for one mini-batch of w.batch_size seeds.
+int enqueue_wide(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_layers, const int64_t *cap_nodes,
+                 const int64_t *cap_edges, const wide_out &o)
 {
-    k_init_seeds<<<clamp_grid(n_seeds, kBlock, 1 << 20), kBlock, 0, c->stream>>>(seeds, n_seeds, c->n_nodes, o.nodes,
-                                                                                c->local_idx, c->meta);
-    const int bm_grid = clamp_grid(c->n_words, 4 * kBlock, TIER_SCAN_BLOCKS);
+    const unsigned slots = (unsigned)w.n_slots;
+    k_init_seeds<<<dim3(clamp_grid(w.batch_size, kBlock, 1 << 20), slots), kBlock, 0, c->stream>>>(w);
+    const dim3 bm_grid(clamp_grid(c->n_words, 4 * kBlock, TIER_SCAN_BLOCKS), slots);
     for (int l = 0; l < n_layers; ++l) {
-        const int k = fanouts[l];
-        const int grid = clamp_grid(cap_nodes[l], kBlock, TIER_SCAN_BLOCKS);
-        if (c->indptr_i64) launch_hop<int64_t>(c, grid, l, k, seed, o);
-        else launch_hop<int32_t>(c, grid, l, k, seed, o);
-        k_bm_partial<<<bm_grid, kBlock, 0, c->stream>>>(c->bitmap, c->n_words, c->partial_bm);
-        k_bm_emit<<<bm_grid, kBlock, 0, c->stream>>>(c->bitmap, c->n_words, c->partial_bm, c->meta, l, o.nodes,
-                                                     c->local_idx);
-        if (o.blocks)
-            k_relabel<<<clamp_grid(cap_edges[l], kBlock, 4096), kBlock, 0, c->stream>>>(c->src_tmp, c->local_idx,
-                                                                                       c->meta, l, o.col[l]);
+        if (c->indptr_i64) launch_hop<int64_t>(c, w, cap_nodes[l], l, fanouts[l], o);
+        else launch_hop<int32_t>(c, w, cap_nodes[l], l, fanouts[l], o);
+        k_bm_partial<<<bm_grid, kBlock, 0, c->stream>>>(w);
+        k_bm_emit<<<bm_grid, kBlock, 0, c->stream>>>(w, l);
     }
-    const int fgrid = clamp_grid(cap_nodes[n_layers], kBlock, 4096);
-    if (o.counts)
-        k_finish<true><<<fgrid, kBlock, 0, c->stream>>>(o.nodes, c->meta, n_layers, c->local_idx, o.counts);
-    else
-        k_finish<false><<<fgrid, kBlock, 0, c->stream>>>(o.nodes, c->meta, n_layers, c->local_idx, nullptr);
+    if (o.blocks) {
+        relabel_t r = {};
+        r.n_layers = n_layers;
+        int64_t most = 1;
+        for (int l = 0; l < n_layers; ++l) {
+            r.col[l] = o.layer[l].col;
+            r.stride[l] = o.layer[l].edge_stride;
+            if (cap_edges[l] > most) most = cap_edges[l];
+        }
+        k_relabel<<<dim3(clamp_grid(most, kBlock, 4096), slots), kBlock, 0, c->stream>>>(w, r);
+    }
+    const dim3 fgrid(clamp_grid(cap_nodes[n_layers], kBlock, 4096), slots);
+    if (o.counts) k_finish<true><<<fgrid, kBlock, 0, c->stream>>>(w, n_layers, o.counts);
+    else k_finish<false><<<fgrid, kBlock, 0, c->stream>>>(w, n_layers, nullptr);
     TIER_HIP(c, hipGetLastError());
     return TIER_OK;
+}
+
+wide_t make_wide(tier_ctx *c, const int32_t *seeds, int64_t n_seeds_total, int32_t batch_size, int32_t n_slots,
+                 int32_t *nodes, int64_t nodes_stride)
+{
+    wide_t w = {};
+    w.seeds = seeds;
+    w.n_seeds_total = n_seeds_total;
+    w.batch_size = batch_size;
+    w.n_slots = n_slots;
+    w.n_nodes = c->n_nodes;
+    w.n_words = c->n_words;
+    w.nodes = nodes;
+    w.nodes_stride = nodes_stride;
+    w.local_idx = c->local_idx;
+    w.bitmap = c->bitmap;
+    w.meta = c->meta;
+    w.partial_hop = c->partial_hop;
+    w.partial_bm = c->partial_bm;
+    return w;
 }
 
 int ensure_i32(tier_ctx *c, int32_t **buf, int64_t *cap, int64_t want)
@@ -416,37 +500,67 @@ int check_fanouts(const int32_t *fanouts, int n_layers)
 
 extern "C" {
 
-int tier_sample_minibatch(tier_ctx *ctx, const int32_t *seeds, int32_t n_seeds, const int32_t *fanouts,
-                          int32_t n_layers, uint64_t seed, tier_blocks *out)
+int tier_max_batches(const tier_ctx *ctx) { return ctx ? ctx->n_slots : 0; }
+
+int tier_sample_minibatches(tier_ctx *ctx, const int32_t *seeds, int64_t n_seeds_total, int32_t batch_size,
+                            int32_t n_batches, const int32_t *fanouts, int32_t n_layers,
+                            const uint64_t *batch_seeds, tier_blocks_batch *out)
 {
-    if (!ctx || !out || n_seeds < 0 || (n_seeds > 0 && !seeds)) return TIER_EINVAL;
+    if (!ctx || !out || !batch_seeds || n_seeds_total < 0 || (n_seeds_total > 0 && !seeds) || batch_size < 1)
+        return TIER_EINVAL;
+    if (n_batches < 1 || n_batches > ctx->n_slots) return TIER_EINVAL;
+    if (n_seeds_total > (int64_t)batch_size * n_batches) return TIER_EINVAL;
     int rc = check_fanouts(fanouts, n_layers);
     if (rc) return rc;
+    const int64_t per_batch = n_seeds_total < batch_size ? n_seeds_total : batch_size;
     int64_t cap_nodes[TIER_MAX_LAYERS + 1], cap_edges[TIER_MAX_LAYERS];
-    rc = tier_blocks_bounds(ctx->n_nodes, n_seeds, fanouts, n_layers, cap_nodes, cap_edges);
+    rc = tier_blocks_bounds(ctx->n_nodes, per_batch, fanouts, n_layers, cap_nodes, cap_edges);
     if (rc) return rc;
-    if (n_seeds > ctx->n_nodes) return TIER_EINVAL;          // seeds are distinct
-    if (!out->nodes || out->cap_nodes < cap_nodes[n_layers]) return out->nodes ? TIER_ECAPACITY : TIER_EINVAL;
-    int64_t max_edges = 1;
-    batch_out o = {};
-    o.nodes = out->nodes;
+    if (per_batch > ctx->n_nodes) return TIER_EINVAL;          // seeds of a mini-batch are distinct
+    if (!out->nodes || !out->n_nodes || !out->n_edges) return TIER_EINVAL;
+    if (out->nodes_stride < cap_nodes[n_layers]) return TIER_ECAPACITY;
+    wide_out o = {};
     o.blocks = true;
     for (int l = 0; l < n_layers; ++l) {
         if (!out->row_ptr[l] || !out->col[l] || !out->eid[l]) return TIER_EINVAL;
-        if (out->cap_dst[l] < cap_nodes[l] || out->cap_edges[l] < cap_edges[l]) return TIER_ECAPACITY;
-        o.row_ptr[l] = out->row_ptr[l];
-        o.col[l] = out->col[l];
-        o.eid[l] = out->eid[l];
-        if (cap_edges[l] > max_edges) max_edges = cap_edges[l];
+        if (out->row_ptr_stride[l] < cap_nodes[l] + 1 || out->edge_stride[l] < cap_edges[l]) return TIER_ECAPACITY;
+        o.layer[l] = layer_out_t{out->row_ptr[l], out->row_ptr_stride[l], out->col[l], out->eid[l],
+                                 out->edge_stride[l]};
     }
-    rc = ensure_i32(ctx, &ctx->src_tmp, &ctx->cap_src_tmp, max_edges);
-    if (rc) return rc;
-    rc = enqueue_batch(ctx, seeds, n_seeds, fanouts, n_layers, seed, cap_nodes, cap_edges, o);
+    wide_t w = make_wide(ctx, seeds, n_seeds_total, batch_size, n_batches, out->nodes, out->nodes_stride);
+    for (int s = 0; s < n_batches; ++s) {
+        w.key0[s] = (uint32_t)batch_seeds[s];
+        w.key1[s] = (uint32_t)(batch_seeds[s] >> 32);
+    }
+    rc = enqueue_wide(ctx, w, fanouts, n_layers, cap_nodes, cap_edges, o);
     if (rc) return rc;
     rc = tier_sync_meta(ctx);
-    for (int l = 0; l <= n_layers; ++l) out->n_nodes[l] = ctx->meta_host[META_NFRONT + l];
-    for (int l = 0; l < n_layers; ++l) out->n_edges[l] = ctx->meta_host[META_NEDGES + l];
+    for (int s = 0; s < n_batches; ++s) {
+        const int64_t *m = ctx->meta_host + (int64_t)s * META_WORDS;
+        for (int l = 0; l <= n_layers; ++l) out->n_nodes[s * (TIER_MAX_LAYERS + 1) + l] = m[META_NFRONT + l];
+        for (int l = 0; l < n_layers; ++l) out->n_edges[s * TIER_MAX_LAYERS + l] = m[META_NEDGES + l];
+    }
     return rc;
+}
+
+int tier_sample_minibatch(tier_ctx *ctx, const int32_t *seeds, int32_t n_seeds, const int32_t *fanouts,
+                          int32_t n_layers, uint64_t seed, tier_blocks *out)
+{
+    if (!out || n_seeds < 0 || n_layers < 1 || n_layers > TIER_MAX_LAYERS) return TIER_EINVAL;
+    // one mini-batch = a batch of one; the caps of tier_blocks serve as strides
+    tier_blocks_batch b = {};
+    b.nodes = out->nodes;
+    b.nodes_stride = out->cap_nodes;
+    for (int l = 0; l < n_layers; ++l) {
+        b.row_ptr[l] = out->row_ptr[l];
+        b.col[l] = out->col[l];
+        b.eid[l] = out->eid[l];
+        b.row_ptr_stride[l] = out->cap_dst[l] + 1;
+        b.edge_stride[l] = out->cap_edges[l];
+    }
+    b.n_nodes = out->n_nodes;
+    b.n_edges = out->n_edges;
+    return tier_sample_minibatches(ctx, seeds, n_seeds, n_seeds > 0 ? n_seeds : 1, 1, fanouts, n_layers, &seed, &b);
 }
 
 int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
@@ -462,22 +576,27 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
     rc = tier_blocks_bounds(ctx->n_nodes, first, fanouts, n_layers, cap_nodes, cap_edges);
     if (rc) return rc;
     if (first > ctx->n_nodes) return TIER_EINVAL;
-    rc = ensure_i32(ctx, &ctx->ps_nodes, &ctx->cap_ps_nodes, cap_nodes[n_layers] > 0 ? cap_nodes[n_layers] : 1);
+    const int64_t stride = cap_nodes[n_layers] > 0 ? cap_nodes[n_layers] : 1;
+    rc = ensure_i32(ctx, &ctx->ps_nodes, &ctx->cap_ps_nodes, stride * ctx->n_slots);
     if (rc) return rc;
 
     k_fill_u32<<<clamp_grid(ctx->n_nodes, kBlock, 4096), kBlock, 0, ctx->stream>>>(counts, ctx->n_nodes, 0u);
     k_clear_totals<<<1, 1, 0, ctx->stream>>>(ctx->meta);
-    batch_out o = {};
-    o.nodes = ctx->ps_nodes;
+    wide_out o = {};
     o.blocks = false;
     o.counts = counts;
     const int64_t n_batches = (n_train + batch_size - 1) / batch_size;
     for (int e = 0; e < epochs; ++e) {
-        for (int64_t b = 0; b < n_batches; ++b) {
+        for (int64_t b = 0; b < n_batches; b += ctx->n_slots) {
+            const int slots = (int)(n_batches - b < ctx->n_slots ? n_batches - b : ctx->n_slots);
             const int64_t lo = b * batch_size;
-            const int32_t n = (int32_t)(n_train - lo < batch_size ? n_train - lo : batch_size);
-            rc = enqueue_batch(ctx, train_ids + lo, n, fanouts, n_layers,
-                               tier_batch_seed(seed, (uint32_t)e, (uint32_t)b), cap_nodes, cap_edges, o);
+            wide_t w = make_wide(ctx, train_ids + lo, n_train - lo, batch_size, slots, ctx->ps_nodes, stride);
+            for (int s = 0; s < slots; ++s) {
+                const uint64_t bs = tier_batch_seed(seed, (uint32_t)e, (uint32_t)(b + s));
+                w.key0[s] = (uint32_t)bs;
+                w.key1[s] = (uint32_t)(bs >> 32);
+            }
+            rc = enqueue_wide(ctx, w, fanouts, n_layers, cap_nodes, cap_edges, o);
             if (rc) return rc;
         }
     }

@@ -30,23 +30,22 @@ struct tier_ctx {
     const int32_t *indices;
     const uint8_t *host_rows;
     int64_t row_bytes;
-    // per-node scratch
-    int32_t *local_idx;      // n_nodes; -1 = not in the current frontier
-    uint32_t *bitmap;        // ceil(n_nodes / 32) words; all zero between hops
-    int64_t n_words;
+    // per-node scratch, one copy per slot (mini-batch sampled side by side)
+    int n_slots;
+    int32_t *local_idx;      // [n_slots][n_nodes]; -1 = not in the slot's current frontier
+    uint32_t *bitmap;        // [n_slots][n_words]; all zero between hops
+    int64_t n_words;         // ceil(n_nodes / 32)
     // placement
     int32_t *slot;           // n_nodes
     uint8_t *cache;          // n_hot * row_bytes
     int64_t n_hot;
     bool placed;
     // sampler scratch
-    int64_t *meta;           // device, META_WORDS
+    int64_t *meta;           // device, [n_slots][META_WORDS]; slot 0 also holds totals, error flag, hit counter
     int64_t *meta_host;      // pinned mirror
-    int32_t *partial_hop;    // TIER_SCAN_BLOCKS
-    int32_t *partial_bm;     // TIER_SCAN_BLOCKS
-    int32_t *src_tmp;        // sampled neighbour ids of the current hop
-    int64_t cap_src_tmp;
-    int32_t *ps_nodes;       // frontier buffer used by tier_presample
+    int32_t *partial_hop;    // [n_slots][TIER_SCAN_BLOCKS]
+    int32_t *partial_bm;     // [n_slots][TIER_SCAN_BLOCKS]
+    int32_t *ps_nodes;       // frontier buffers used by tier_presample
     int64_t cap_ps_nodes;
 };
 

@@ -13,6 +13,7 @@ import torch
 
 MAX_LAYERS = 8
 MAX_FANOUT = 64
+MAX_BATCHES = 16
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtier.so")
 _lib = None
@@ -20,6 +21,7 @@ _lib = None
 EXPORTS = (
     "tier_host_alloc", "tier_host_free", "tier_blocks_bounds", "tier_create", "tier_destroy",
     "tier_presample", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
+    "tier_sample_minibatches", "tier_max_batches",
     "tier_gather_features", "tier_strerror", "tier_last_hip_error",
 )
 
@@ -47,6 +49,14 @@ class _Blocks(C.Structure):
                 ("n_nodes", C.c_int64 * (MAX_LAYERS + 1)), ("n_edges", C.c_int64 * MAX_LAYERS)]
 
 
+class _BlocksBatch(C.Structure):
+    _fields_ = [("nodes", C.c_void_p), ("nodes_stride", C.c_int64),
+                ("row_ptr", C.c_void_p * MAX_LAYERS), ("col", C.c_void_p * MAX_LAYERS),
+                ("eid", C.c_void_p * MAX_LAYERS),
+                ("row_ptr_stride", C.c_int64 * MAX_LAYERS), ("edge_stride", C.c_int64 * MAX_LAYERS),
+                ("n_nodes", C.POINTER(C.c_int64)), ("n_edges", C.POINTER(C.c_int64))]
+
+
 class _Stats(C.Structure):
     _fields_ = [("hit_rows", C.c_int64), ("miss_rows", C.c_int64)]
 
@@ -69,6 +79,9 @@ def _load():
         lib.tier_place.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, i64p]
         lib.tier_sample_minibatch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, i32p, C.c_int32, C.c_uint64,
                                               C.POINTER(_Blocks)]
+        lib.tier_sample_minibatches.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, i32p,
+                                                C.c_int32, C.POINTER(C.c_uint64), C.POINTER(_BlocksBatch)]
+        lib.tier_max_batches.argtypes = [C.c_void_p]
         lib.tier_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(_Stats)]
         lib.tier_strerror.argtypes = [C.c_int]; lib.tier_strerror.restype = C.c_char_p
         lib.tier_last_hip_error.argtypes = [C.c_void_p]
@@ -243,6 +256,62 @@ def tier_sample_minibatch(ctx: Context, seeds: torch.Tensor, fanouts, seed: int,
     _check(rc, "tier_sample_minibatch")
     blocks.n_nodes = list(blocks._c.n_nodes[: L + 1])
     blocks.n_edges = list(blocks._c.n_edges[:L])
+    return blocks
+
+
+class BlocksBatch:
+    """Device buffers for the blocks of up to ``n_batches`` mini-batches sampled by one
+    call: every array has a leading mini-batch dimension, sized to the upper bounds."""
+
+    def __init__(self, n_graph_nodes: int, batch_size: int, fanouts, n_batches: int, device):
+        self.fanouts = tuple(int(k) for k in fanouts)
+        self.n_batches = n_batches
+        L = len(self.fanouts)
+        cn, ce = tier_blocks_bounds(n_graph_nodes, batch_size, self.fanouts)
+        self.cap_nodes, self.cap_edges = cn, ce
+        B = n_batches
+        self.nodes = torch.empty((B, max(cn[L], 1)), dtype=torch.int32, device=device)
+        self.row_ptr = [torch.empty((B, cn[l] + 1), dtype=torch.int32, device=device) for l in range(L)]
+        self.col = [torch.empty((B, max(ce[l], 1)), dtype=torch.int32, device=device) for l in range(L)]
+        self.eid = [torch.empty((B, max(ce[l], 1)), dtype=torch.int64, device=device) for l in range(L)]
+        self._nn = (C.c_int64 * (B * (MAX_LAYERS + 1)))()
+        self._ne = (C.c_int64 * (B * MAX_LAYERS))()
+        self.n_nodes = [[0] * (L + 1) for _ in range(B)]
+        self.n_edges = [[0] * L for _ in range(B)]
+        s = _BlocksBatch()
+        s.nodes = self.nodes.data_ptr(); s.nodes_stride = self.nodes.shape[1]
+        for l in range(L):
+            s.row_ptr[l] = self.row_ptr[l].data_ptr(); s.col[l] = self.col[l].data_ptr()
+            s.eid[l] = self.eid[l].data_ptr()
+            s.row_ptr_stride[l] = self.row_ptr[l].shape[1]; s.edge_stride[l] = self.col[l].shape[1]
+        s.n_nodes = C.cast(self._nn, C.POINTER(C.c_int64)); s.n_edges = C.cast(self._ne, C.POINTER(C.c_int64))
+        self._c = s
+
+    def frontier(self, b: int, l: int = None) -> torch.Tensor:
+        l = len(self.fanouts) if l is None else l
+        return self.nodes[b, : self.n_nodes[b][l]]
+
+
+def tier_max_batches(ctx: Context) -> int:
+    return int(_load().tier_max_batches(ctx.handle))
+
+
+def tier_sample_minibatches(ctx: Context, seeds: torch.Tensor, batch_size: int, batch_seeds, fanouts,
+                            blocks: BlocksBatch = None) -> BlocksBatch:
+    """Mini-batch s takes seeds[s*batch_size:(s+1)*batch_size] and samples with batch_seeds[s]."""
+    B = len(batch_seeds)
+    if blocks is None:
+        blocks = BlocksBatch(ctx.n_nodes, batch_size, fanouts, B, seeds.device)
+    if B > blocks.n_batches:
+        raise ValueError("more mini-batches than the buffers hold")
+    fan, L = _fan(fanouts)
+    bs = (C.c_uint64 * B)(*[int(x) for x in batch_seeds])
+    rc = _load().tier_sample_minibatches(ctx.handle, _dev(seeds, torch.int32, "seeds"), seeds.numel(), batch_size, B,
+                                         fan, L, bs, C.byref(blocks._c))
+    _check(rc, "tier_sample_minibatches")
+    for s in range(B):
+        blocks.n_nodes[s] = list(blocks._nn[s * (MAX_LAYERS + 1): s * (MAX_LAYERS + 1) + L + 1])
+        blocks.n_edges[s] = list(blocks._ne[s * MAX_LAYERS: s * MAX_LAYERS + L])
     return blocks
 
 

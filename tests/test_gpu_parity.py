@@ -130,6 +130,36 @@ def test_blocks_bad_arguments(small):
     compare_blocks(small, np.arange(10, dtype=np.int32), (3,), 1)             # context still good
 
 
+@pytest.mark.parametrize("fanouts,batch_size,n_total", [((10, 5), 100, 1570), ((4, 3, 2), 64, 64 * 16), ((15,), 333, 400),
+                                                        ((25, 15), 128, 5)])
+def test_batched_sampling_matches_oracle(small, fanouts, batch_size, n_total):
+    """Several mini-batches in one call: each equals the oracle's mini-batch for its
+    seeds and its seed (ragged last batch, empty trailing batches included)."""
+    B = tier.tier_max_batches(small.ctx)
+    assert 1 <= B <= tier.MAX_BATCHES
+    n_total = min(n_total, B * batch_size)
+    rng = np.random.default_rng(n_total)
+    seeds = rng.choice(small.n, n_total, replace=False).astype(np.int32)
+    bseeds = [tier.tier_batch_seed(77, 0, b) for b in range(B)]
+    got = tier.tier_sample_minibatches(small.ctx, torch.from_numpy(seeds).to(DEV), batch_size, bseeds, fanouts)
+    L = len(fanouts)
+    for b in range(B):
+        want = orc.sample_minibatch(small.indptr, small.indices, seeds[b * batch_size:(b + 1) * batch_size], fanouts,
+                                    bseeds[b], local_idx=small.local_idx)
+        assert got.n_nodes[b] == want["n_nodes"].tolist() and got.n_edges[b] == want["n_edges"].tolist(), b
+        assert np.array_equal(got.frontier(b).cpu().numpy(), want["nodes"])
+        for l in range(L):
+            nd, ne = got.n_nodes[b][l], got.n_edges[b][l]
+            assert np.array_equal(got.row_ptr[l][b, : nd + 1].cpu().numpy(), want["row_ptr"][l])
+            assert np.array_equal(got.eid[l][b, :ne].cpu().numpy(), want["eid"][l])
+            assert np.array_equal(got.col[l][b, :ne].cpu().numpy(), want["col"][l])
+    with pytest.raises(tier.TierError):                              # more seeds than the batches hold
+        tier.tier_sample_minibatches(small.ctx, torch.arange(50, dtype=torch.int32, device=DEV), 10, bseeds[:2], (3,))
+    with pytest.raises(tier.TierError):
+        tier.tier_sample_minibatches(small.ctx, torch.arange(50, dtype=torch.int32, device=DEV), 10,
+                                     [1] * (B + 1), (3,), tier.BlocksBatch(small.n, 10, (3,), B + 1, DEV))
+
+
 def test_blocks_large_frontier_spans_many_tiles():
     """Frontier above 1024 blocks x 256 nodes, so blocks walk several tiles."""
     say("large frontier")
