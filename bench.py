@@ -40,8 +40,10 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--budget", type=float, default=None, help="override: fraction of feature bytes kept in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-streams", action="store_true", help="skip the all-hit / all-miss gather runs")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink nodes, edges and budget alike")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference for profiler byte counters)")
+                    help="also run one plain 1 GiB streaming kernel (reference for profiler byte counters)")
     ap.add_argument("--cpu-batches", type=int, default=192, help="mini-batches in the CPU baseline's sample")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -58,20 +60,28 @@ def main():
     torch.cuda.set_device(dev)
     wl = synth.WORKLOADS[args.workload]
     t0 = time.time()
-    indptr, indices, train = synth.make_graph(wl, dev)
+    dtype = torch.float32 if wl.dtype == "float32" else torch.float16
+    scale = args.scale
+    try:
+        table = tier.tier_host_alloc(max(64, int(wl.n_nodes * scale)), wl.dim, dtype)
+    except tier.TierError as e:
+        # the host refuses to pin that much memory: same recipe at 2/3 of the size
+        scale = scale * 0.66
+        log(f"[bench] {wl.feature_bytes * args.scale / 2**30:.1f} GiB of pinned host memory refused ({e}); "
+            f"running at scale {scale}")
+        table = tier.tier_host_alloc(max(64, int(wl.n_nodes * scale)), wl.dim, dtype)
+    indptr, indices, train = synth.make_graph(wl, dev, scale)
     torch.cuda.synchronize()
     n = indptr.numel() - 1
     log(f"[bench] {wl.name}: {n} nodes, {indices.numel()} edges, {train.numel()} train nodes "
         f"({time.time() - t0:.1f}s to generate)")
-    dtype = torch.float32 if wl.dtype == "float32" else torch.float16
-    table = tier.tier_host_alloc(n, wl.dim, dtype)
     synth.fill_features(table.tensor, wl.dist, synth.GRAPH_SEED + 2, dev)
     torch.cuda.synchronize()
     log(f"[bench] features: {table.nbytes / 1e9:.2f} GB pinned ({time.time() - t0:.1f}s)")
 
     ctx = tier.tier_create(indptr, indices, table)
     R = ctx.row_bytes
-    budget = wl.budget_bytes(args.budget)
+    budget = int(wl.budget_bytes(args.budget) * scale)
     n_train = train.numel()
     bs = wl.batch_size
     n_batches = -(-n_train // bs)
@@ -123,6 +133,13 @@ def main():
             record["gather_launches"] = len(g_pairs)
         return rows, edges
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)       # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        torch.bitwise_not(src, out=dst)                                # a plain streaming kernel, by name in the trace
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step(None)
     rec = {"presample_ms": [], "place_ms": [], "sample_ms": [], "gather_ms": []}
@@ -163,7 +180,7 @@ def main():
         "bound": "hbm", "kernel": "k_gather", "achieved": round(achieved, 2),
         "peak": round(peak_time_additive, 2), "unit": "GB/s",
         "frac": round(achieved / peak_time_additive, 4) if peak_time_additive else None,
-        "traffic": None,
+        "traffic": measured_traffic(wl.name) if scale == 1.0 and args.budget is None else None,
         "peak_model": "time-additive blend: (2R+8) / (((1+h)R+8)/HBM + (1-h)R/link), HBM 8000 GB/s, host link 64 GB/s",
         "hit_fraction": round(h, 4),
         "avg_launch_ms": round(avg_launch_ms, 4), "launches_per_step": launches,
@@ -174,6 +191,30 @@ def main():
         "arithmetic_blend_frac": round(gathered_bytes / (gather_ms * 1e-3) / 1e9 / peak_arithmetic, 4) if gather_ms else None,
     }
 
+    # the two streams on their own: every row from HBM, then every row over the host link
+    streams = None
+    if not args.no_streams:
+        streams = {}
+        for name, bud in (("all_hit", n * R), ("all_miss", 0)):
+            tier.tier_place(ctx, counts, bud, want_slot_map=False)
+            ms = 0.0; nrows = 0; nl = 0
+            for g in groups[:4]:
+                blk = sample_group(g)
+                for i in range(len(g)):
+                    a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(); tier.tier_gather_features(ctx, blk.frontier(i), out); b_.record()
+                    torch.cuda.synchronize()
+                    ms += a.elapsed_time(b_); nrows += blk.n_nodes[i][L]; nl += 1
+            if name == "all_hit":
+                streams[name] = {"hbm_GBps": round(nrows * alg_bytes_row / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak":
+                                 round(nrows * alg_bytes_row / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                 "avg_launch_ms": round(ms / nl, 4), "launches": nl}
+            else:
+                streams[name] = {"host_link_GBps": round(nrows * R / (ms * 1e-3) / 1e9, 2), "frac_of_link_peak":
+                                 round(nrows * R / (ms * 1e-3) / 1e9 / LINK_PEAK_GBPS, 4),
+                                 "avg_launch_ms": round(ms / nl, 4), "launches": nl}
+        roofline["streams"] = streams
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(args, wl, indptr, indices, train, epoch_ids, table, budget, bseed)
@@ -183,7 +224,7 @@ def main():
         "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: {wl.graph} graph, {n} nodes, {indices.numel()} edges, "
+        "config": {"workload": f"{wl.name}{'' if scale == 1.0 else f' at scale {scale:g}'}: {wl.graph} graph, {n} nodes, {indices.numel()} edges, "
                                f"{wl.dim} x {wl.dtype} features, fanout {list(wl.fanouts)}, batch {bs}, "
                                f"{n_batches} mini-batches per epoch sampled {B} per call, HBM budget {budget} B ({rec['n_hot']} rows)"},
         "sampled_edges_per_s": round(edges / (sample_ms * 1e-3)) if sample_ms else None,
@@ -235,6 +276,20 @@ def cpu_baseline(args, wl, indptr, indices, train, epoch_ids, table, budget, bse
             "sample": f"first {nb} of the mini-batches: presample of {nb} batches, placement of all {n} nodes, "
                       f"then sample + gather of {nb} batches; {dt:.1f} s wall on {threads} threads",
             "seconds": round(dt, 2)}
+
+
+def measured_traffic(workload):
+    """HBM bytes per gather launch measured with rocprofv3 counters (FETCH_SIZE and
+    WRITE_SIZE runs of this script, scaled by a plain copy of known size); read from
+    the committed summary of those runs, None when there is none for the workload."""
+    path = os.path.join(ROOT, "profiles", f"gather_{workload}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def synth_seed(which):
