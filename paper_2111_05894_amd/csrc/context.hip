@@ -117,6 +117,7 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     (void)hipFree(ctx->local_idx);
     (void)hipFree(ctx->bitmap);
+    (void)hipFree(ctx->summary);
     (void)hipFree(ctx->slot);
     (void)hipFree(ctx->cache);
     (void)hipFree(ctx->meta);
@@ -148,13 +149,15 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
 
     const int64_t n = c->n_nodes;
     c->n_words = (n + 31) / 32;
+    c->n_sum = (c->n_words + 31) / 32;
     // as many mini-batch slots as fit in 4 GiB of per-node scratch
-    const int64_t per_slot = (n + c->n_words + 1) * 4;
+    const int64_t per_slot = (n + c->n_words + c->n_sum + 1) * 4;
     int64_t slots = (4LL << 30) / per_slot;
     c->n_slots = (int)(slots < 1 ? 1 : (slots > TIER_MAX_BATCHES ? TIER_MAX_BATCHES : slots));
     const size_t S = (size_t)c->n_slots;
     TIER_HIP(c, hipMalloc(&c->local_idx, S * (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->bitmap, S * (size_t)(c->n_words > 0 ? c->n_words : 1) * sizeof(uint32_t)));
+    TIER_HIP(c, hipMalloc(&c->summary, S * (size_t)(c->n_sum > 0 ? c->n_sum : 1) * sizeof(uint32_t)));
     TIER_HIP(c, hipMalloc(&c->slot, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->meta, S * META_WORDS * sizeof(int64_t)));
     TIER_HIP(c, hipHostMalloc((void **)&c->meta_host, S * META_WORDS * sizeof(int64_t), hipHostMallocDefault));
@@ -163,6 +166,8 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     k_fill_i32<<<grid_for(n * (int64_t)S, 256, 8192), 256, 0, c->stream>>>(c->local_idx, n * (int64_t)S, -1);
     k_fill_i32<<<grid_for(c->n_words * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->bitmap,
                                                                                   c->n_words * (int64_t)S, 0);
+    k_fill_i32<<<grid_for(c->n_sum * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->summary,
+                                                                                c->n_sum * (int64_t)S, 0);
     k_fill_i32<<<4, 256, 0, c->stream>>>((int32_t *)c->meta, (int64_t)S * META_WORDS * 2, 0);
     TIER_HIP(c, hipGetLastError());
 

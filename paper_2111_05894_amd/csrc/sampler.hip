@@ -15,10 +15,13 @@
 //                   draw i, the Floyd collision rule is resolved with in-group
 //                   shuffles; every neighbour not yet in the frontier sets its
 //                   bit in a bitmap over all nodes
-//   k_bm_partial    popcounts of the bitmap
+//   k_bm_partial    popcounts of the bitmap, visiting only its non-zero words: a
+//                   summary bitmap holds one bit per bitmap word (set by whoever
+//                   sets the first bit of that word), so the cost follows the
+//                   mini-batch, not the graph
 //   k_bm_emit       bitmap -> ascending list of new nodes appended to the
 //                   frontier (dedup and sort in one pass), their frontier index
-//                   recorded in local_idx[], bitmap cleared
+//                   recorded in local_idx[], both bitmaps cleared
 //   k_relabel       once per mini-batch, all hops: col[e] = frontier index of
 //                   the sampled neighbour (col[] held its node id until then)
 //
@@ -43,10 +46,12 @@ struct wide_t {
     int32_t n_slots;
     int64_t n_nodes;             // graph nodes
     int64_t n_words;             // bitmap words per slot
+    int64_t n_sum;               // summary words per slot (one bit per bitmap word)
     int32_t *nodes;              // slot s: nodes + s * nodes_stride
     int64_t nodes_stride;
     int32_t *local_idx;          // [slot][n_nodes]
     uint32_t *bitmap;            // [slot][n_words]
+    uint32_t *summary;           // [slot][n_sum]
     int64_t *meta;               // [slot][META_WORDS]; totals and the error flag live in slot 0
     int32_t *partial_hop;        // [slot][TIER_SCAN_BLOCKS]
     int32_t *partial_bm;         // [slot][TIER_SCAN_BLOCKS]
@@ -71,6 +76,7 @@ struct slot_view {
     int32_t *nodes;
     int32_t *local_idx;
     uint32_t *bitmap;
+    uint32_t *summary;
     int64_t *meta;
     int32_t *partial_hop;
     int32_t *partial_bm;
@@ -83,6 +89,7 @@ __device__ inline slot_view view_of(const wide_t &w)
     v.nodes = w.nodes + s * w.nodes_stride;
     v.local_idx = w.local_idx + s * w.n_nodes;
     v.bitmap = w.bitmap + s * w.n_words;
+    v.summary = w.summary + s * w.n_sum;
     v.meta = w.meta + s * META_WORDS;
     v.partial_hop = w.partial_hop + s * TIER_SCAN_BLOCKS;
     v.partial_bm = w.partial_bm + s * TIER_SCAN_BLOCKS;
@@ -230,11 +237,12 @@ __global__ __launch_bounds__(kBlock) void k_hop_rowptr(wide_t w, const OffT *__r
 // d <= k: all neighbours in adjacency order.  d > k: Floyd's subset algorithm, draw i
 // on lane i: t_i uniform in [0, d-k+i]; position = t_i unless an earlier draw already
 // took t_i, then d-k+i.
-template <int G, bool BLOCKS, typename OffT>
+template <int G, bool BLOCKS, bool TWO_LEVEL, typename OffT>
 __device__ inline void sample_one(int lane, int32_t v, OffT beg, int32_t d, int k, int layer, uint32_t key0,
                                   uint32_t key1, const int32_t *__restrict__ indices,
                                   const int32_t *__restrict__ local_idx, uint32_t *__restrict__ bitmap,
-                                  int64_t *__restrict__ eid, int32_t *__restrict__ col, int32_t rp)
+                                  uint32_t *__restrict__ summary, int64_t *__restrict__ eid,
+                                  int32_t *__restrict__ col, int32_t rp)
 {
     const bool draw = d > k;
     const int cnt = draw ? k : d;
@@ -261,12 +269,20 @@ __device__ inline void sample_one(int lane, int32_t v, OffT beg, int32_t d, int 
             eid[rp + lane] = (int64_t)e;
             col[rp + lane] = u;                     // node id for now; k_relabel turns it into an index
         }
-        if (local_idx[u] < 0) atomicOr(&bitmap[u >> 5], 1u << (u & 31));
+        if (local_idx[u] < 0) {
+            const uint32_t word = (uint32_t)u >> 5;
+            if (TWO_LEVEL) {
+                if (atomicOr(&bitmap[word], 1u << (u & 31)) == 0u)  // first bit of this word
+                    atomicOr(&summary[word >> 5], 1u << (word & 31));
+            } else {
+                atomicOr(&bitmap[word], 1u << (u & 31));
+            }
+        }
     }
 }
 
 // One group of G lanes per dst node, all dst nodes of the frontier side by side.
-template <typename OffT, int G, bool BLOCKS>
+template <typename OffT, int G, bool BLOCKS, bool TWO_LEVEL>
 __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, const OffT *__restrict__ indptr,
                                                        const int32_t *__restrict__ indices, int layer, int k,
                                                        layer_out_t o)
@@ -290,8 +306,8 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, const OffT *__r
         int32_t rp = 0;
         if (BLOCKS) rp = row_ptr[i];
         else if (lane == 0) edges += d < k ? d : k;
-        sample_one<G, BLOCKS, OffT>(lane, u, beg, d, k, layer, key0, key1, indices, v.local_idx, v.bitmap, eid, col,
-                                    rp);
+        sample_one<G, BLOCKS, TWO_LEVEL, OffT>(lane, u, beg, d, k, layer, key0, key1, indices, v.local_idx, v.bitmap, v.summary,
+                                    eid, col, rp);
     }
     if (!BLOCKS) {
         int tot = block_sum(edges, s_wave);
@@ -300,7 +316,72 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, const OffT *__r
     }
 }
 
+// Each thread owns one summary word = 32 bitmap words = 1024 node ids.
 __global__ __launch_bounds__(kBlock) void k_bm_partial(wide_t w)
+{
+    __shared__ int s_wave[kBlock / 64];
+    const slot_view v = view_of(w);
+    int64_t lo, hi;
+    block_range(w.n_sum, lo, hi);
+    int sum = 0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
+        uint32_t live = v.summary[i];
+        while (live) {
+            int j = __ffs(live) - 1;
+            live &= live - 1;
+            sum += __popc(v.bitmap[i * 32 + j]);
+        }
+    }
+    int tot = block_sum(sum, s_wave);
+    if (threadIdx.x == 0) v.partial_bm[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int layer)
+{
+    __shared__ int s_wave[kBlock / 64];
+    const slot_view v = view_of(w);
+    int64_t lo, hi;
+    block_range(w.n_sum, lo, hi);
+    int carry, all;
+    partial_prefix(v.partial_bm, carry, all, s_wave);
+    const int64_t base = v.meta[META_NFRONT + layer];
+    if (blockIdx.x == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all;
+    for (int64_t tile = lo; tile < hi; tile += kBlock) {
+        const int64_t i = tile + threadIdx.x;
+        const uint32_t live0 = i < hi ? v.summary[i] : 0u;
+        int cnt = 0;
+        for (uint32_t live = live0; live;) {
+            int j = __ffs(live) - 1;
+            live &= live - 1;
+            cnt += __popc(v.bitmap[i * 32 + j]);
+        }
+        int tot;
+        int64_t pos = base + carry + block_excl_scan(cnt, tot, s_wave);
+        carry += tot;
+        if (live0) {
+            v.summary[i] = 0u;
+            for (uint32_t live = live0; live;) {
+                int j = __ffs(live) - 1;
+                live &= live - 1;
+                const int64_t word = i * 32 + j;
+                uint32_t bits = v.bitmap[word];
+                v.bitmap[word] = 0u;
+                while (bits) {
+                    int b = __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    int32_t u = (int32_t)(word * 32 + b);
+                    v.nodes[pos] = u;
+                    v.local_idx[u] = (int32_t)pos;
+                    ++pos;
+                }
+            }
+        }
+    }
+}
+
+// Flat variant for graphs whose whole bitmap is cheap to walk: every thread owns one
+// bitmap word, no summary is kept.
+__global__ __launch_bounds__(kBlock) void k_bm_partial_flat(wide_t w)
 {
     __shared__ int s_wave[kBlock / 64];
     const slot_view v = view_of(w);
@@ -312,7 +393,7 @@ __global__ __launch_bounds__(kBlock) void k_bm_partial(wide_t w)
     if (threadIdx.x == 0) v.partial_bm[blockIdx.x] = tot;
 }
 
-__global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int layer)
+__global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int layer)
 {
     __shared__ int s_wave[kBlock / 64];
     const slot_view v = view_of(w);
@@ -398,15 +479,28 @@ struct wide_out {             // where the mini-batches' results go
     uint32_t *counts;         // non-null: count the final frontiers
 };
 
-template <typename OffT, int G>
-void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, const wide_out &o)
+// The summary bitmap pays off once walking the whole bitmap costs more than the
+// returning atomics it needs: above 2^20 bitmap words (32 M nodes).
+bool two_level(const tier_ctx *c) { return c->n_words > (1 << 20); }
+
+template <typename OffT, int G, bool TWO_LEVEL>
+void launch_hop_sample2(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, const wide_out &o)
 {
     const OffT *ip = (const OffT *)c->indptr;
     const dim3 grid(clamp_grid(cap_dst, kBlock / G, 16384), w.n_slots);
     if (o.blocks)
-        k_hop_sample<OffT, G, true><<<grid, kBlock, 0, c->stream>>>(w, ip, c->indices, layer, k, o.layer[layer]);
+        k_hop_sample<OffT, G, true, TWO_LEVEL><<<grid, kBlock, 0, c->stream>>>(w, ip, c->indices, layer, k,
+                                                                               o.layer[layer]);
     else
-        k_hop_sample<OffT, G, false><<<grid, kBlock, 0, c->stream>>>(w, ip, c->indices, layer, k, layer_out_t{});
+        k_hop_sample<OffT, G, false, TWO_LEVEL><<<grid, kBlock, 0, c->stream>>>(w, ip, c->indices, layer, k,
+                                                                                layer_out_t{});
+}
+
+template <typename OffT, int G>
+void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, const wide_out &o)
+{
+    if (two_level(c)) launch_hop_sample2<OffT, G, true>(c, w, cap_dst, layer, k, o);
+    else launch_hop_sample2<OffT, G, false>(c, w, cap_dst, layer, k, o);
 }
 
 template <typename OffT>
@@ -431,12 +525,19 @@ int enqueue_wide(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_lay
 {
     const unsigned slots = (unsigned)w.n_slots;
     k_init_seeds<<<dim3(clamp_grid(w.batch_size, kBlock, 1 << 20), slots), kBlock, 0, c->stream>>>(w);
-    const dim3 bm_grid(clamp_grid(c->n_words, 4 * kBlock, TIER_SCAN_BLOCKS), slots);
+    const bool tl = two_level(c);
+    const dim3 bm_grid(tl ? clamp_grid(c->n_sum, kBlock, TIER_SCAN_BLOCKS)
+                          : clamp_grid(c->n_words, 4 * kBlock, TIER_SCAN_BLOCKS), slots);
     for (int l = 0; l < n_layers; ++l) {
         if (c->indptr_i64) launch_hop<int64_t>(c, w, cap_nodes[l], l, fanouts[l], o);
         else launch_hop<int32_t>(c, w, cap_nodes[l], l, fanouts[l], o);
-        k_bm_partial<<<bm_grid, kBlock, 0, c->stream>>>(w);
-        k_bm_emit<<<bm_grid, kBlock, 0, c->stream>>>(w, l);
+        if (tl) {
+            k_bm_partial<<<bm_grid, kBlock, 0, c->stream>>>(w);
+            k_bm_emit<<<bm_grid, kBlock, 0, c->stream>>>(w, l);
+        } else {
+            k_bm_partial_flat<<<bm_grid, kBlock, 0, c->stream>>>(w);
+            k_bm_emit_flat<<<bm_grid, kBlock, 0, c->stream>>>(w, l);
+        }
     }
     if (o.blocks) {
         relabel_t r = {};
@@ -470,6 +571,8 @@ wide_t make_wide(tier_ctx *c, const int32_t *seeds, int64_t n_seeds_total, int32
     w.nodes_stride = nodes_stride;
     w.local_idx = c->local_idx;
     w.bitmap = c->bitmap;
+    w.summary = c->summary;
+    w.n_sum = c->n_sum;
     w.meta = c->meta;
     w.partial_hop = c->partial_hop;
     w.partial_bm = c->partial_bm;

@@ -35,6 +35,8 @@ struct tier_ctx {
     int32_t *local_idx;      // [n_slots][n_nodes]; -1 = not in the slot's current frontier
     uint32_t *bitmap;        // [n_slots][n_words]; all zero between hops
     int64_t n_words;         // ceil(n_nodes / 32)
+    uint32_t *summary;       // [n_slots][n_sum]; bit j of word i set <=> bitmap word 32 i + j is non-zero
+    int64_t n_sum;           // ceil(n_words / 32)
     // placement
     int32_t *slot;           // n_nodes
     uint8_t *cache;          // n_hot * row_bytes
