@@ -63,6 +63,12 @@ def _load():
         _lib.orc_fill_cache.argtypes = [_u8p, C.c_int64, C.c_int64, _i32p, _u8p]
         _lib.orc_gather.restype = None
         _lib.orc_gather.argtypes = [_u8p, _u8p, _i32p, C.c_int64, _i32p, C.c_int64, _u8p, _i64p, _i64p]
+        _lib.orc_reorder_graph.restype = None
+        _lib.orc_reorder_graph.argtypes = [C.c_int64, _i64p, _i32p, _i32p, _i64p, _i32p]
+        _lib.orc_reorder_rows.restype = None
+        _lib.orc_reorder_rows.argtypes = [_u8p, C.c_int64, C.c_int64, _i32p, _u8p]
+        _lib.orc_gather_boundary.restype = None
+        _lib.orc_gather_boundary.argtypes = [_u8p, _u8p, C.c_int64, C.c_int64, _i32p, C.c_int64, _u8p, _i64p]
     return _lib
 
 
@@ -205,3 +211,34 @@ def gather(feat_bytes, cache, slot, ids):
     _load().orc_gather(_p(feat_bytes, _u8p), _p(cache, _u8p), _p(slot, _i32p), rb, _p(ids, _i32p),
                        ids.shape[0], _p(out, _u8p), C.byref(hit), C.byref(miss))
     return out, hit.value, miss.value
+
+
+def reorder_graph(indptr, indices, rank):
+    """Alg. 2: returns (indptr_new int64, indices_new int32) with every node renamed to rank[node]."""
+    indptr = _as(indptr, np.int64); indices = _as(indices, np.int32); rank = _as(rank, np.int32)
+    n = indptr.shape[0] - 1
+    nd_new = np.zeros(n + 1, np.int64); edg_new = np.empty(max(indices.shape[0], 1), np.int32)
+    _load().orc_reorder_graph(n, _p(indptr, _i64p), _p(indices, _i32p), _p(rank, _i32p), _p(nd_new, _i64p),
+                              _p(edg_new, _i32p))
+    return nd_new, edg_new[: indices.shape[0]]
+
+
+def reorder_rows(feat_bytes, rank):
+    assert feat_bytes.dtype == np.uint8 and feat_bytes.flags.c_contiguous
+    rank = _as(rank, np.int32)
+    out = np.empty_like(feat_bytes)
+    _load().orc_reorder_rows(_p(feat_bytes, _u8p), feat_bytes.shape[0], feat_bytes.shape[1], _p(rank, _i32p),
+                             _p(out, _u8p))
+    return out
+
+
+def gather_boundary(feat_bytes_reordered, boundary: int, ids):
+    """Hot tensor = rows [0, boundary), cold tensor = the rest, as two separate arrays."""
+    fb = feat_bytes_reordered
+    hot = np.ascontiguousarray(fb[:boundary]); cold = np.ascontiguousarray(fb[boundary:])
+    ids = _as(ids, np.int32)
+    out = np.empty((ids.shape[0], fb.shape[1]), np.uint8)
+    hit = C.c_int64(0)
+    _load().orc_gather_boundary(_p(hot, _u8p), _p(cold, _u8p), boundary, fb.shape[1], _p(ids, _i32p), ids.shape[0],
+                                _p(out, _u8p), C.byref(hit))
+    return out, hit.value

@@ -325,3 +325,56 @@ void orc_gather(const uint8_t *feat, const uint8_t *cache, const int32_t *slot,
     if (hit_rows)  *hit_rows = hit;
     if (miss_rows) *miss_rows = n - hit;
 }
+
+/* ------------------------------------------------------------------------ */
+/* Graph and feature reordering (Sec. 3.2, Alg. 2 "Parallelizable Graph      */
+/* Reordering"): every node takes its rank as its new id.  srt_idx is the    */
+/* old id -> new id map (the rank).  In the algorithm's order:               */
+/*   1. nd_new[srt_idx[i] + 1] = length of node i's neighbour list           */
+/*   2. nd_new[0] = 0, prefix sum over nd_new                                */
+/*   3. every value of the edge list is replaced by its new id               */
+/*   4. node i's list moves from nd[i] to nd_new[srt_idx[i]], order kept     */
+/* Reading: the printed last loop indexes nd_new with the old id i; the text */
+/* ("identify the location of old neighbor list using nd and place to the    */
+/* new location using nd_new") fixes the new location as that of the new id. */
+/* ------------------------------------------------------------------------ */
+void orc_reorder_graph(int64_t n, const int64_t *nd, const int32_t *edg, const int32_t *srt_idx,
+                       int64_t *nd_new, int32_t *edg_new)
+{
+    int64_t n_edges = nd[n];
+    int32_t *relabelled = (int32_t *)malloc((size_t)(n_edges > 0 ? n_edges : 1) * sizeof(int32_t));
+    for (int64_t i = 0; i < n; ++i) nd_new[srt_idx[i] + 1] = nd[i + 1] - nd[i];
+    nd_new[0] = 0;
+    for (int64_t i = 0; i < n; ++i) nd_new[i + 1] += nd_new[i];
+    for (int64_t e = 0; e < n_edges; ++e) relabelled[e] = srt_idx[edg[e]];
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t len = nd[i + 1] - nd[i];
+        for (int64_t j = 0; j < len; ++j) edg_new[nd_new[srt_idx[i]] + j] = relabelled[nd[i] + j];
+    }
+    free(relabelled);
+}
+
+/* Feature rows follow their nodes (Sec. 3.2: the table is reordered by score). */
+void orc_reorder_rows(const uint8_t *feat, int64_t n, int64_t row_bytes, const int32_t *srt_idx,
+                      uint8_t *feat_new)
+{
+    for (int64_t i = 0; i < n; ++i)
+        memcpy(feat_new + (size_t)srt_idx[i] * (size_t)row_bytes, feat + (size_t)i * (size_t)row_bytes,
+               (size_t)row_bytes);
+}
+
+/* Tiered gather on reordered data (Sec. 4.1; Listing 1 with no peer GPUs): ids below */
+/* the boundary index the hot tensor, the others index the cold tensor by their       */
+/* offset from the boundary.                                                          */
+void orc_gather_boundary(const uint8_t *hot, const uint8_t *cold, int64_t boundary, int64_t row_bytes,
+                         const int32_t *ids, int64_t n, uint8_t *out, int64_t *hit_rows)
+{
+    int64_t hit = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const uint8_t *row;
+        if (ids[i] < boundary) { row = hot + (size_t)ids[i] * (size_t)row_bytes; ++hit; }
+        else                   { row = cold + (size_t)(ids[i] - boundary) * (size_t)row_bytes; }
+        memcpy(out + (size_t)i * (size_t)row_bytes, row, (size_t)row_bytes);
+    }
+    if (hit_rows) *hit_rows = hit;
+}

@@ -12,15 +12,18 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kRowsInFlight = 4;
 
-// TIERED = false is the untiered copy (every row from host memory) that fills the
-// HBM cache at placement time.
-template <int LPR, bool TIERED>
+// MODE: GATHER_SLOT     hot <=> slot[id] >= 0, cache row = slot[id]      (ids keep their meaning)
+//       GATHER_BOUNDARY hot <=> id < n_hot, cache row = id, cold row = id - n_hot of the cold
+//                       part (rows in rank order: the two-way branch of Listing 1)
+//       GATHER_HOST     every row from host memory: the untiered copy that fills the HBM
+//                       cache at placement time
+template <int LPR, int MODE>
 __global__ __launch_bounds__(kBlock) void k_gather(const int32_t *__restrict__ ids, int64_t n,
                                                    const int32_t *__restrict__ slot,
                                                    const uint4 *__restrict__ cache,
                                                    const uint4 *__restrict__ host,
                                                    uint4 *__restrict__ out, int cpr, int64_t n_nodes,
-                                                   int64_t *__restrict__ meta, int count_hits)
+                                                   int64_t n_hot, int64_t *__restrict__ meta, int count_hits)
 {
     constexpr int kGroups = kBlock / LPR;
     const int lane = threadIdx.x % LPR;
@@ -40,10 +43,15 @@ __global__ __launch_bounds__(kBlock) void k_gather(const int32_t *__restrict__ i
                 if ((uint32_t)id >= (uint64_t)n_nodes) {
                     bad = 1;                       // row of zeros, error reported by the host
                 } else {
-                    int32_t s = TIERED ? slot[id] : -1;
+                    int32_t s = -1;
+                    if (MODE == GATHER_SLOT) s = slot[id];
+                    if (MODE == GATHER_BOUNDARY) s = id < n_hot ? id : -1;
                     if (s >= 0) {
                         src[j] = cache + (int64_t)s * cpr;
                         hits += (lane == 0);
+                    } else if (MODE == GATHER_BOUNDARY) {
+                        const uint4 *cold = host + n_hot * cpr;          // first row of the cold part
+                        src[j] = cold + ((int64_t)id - n_hot) * cpr;
                     } else {
                         src[j] = host + (int64_t)id * cpr;
                     }
@@ -74,8 +82,7 @@ __global__ void k_clear_hits(int64_t *meta) { meta[META_HIT_ROWS] = 0; }
 
 }  // namespace
 
-int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, const int32_t *slot,
-                       const uint8_t *cache, void *out, bool count_hits)
+int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, void *out, bool count_hits)
 {
     if (n <= 0) return TIER_OK;
     const int cpr = (int)(ctx->row_bytes / 16);
@@ -86,16 +93,15 @@ int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, const int32
     const int64_t max_blocks = 256 * 64;
     if (blocks > max_blocks) blocks = max_blocks;
     if (count_hits) k_clear_hits<<<1, 1, 0, ctx->stream>>>(ctx->meta);
-#define GATHER_CASE(L)                                                                              \
-    case L:                                                                                         \
-        if (slot)                                                                                   \
-            k_gather<L, true><<<(int)blocks, kBlock, 0, ctx->stream>>>(                             \
-                ids, n, slot, (const uint4 *)cache, (const uint4 *)ctx->host_rows, (uint4 *)out,    \
-                cpr, ctx->n_nodes, ctx->meta, count_hits ? 1 : 0);                                  \
-        else                                                                                        \
-            k_gather<L, false><<<(int)blocks, kBlock, 0, ctx->stream>>>(                            \
-                ids, n, nullptr, nullptr, (const uint4 *)ctx->host_rows, (uint4 *)out, cpr,         \
-                ctx->n_nodes, ctx->meta, 0);                                                        \
+#define GATHER_LAUNCH(L, M)                                                                          \
+    k_gather<L, M><<<(int)blocks, kBlock, 0, ctx->stream>>>(                                         \
+        ids, n, ctx->slot, (const uint4 *)ctx->cache, (const uint4 *)ctx->host_rows, (uint4 *)out,   \
+        cpr, ctx->n_nodes, ctx->n_hot, ctx->meta, count_hits ? 1 : 0)
+#define GATHER_CASE(L)                                                                               \
+    case L:                                                                                          \
+        if (mode == GATHER_SLOT) GATHER_LAUNCH(L, GATHER_SLOT);                                      \
+        else if (mode == GATHER_BOUNDARY) GATHER_LAUNCH(L, GATHER_BOUNDARY);                         \
+        else GATHER_LAUNCH(L, GATHER_HOST);                                                          \
         break;
     switch (lpr) {
         GATHER_CASE(8)
@@ -104,6 +110,7 @@ int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, const int32
         GATHER_CASE(64)
     }
 #undef GATHER_CASE
+#undef GATHER_LAUNCH
     TIER_HIP(ctx, hipGetLastError());
     return TIER_OK;
 }
@@ -114,7 +121,7 @@ extern "C" int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n
     if (!ctx || n < 0 || (n > 0 && (!ids || !out))) return TIER_EINVAL;
     if (((uintptr_t)out & 15u) != 0) return TIER_EINVAL;
     if (!ctx->placed) return TIER_ESTATE;
-    int rc = tier_launch_gather(ctx, ids, n, ctx->slot, ctx->cache, out, stats != nullptr);
+    int rc = tier_launch_gather(ctx, ids, n, ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT, out, stats != nullptr);
     if (rc != TIER_OK) return rc;
     if (stats) {
         stats->hit_rows = 0;

@@ -211,16 +211,13 @@ struct sort_bufs {
 
 }  // namespace
 
-extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes, int32_t *slot_map,
-                          int64_t *n_hot_out)
+// Order the node ids by (count descending, id ascending) on the context's stream.
+// *order points into b (rank -> node id) and is valid until b dies.  Waits once
+// (for the largest count, which fixes the number of radix passes).
+static int sort_by_count(tier_ctx *ctx, const uint32_t *counts, sort_bufs &b, int32_t **order_out)
 {
-    if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
     const int64_t n = ctx->n_nodes;
     hipStream_t st = ctx->stream;
-    int64_t n_hot = (int64_t)(budget_bytes / (uint64_t)ctx->row_bytes);
-    if (n_hot > n) n_hot = n;
-
-    sort_bufs b;
     TIER_HIP(ctx, hipMalloc(&b.max_dev, sizeof(uint32_t)));
     k_zero_u32<<<1, 1, 0, st>>>(b.max_dev);
     if (n > 0) k_max_u32<<<grid_for(n, 256, 2048), 256, 0, st>>>(counts, n, b.max_dev);
@@ -268,9 +265,70 @@ extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget
         }
     }
     TIER_HIP(ctx, hipGetLastError());
+    *order_out = order;
+    return TIER_OK;
+}
+
+extern "C" int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, int32_t *order)
+{
+    if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
+    const int64_t n = ctx->n_nodes;
+    sort_bufs b;
+    int32_t *ord = nullptr;
+    int rc = sort_by_count(ctx, counts, b, &ord);
+    if (rc != TIER_OK) return rc;
+    if (rank && n > 0) k_slot_map<<<grid_for(n, 256, 4096), 256, 0, ctx->stream>>>(ord, n, n, rank);
+    if (order && n > 0)
+        TIER_HIP(ctx, hipMemcpyAsync(order, ord, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, ctx->stream));
+    TIER_HIP(ctx, hipGetLastError());
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->stream));   // the sort buffers are freed on return
+    return TIER_OK;
+}
+
+extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes, int32_t *slot_map,
+                          int64_t *n_hot_out)
+{
+    if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
+    const int64_t n = ctx->n_nodes;
+    hipStream_t st = ctx->stream;
+    int64_t n_hot = (int64_t)(budget_bytes / (uint64_t)ctx->row_bytes);
+    if (n_hot > n) n_hot = n;
+
+    sort_bufs b;
+    int32_t *order = nullptr;
+    int rc = sort_by_count(ctx, counts, b, &order);
+    if (rc != TIER_OK) return rc;
     if (n > 0) k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n, n_hot, ctx->slot);
 
     // (re)build the HBM cache: cache row r = feature row of the node of rank r
+    TIER_HIP(ctx, hipStreamSynchronize(st));
+    ctx->placed = false;
+    ctx->boundary = false;
+    if (ctx->cache) TIER_HIP(ctx, hipFree(ctx->cache));
+    ctx->cache = nullptr;
+    ctx->n_hot = 0;
+    if (n_hot > 0) {
+        TIER_HIP(ctx, hipMalloc(&ctx->cache, (size_t)n_hot * (size_t)ctx->row_bytes));
+        rc = tier_launch_gather(ctx, order, n_hot, GATHER_HOST, ctx->cache, false);
+        if (rc != TIER_OK) return rc;
+    }
+    ctx->n_hot = n_hot;
+    if (slot_map && n > 0)
+        TIER_HIP(ctx, hipMemcpyAsync(slot_map, ctx->slot, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    TIER_HIP(ctx, hipStreamSynchronize(st));   // `order` is freed on return
+    ctx->placed = true;
+    if (n_hot_out) *n_hot_out = n_hot;
+    return TIER_OK;
+}
+
+// Placement for a graph and table already ordered by rank (Sec. 3.2 second method,
+// Sec. 4.1): the first n_hot rows are the hot part, copied to HBM in one piece.
+extern "C" int tier_place_boundary(tier_ctx *ctx, uint64_t budget_bytes, int64_t *n_hot_out)
+{
+    if (!ctx) return TIER_EINVAL;
+    hipStream_t st = ctx->stream;
+    int64_t n_hot = (int64_t)(budget_bytes / (uint64_t)ctx->row_bytes);
+    if (n_hot > ctx->n_nodes) n_hot = ctx->n_nodes;
     TIER_HIP(ctx, hipStreamSynchronize(st));
     ctx->placed = false;
     if (ctx->cache) TIER_HIP(ctx, hipFree(ctx->cache));
@@ -278,13 +336,12 @@ extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget
     ctx->n_hot = 0;
     if (n_hot > 0) {
         TIER_HIP(ctx, hipMalloc(&ctx->cache, (size_t)n_hot * (size_t)ctx->row_bytes));
-        int rc = tier_launch_gather(ctx, order, n_hot, nullptr, nullptr, ctx->cache, false);
-        if (rc != TIER_OK) return rc;
+        TIER_HIP(ctx, hipMemcpyAsync(ctx->cache, ctx->host_rows, (size_t)n_hot * (size_t)ctx->row_bytes,
+                                     hipMemcpyDefault, st));
+        TIER_HIP(ctx, hipStreamSynchronize(st));
     }
     ctx->n_hot = n_hot;
-    if (slot_map && n > 0)
-        TIER_HIP(ctx, hipMemcpyAsync(slot_map, ctx->slot, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
-    TIER_HIP(ctx, hipStreamSynchronize(st));   // `order` is freed on return
+    ctx->boundary = true;
     ctx->placed = true;
     if (n_hot_out) *n_hot_out = n_hot;
     return TIER_OK;

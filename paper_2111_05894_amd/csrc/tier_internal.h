@@ -42,6 +42,7 @@ struct tier_ctx {
     uint8_t *cache;          // n_hot * row_bytes
     int64_t n_hot;
     bool placed;
+    bool boundary;           // true: rows are in rank order, hot <=> id < n_hot (no slot map)
     // sampler scratch
     int64_t *meta;           // device, [n_slots][META_WORDS]; slot 0 also holds totals, error flag, hit counter
     int64_t *meta_host;      // pinned mirror
@@ -62,9 +63,9 @@ struct tier_ctx {
     } while (0)
 
 // gather.hip: row copy used by tier_gather_features and by the cache fill of tier_place.
-// slot == nullptr reads every row from host_rows.
-int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, const int32_t *slot,
-                       const uint8_t *cache, void *out, bool count_hits);
+// mode 0: every row from host_rows; 1: through the slot map; 2: by the boundary n_hot.
+enum { GATHER_HOST = 0, GATHER_SLOT = 1, GATHER_BOUNDARY = 2 };
+int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, void *out, bool count_hits);
 
 // context.hip: copy the bookkeeping array into ctx->meta_host and wait for the
 // stream.  Returns TIER_EINVAL once (and clears the flag) when a kernel met an id
