@@ -162,6 +162,36 @@ uint64_t tier_batch_seed(uint64_t seed, uint32_t epoch, uint32_t batch);
 int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes,
                int32_t *slot_map, int64_t *n_hot);
 
+/* The ranking alone (Sec. 3.2: "srt_idx", the indices that sort the scores in
+ * descending order, and the old-id -> new-id map built from them).  counts: (device)
+ * n_nodes scores.  rank (device, optional): rank[v] = position of v in the order (count
+ * descending, id ascending) = the new id of v.  order (device, optional): order[r] = the
+ * node of rank r.  Waits. */
+int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, int32_t *order);
+
+/* Graph reordering (Sec. 3.2, Alg. 2): the context's graph with every node renamed to
+ * rank[node]: new node r has the neighbour list of order[r], in its old order, values
+ * renamed.  indptr_new: (device) n_nodes + 1 offsets of the context graph's offset type;
+ * indices_new: (device) n_edges ids.  rank/order as from tier_rank.  Waits. */
+int tier_reorder_graph(tier_ctx *ctx, const int32_t *rank, const int32_t *order, void *indptr_new,
+                       int32_t *indices_new);
+
+/* Feature rows follow their nodes (Sec. 3.2): rows_new[rank[v]] = row v of the context's
+ * table.  rows_new: (device-visible: pinned host or device) n_nodes * row_bytes bytes,
+ * 16-byte aligned, not overlapping the table.  Asynchronous. */
+int tier_reorder_rows(tier_ctx *ctx, const int32_t *rank, void *rows_new);
+
+/* out[i] = rank[ids[i]] (e.g. the training ids of the reordered graph).  ids, out:
+ * (device) n entries.  Waits; TIER_EINVAL if an id is outside [0, n_nodes). */
+int tier_relabel_ids(tier_ctx *ctx, const int32_t *rank, const int32_t *ids, int64_t n, int32_t *out);
+
+/* Placement for a context whose graph and table are already in rank order (created on
+ * the outputs of tier_reorder_graph / tier_reorder_rows): the hot part is the first
+ * n_hot = min(n_nodes, budget_bytes / row_bytes) rows (Sec. 4.1), copied to HBM in one
+ * piece; tier_gather_features then branches on id < n_hot (Listing 1: the cold part is
+ * indexed by id - n_hot) and reads no map.  Replaces any earlier placement.  Waits. */
+int tier_place_boundary(tier_ctx *ctx, uint64_t budget_bytes, int64_t *n_hot);
+
 /* One mini-batch (Sec. 2.2).  seeds: (device) n_seeds distinct node ids.  At hop l
  * every node of frontier_l draws min(fanouts[l], degree) distinct neighbours
  * uniformly at random (all of them, in adjacency order, when degree <= fanouts[l]);

@@ -22,6 +22,7 @@ EXPORTS = (
     "tier_host_alloc", "tier_host_free", "tier_blocks_bounds", "tier_create", "tier_destroy",
     "tier_presample", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
     "tier_sample_minibatches", "tier_max_batches",
+    "tier_rank", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
     "tier_gather_features", "tier_strerror", "tier_last_hip_error",
 )
 
@@ -82,6 +83,11 @@ def _load():
         lib.tier_sample_minibatches.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, i32p,
                                                 C.c_int32, C.POINTER(C.c_uint64), C.POINTER(_BlocksBatch)]
         lib.tier_max_batches.argtypes = [C.c_void_p]
+        lib.tier_rank.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.tier_reorder_graph.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.tier_reorder_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.tier_relabel_ids.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        lib.tier_place_boundary.argtypes = [C.c_void_p, C.c_uint64, i64p]
         lib.tier_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(_Stats)]
         lib.tier_strerror.argtypes = [C.c_int]; lib.tier_strerror.restype = C.c_char_p
         lib.tier_last_hip_error.argtypes = [C.c_void_p]
@@ -218,6 +224,48 @@ def tier_place(ctx: Context, counts: torch.Tensor, budget_bytes: int, want_slot_
                             _dev(slot, torch.int32, "slot_map") if want_slot_map else None, C.byref(n_hot))
     _check(rc, "tier_place")
     return slot, n_hot.value
+
+
+def tier_rank(ctx: Context, counts: torch.Tensor):
+    """Returns (rank, order): rank[v] = new id of v, order[r] = node of rank r."""
+    rank = torch.empty(ctx.n_nodes, dtype=torch.int32, device=counts.device)
+    order = torch.empty_like(rank)
+    _check(_load().tier_rank(ctx.handle, _dev(counts, torch.int32, "counts"), _dev(rank, torch.int32, "rank"),
+                             _dev(order, torch.int32, "order")), "tier_rank")
+    return rank, order
+
+
+def tier_reorder_graph(ctx: Context, rank: torch.Tensor, order: torch.Tensor):
+    """Alg. 2 on the context's graph: returns (indptr_new, indices_new)."""
+    indptr, indices, _ = ctx._keep
+    indptr_new = torch.empty_like(indptr); indices_new = torch.empty_like(indices)
+    _check(_load().tier_reorder_graph(ctx.handle, _dev(rank, torch.int32, "rank"), _dev(order, torch.int32, "order"),
+                                      C.c_void_p(indptr_new.data_ptr()), C.c_void_p(indices_new.data_ptr())),
+           "tier_reorder_graph")
+    return indptr_new, indices_new
+
+
+def tier_reorder_rows(ctx: Context, rank: torch.Tensor, rows_new):
+    """rows_new: a HostTable or a pinned / device tensor of the table's shape."""
+    t = rows_new.tensor if isinstance(rows_new, HostTable) else rows_new
+    if t.numel() * t.element_size() != ctx.n_nodes * ctx.row_bytes or not t.is_contiguous():
+        raise TypeError("rows_new: contiguous, same size as the feature table")
+    _check(_load().tier_reorder_rows(ctx.handle, _dev(rank, torch.int32, "rank"), C.c_void_p(t.data_ptr())),
+           "tier_reorder_rows")
+    return rows_new
+
+
+def tier_relabel_ids(ctx: Context, rank: torch.Tensor, ids: torch.Tensor) -> torch.Tensor:
+    out = torch.empty_like(ids)
+    _check(_load().tier_relabel_ids(ctx.handle, _dev(rank, torch.int32, "rank"), _dev(ids, torch.int32, "ids"),
+                                    ids.numel(), C.c_void_p(out.data_ptr())), "tier_relabel_ids")
+    return out
+
+
+def tier_place_boundary(ctx: Context, budget_bytes: int) -> int:
+    n_hot = C.c_int64(0)
+    _check(_load().tier_place_boundary(ctx.handle, budget_bytes, C.byref(n_hot)), "tier_place_boundary")
+    return n_hot.value
 
 
 class Blocks:
