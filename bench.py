@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--budget", type=float, default=None, help="override: fraction of feature bytes kept in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streams", action="store_true", help="skip the all-hit / all-miss gather runs")
+    ap.add_argument("--no-reorder", action="store_true",
+                    help="skip the reordered variant (graph and table renamed by rank, gather by boundary)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink nodes, edges and budget alike")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for profiler byte counters)")
@@ -215,6 +217,10 @@ def main():
                                  "avg_launch_ms": round(ms / nl, 4), "launches": nl}
         roofline["streams"] = streams
 
+    reorder = None
+    if not args.no_reorder:
+        reorder = reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(args, wl, indptr, indices, train, epoch_ids, table, budget, bseed)
@@ -234,10 +240,68 @@ def main():
         "host_link_reduction": round(h, 4),
         "phase_ms": {"presample": round(mean(rec["presample_ms"]), 3), "place": round(mean(rec["place_ms"]), 3),
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "reordered": reorder, "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
     ctx.close()
+
+
+def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log):
+    """The paper's own layout (Sec. 3.2, Alg. 2): graph and table renamed by rank, hot part =
+    ids below the boundary, gather without a map.  Times the reordering and one sampled and
+    gathered epoch on the reordered data (its draws differ: they are keyed by node id)."""
+    def timed(f):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); r = f(); b.record(); torch.cuda.synchronize()
+        return r, a.elapsed_time(b)
+
+    res = {}
+    tier.tier_presample(ctx, train, wl.batch_size, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
+    (rank, order), res["rank_ms"] = timed(lambda: tier.tier_rank(ctx, counts))
+    (ip2, ix2), res["graph_ms"] = timed(lambda: tier.tier_reorder_graph(ctx, rank, order))
+    try:
+        table2 = tier.tier_host_alloc(n, wl.dim, dtype)
+    except tier.TierError as e:
+        res["note"] = f"no second pinned table of {table.nbytes / 2**30:.1f} GiB on this host ({e}): rows not reordered"
+        log("[bench] " + res["note"])
+        return {k: (round(v, 3) if isinstance(v, float) else v) for k, v in res.items()}
+    try:
+        _, res["rows_ms"] = timed(lambda: tier.tier_reorder_rows(ctx, rank, table2))
+        train2 = tier.tier_relabel_ids(ctx, rank, train)
+        ctx2 = tier.tier_create(ip2, ix2, table2)
+        n_hot, res["place_boundary_ms"] = timed(lambda: tier.tier_place_boundary(ctx2, budget))
+        bs = wl.batch_size; L = len(wl.fanouts)
+        n_train = train2.numel(); n_batches = -(-n_train // bs)
+        order_e = synth.random_order(n_train, synth.EPOCH_SEED, 1, dev)
+        ep = train2[order_e].contiguous()
+        B = tier.tier_max_batches(ctx2)
+        blocks = tier.BlocksBatch(n, bs, wl.fanouts, B, dev)
+        out = torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=dev)
+        rows = hits = 0; ms = 0.0; launches = 0
+        for g0 in range(0, n_batches, B):
+            g = list(range(g0, min(g0 + B, n_batches)))
+            blk = tier.tier_sample_minibatches(ctx2, ep[g[0] * bs: min(n_train, (g[-1] + 1) * bs)], bs,
+                                               [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in g], wl.fanouts,
+                                               blocks)
+            evs = []
+            for i in range(len(g)):
+                a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(); tier.tier_gather_features(ctx2, blk.frontier(i), out); b_.record()
+                evs.append((a, b_)); rows += blk.n_nodes[i][L]
+            torch.cuda.synchronize()
+            ms += sum(a.elapsed_time(b_) for a, b_ in evs); launches += len(evs)
+            hits += sum(int((blk.frontier(i) < n_hot).sum()) for i in range(len(g)))
+        R = ctx2.row_bytes
+        h = hits / rows if rows else 0.0
+        res.update({"n_hot": n_hot, "rows_per_epoch": rows, "hit_fraction": round(h, 4),
+                    "gather_ms": round(ms, 3), "gather_GBps": round(rows * R / (ms * 1e-3) / 1e9, 2) if ms else None,
+                    "avg_launch_ms": round(ms / launches, 4) if launches else None})
+        peak = (2 * R + 4) / (((1 + h) * R + 4) / HBM_PEAK_GBPS + (1 - h) * R / LINK_PEAK_GBPS)
+        res["roofline_frac"] = round((2 * R + 4) * rows / (ms * 1e-3) / 1e9 / peak, 4) if ms else None
+        ctx2.close()
+    finally:
+        table2.free()
+    return {k: (round(v, 3) if isinstance(v, float) else v) for k, v in res.items()}
 
 
 def cpu_baseline(args, wl, indptr, indices, train, epoch_ids, table, budget, bseed):

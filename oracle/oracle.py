@@ -31,7 +31,7 @@ def build(force: bool = False) -> str:
     if force or stale:
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.run(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
-                        "-o", tmp, _SRC], check=True)
+                        "-ffp-contract=off", "-o", tmp, _SRC], check=True)
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -69,6 +69,13 @@ def _load():
         _lib.orc_reorder_rows.argtypes = [_u8p, C.c_int64, C.c_int64, _i32p, _u8p]
         _lib.orc_gather_boundary.restype = None
         _lib.orc_gather_boundary.argtypes = [_u8p, _u8p, C.c_int64, C.c_int64, _i32p, C.c_int64, _u8p, _i64p]
+        _f64p = C.POINTER(C.c_double)
+        _lib.orc_score_degree.restype = None
+        _lib.orc_score_degree.argtypes = [C.c_int64, _i64p, _i32p, _u32p]
+        _lib.orc_score_wrpr.restype = None
+        _lib.orc_score_wrpr.argtypes = [C.c_int64, _i64p, _i32p, _i32p, C.c_int64, C.c_int, C.c_double, _f64p]
+        _lib.orc_rank_scores.restype = C.c_int
+        _lib.orc_rank_scores.argtypes = [_f64p, C.c_int64, _i32p]
     return _lib
 
 
@@ -242,3 +249,29 @@ def gather_boundary(feat_bytes_reordered, boundary: int, ids):
     _load().orc_gather_boundary(_p(hot, _u8p), _p(cold, _u8p), boundary, fb.shape[1], _p(ids, _i32p), ids.shape[0],
                                 _p(out, _u8p), C.byref(hit))
     return out, hit.value
+
+
+def score_degree(indptr, indices):
+    indptr = _as(indptr, np.int64); indices = _as(indices, np.int32)
+    n = indptr.shape[0] - 1
+    deg = np.zeros(n, np.uint32)
+    _load().orc_score_degree(n, _p(indptr, _i64p), _p(indices, _i32p), _p(deg, _u32p))
+    return deg
+
+
+def score_wrpr(indptr, indices, train_ids, iters: int, damp: float):
+    """Weighted reverse PageRank (Alg. 1); no training ids = plain reverse PageRank."""
+    indptr = _as(indptr, np.int64); indices = _as(indices, np.int32); tid = _as(train_ids, np.int32)
+    n = indptr.shape[0] - 1
+    score = np.zeros(max(n, 1), np.float64)
+    _load().orc_score_wrpr(n, _p(indptr, _i64p), _p(indices, _i32p), _p(tid, _i32p), tid.shape[0], iters, damp,
+                           _p(score, C.POINTER(C.c_double)))
+    return score[:n]
+
+
+def rank_scores(score):
+    score = _as(score, np.float64)
+    rank = np.empty(score.shape[0], np.int32)
+    if _load().orc_rank_scores(_p(score, C.POINTER(C.c_double)), score.shape[0], _p(rank, _i32p)):
+        raise MemoryError
+    return rank

@@ -378,3 +378,73 @@ void orc_gather_boundary(const uint8_t *hot, const uint8_t *cold, int64_t bounda
     }
     if (hit_rows) *hit_rows = hit;
 }
+
+/* ------------------------------------------------------------------------ */
+/* The paper's own score functions (Sec. 3.1), alternatives to the measured  */
+/* access count.  Edges run source -> target; row v of the CSR lists the     */
+/* sources of the edges into v, so in_degree(v) is the length of row v and   */
+/* out_degree(u) the number of rows that contain u.                          */
+/* ------------------------------------------------------------------------ */
+
+/* Score 1: the out degree of each node. */
+void orc_score_degree(int64_t n, const int64_t *indptr, const int32_t *indices, uint32_t *degree)
+{
+    memset(degree, 0, (size_t)n * sizeof(uint32_t));
+    for (int64_t e = 0; e < indptr[n]; ++e) degree[indices[e]] += 1u;
+}
+
+/* Score 3: weighted reverse PageRank (Alg. 1).  In the algorithm's order:          */
+/*   score = 1/N everywhere, times N/N_train on the training nodes;                  */
+/*   per iteration: score[j] /= in_degree[j]; every node pulls (sums) the scores of  */
+/*   the nodes it targets; score[j] = (1-d)/N + d*score[j].                          */
+/* With weight 1 (no training ids) this is plain reverse PageRank (score 2) cut     */
+/* after `iter` rounds.  Readings: a node without incoming edges is not divided      */
+/* (nobody pulls from it); the pull replaces the score (a node that targets nothing  */
+/* pulls 0); sums run over rows in order and over each row in list order.            */
+void orc_score_wrpr(int64_t n, const int64_t *indptr, const int32_t *indices,
+                    const int32_t *tid, int64_t num_train, int iter, double d, double *score)
+{
+    double *pulled = (double *)malloc((size_t)(n > 0 ? n : 1) * sizeof(double));
+    for (int64_t i = 0; i < n; ++i) score[i] = 1.0 / (double)n;
+    if (num_train > 0) {
+        double weight = (double)n / (double)num_train;
+        for (int64_t i = 0; i < num_train; ++i) score[tid[i]] = score[tid[i]] * weight;
+    }
+    for (int it = 0; it < iter; ++it) {
+        for (int64_t j = 0; j < n; ++j) {
+            int64_t in_degree = indptr[j + 1] - indptr[j];
+            if (in_degree > 0) score[j] = score[j] / (double)in_degree;
+        }
+        /* pull_from_neighbor: source u sums over the nodes v it targets; row v lists those sources */
+        for (int64_t u = 0; u < n; ++u) pulled[u] = 0.0;
+        for (int64_t v = 0; v < n; ++v)
+            for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e) pulled[indices[e]] += score[v];
+        for (int64_t j = 0; j < n; ++j) {
+            double a = (1.0 - d) / (double)n;
+            double b = d * pulled[j];
+            score[j] = a + b;
+        }
+    }
+    free(pulled);
+}
+
+/* Ranking by a real-valued score: descending score, equal scores by ascending id. */
+typedef struct { double score; int32_t id; } rscored;
+
+static int cmp_rscored(const void *a, const void *b)
+{
+    const rscored *x = (const rscored *)a, *y = (const rscored *)b;
+    if (x->score != y->score) return x->score > y->score ? -1 : 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+int orc_rank_scores(const double *score, int64_t n, int32_t *rank)
+{
+    rscored *s = (rscored *)malloc((size_t)(n > 0 ? n : 1) * sizeof(rscored));
+    if (!s) return -1;
+    for (int64_t v = 0; v < n; ++v) { s[v].score = score[v]; s[v].id = (int32_t)v; }
+    qsort(s, (size_t)n, sizeof(rscored), cmp_rscored);
+    for (int64_t r = 0; r < n; ++r) rank[s[r].id] = (int32_t)r;
+    free(s);
+    return 0;
+}
