@@ -162,6 +162,31 @@ uint64_t tier_batch_seed(uint64_t seed, uint32_t epoch, uint32_t batch);
 int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes,
                int32_t *slot_map, int64_t *n_hot);
 
+/* The paper's predictive scores (Sec. 3.1), alternatives to the measured access count.
+ * Edges run source -> target and row v of the graph lists the sources of the edges into v.
+ *
+ * tier_score_degree: degree[u] = out degree of u = number of adjacency lists that hold u
+ * ("the first metric", Sec. 3.1).  degree: (device) n_nodes entries, overwritten; feed it
+ * to tier_place / tier_rank as the counts.  Asynchronous.
+ *
+ * tier_score_wrpr: weighted reverse PageRank (Alg. 1): score = 1/N, times N/n_train on the
+ * training nodes; `iterations` rounds of { score[j] /= in_degree[j] (skipped when 0);
+ * every node sums the scores of the nodes it targets; score[j] = (1-damp)/N + damp*sum }.
+ * n_train = 0 gives plain reverse PageRank cut after `iterations` rounds (Sec. 3.1).
+ * The paper runs 5 rounds and leaves damp open (0.85 is PageRank's usual value).
+ * train_ids: (device) distinct ids.  score: (device) n_nodes doubles, overwritten.
+ * fp64 throughout; the order of each node's sum varies from run to run, so results
+ * agree to ~1e-15 relative, not bit for bit.  Waits. */
+int tier_score_degree(tier_ctx *ctx, uint32_t *degree);
+int tier_score_wrpr(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t iterations, double damp,
+                    double *score);
+
+/* Ranking and placement by a real-valued score (descending, equal scores by ascending
+ * id; no NaN): as tier_rank and tier_place.  scores: (device) n_nodes doubles. */
+int tier_rank_scores(tier_ctx *ctx, const double *scores, int32_t *rank, int32_t *order);
+int tier_place_scores(tier_ctx *ctx, const double *scores, uint64_t budget_bytes, int32_t *slot_map,
+                      int64_t *n_hot);
+
 /* The ranking alone (Sec. 3.2: "srt_idx", the indices that sort the scores in
  * descending order, and the old-id -> new-id map built from them).  counts: (device)
  * n_nodes scores.  rank (device, optional): rank[v] = position of v in the order (count

@@ -1,13 +1,15 @@
 // Hot/cold placement (Sec. 3.2: order by descending score, old-id -> rank map;
 // Sec. 4.1: the top rows live in GPU memory, the rest in host memory).
 //
-// The score is the access count.  Ordering by (count descending, id ascending)
-// is a stable sort of the ids 0..N-1 by the key (max_count - count): a
-// least-significant-digit radix sort with 8-bit digits over only as many digits
-// as max_count has.  Each wavefront owns one contiguous share of the input, so
-// stability needs no cross-wavefront ordering: per-(digit, wavefront) counts are
-// scanned digit-major into start offsets, and inside a wavefront the rank among
-// equal digits comes from ballots.
+// Ordering by (score descending, id ascending) is a stable sort of the ids 0..N-1
+// by a key that grows as the score falls: ~count for integer scores (access
+// counts, degrees), the complemented order-preserving bit pattern for real ones.
+// The sort is a least-significant-digit radix sort with 8-bit digits that runs
+// only the digits in which the keys differ at all (small counts: one or two
+// passes).  Each wavefront owns one contiguous share of the input, so stability
+// needs no cross-wavefront ordering: per-(digit, wavefront) counts are scanned
+// digit-major into start offsets, and inside a wavefront the rank among equal
+// digits comes from ballots.
 #include "tier_internal.h"
 
 namespace {
@@ -17,40 +19,48 @@ constexpr int kDigits = 256;
 constexpr int kMaxShares = 4096;
 constexpr int kScanBlock = 256;
 
-__global__ void k_max_u32(const uint32_t *__restrict__ x, int64_t n, uint32_t *__restrict__ out)
+__global__ void k_keys_from_counts(const uint32_t *__restrict__ counts, int64_t n, uint32_t *__restrict__ keys)
 {
-    uint32_t m = 0;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) m = x[i] > m ? x[i] : m;
-    for (int off = 32; off > 0; off >>= 1) {
-        uint32_t o = (uint32_t)__shfl_xor((int)m, off);
-        m = o > m ? o : m;
-    }
-    if ((threadIdx.x & 63) == 0 && m) atomicMax(out, m);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) keys[i] = ~counts[i];
 }
 
-// keys of the first pass come from the counts; later passes read the previous pass
-__device__ inline uint32_t load_key(const uint32_t *__restrict__ counts, const uint32_t *__restrict__ keys_in,
-                                    uint32_t max_count, int64_t i)
+// ascending unsigned order of the key = descending order of the value (-0.0 counts as 0.0)
+__global__ void k_keys_from_scores(const double *__restrict__ scores, int64_t n, uint64_t *__restrict__ keys)
 {
-    return counts ? max_count - counts[i] : keys_in[i];
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        uint64_t b = (uint64_t)__double_as_longlong(scores[i] + 0.0);
+        b ^= (b >> 63) ? ~0ull : (1ull << 63);          // now ascending with the value
+        keys[i] = ~b;
+    }
+}
+
+// bits in which any key differs from the first one
+template <typename K>
+__global__ void k_varying_bits(const K *__restrict__ keys, int64_t n, unsigned long long *__restrict__ out)
+{
+    const K first = keys[0];
+    K m = 0;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) m |= keys[i] ^ first;
+    unsigned long long mm = (unsigned long long)m;
+    for (int off = 32; off > 0; off >>= 1) mm |= (unsigned long long)__shfl_xor((long long)mm, off);
+    if ((threadIdx.x & 63) == 0 && mm) atomicOr(out, mm);
 }
 
 // launched with one wavefront per block; block b owns items [b*share, (b+1)*share)
-__global__ __launch_bounds__(kWave) void k_radix_hist(const uint32_t *__restrict__ counts,
-                                                      const uint32_t *__restrict__ keys_in, uint32_t max_count,
-                                                      int64_t n, int64_t share, int shift,
-                                                      uint32_t *__restrict__ hist, int n_shares)
+template <typename K>
+__global__ __launch_bounds__(kWave) void k_radix_hist(const K *__restrict__ keys_in, int64_t n, int64_t share,
+                                                      int shift, uint32_t *__restrict__ hist, int n_shares)
 {
     __shared__ uint32_t s_hist[kDigits];
     for (int d = threadIdx.x; d < kDigits; d += kWave) s_hist[d] = 0;
     __syncthreads();
     int64_t lo = (int64_t)blockIdx.x * share, hi = lo + share;
     if (hi > n) hi = n;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kWave) {
-        uint32_t key = load_key(counts, keys_in, max_count, i);
-        atomicAdd(&s_hist[(key >> shift) & 255u], 1u);
-    }
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kWave)
+        atomicAdd(&s_hist[(uint32_t)(keys_in[i] >> shift) & 255u], 1u);
     __syncthreads();
     for (int d = threadIdx.x; d < kDigits; d += kWave) hist[(int64_t)d * n_shares + blockIdx.x] = s_hist[d];
 }
@@ -121,13 +131,12 @@ __global__ __launch_bounds__(kScanBlock) void k_scan_apply(uint32_t *__restrict_
     }
 }
 
-__global__ __launch_bounds__(kWave) void k_radix_scatter(const uint32_t *__restrict__ counts,
-                                                         const uint32_t *__restrict__ keys_in,
-                                                         const int32_t *__restrict__ vals_in, uint32_t max_count,
-                                                         int64_t n, int64_t share, int shift,
+template <typename K>
+__global__ __launch_bounds__(kWave) void k_radix_scatter(const K *__restrict__ keys_in,
+                                                         const int32_t *__restrict__ vals_in, int64_t n,
+                                                         int64_t share, int shift,
                                                          const uint32_t *__restrict__ offsets, int n_shares,
-                                                         uint32_t *__restrict__ keys_out,
-                                                         int32_t *__restrict__ vals_out)
+                                                         K *__restrict__ keys_out, int32_t *__restrict__ vals_out)
 {
     __shared__ uint32_t s_off[kDigits];
     for (int d = threadIdx.x; d < kDigits; d += kWave) s_off[d] = offsets[(int64_t)d * n_shares + blockIdx.x];
@@ -138,13 +147,13 @@ __global__ __launch_bounds__(kWave) void k_radix_scatter(const uint32_t *__restr
     for (int64_t base = lo; base < hi; base += kWave) {
         const int64_t i = base + threadIdx.x;
         const bool valid = i < hi;
-        uint32_t key = 0;
+        K key = 0;
         int32_t val = 0;
         if (valid) {
-            key = load_key(counts, keys_in, max_count, i);
+            key = keys_in[i];
             val = vals_in ? vals_in[i] : (int32_t)i;
         }
-        const uint32_t digit = (key >> shift) & 255u;
+        const uint32_t digit = (uint32_t)(key >> shift) & 255u;
         uint64_t peers = __ballot(valid);
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
@@ -181,7 +190,7 @@ __global__ void k_slot_map(const int32_t *__restrict__ order, int64_t n, int64_t
         slot[order[r]] = r < n_hot ? (int32_t)r : -1;
 }
 
-__global__ void k_zero_u32(uint32_t *p) { *p = 0; }
+__global__ void k_zero_u64(unsigned long long *p) { *p = 0; }
 
 int grid_for(int64_t n, int block, int cap)
 {
@@ -192,11 +201,11 @@ int grid_for(int64_t n, int block, int cap)
 }
 
 struct sort_bufs {
-    uint32_t *keys[2] = {nullptr, nullptr};
+    void *keys[2] = {nullptr, nullptr};
     int32_t *vals[2] = {nullptr, nullptr};
     uint32_t *hist = nullptr;
     uint32_t *partial = nullptr;
-    uint32_t *max_dev = nullptr;
+    unsigned long long *mask_dev = nullptr;
     ~sort_bufs()
     {
         for (int i = 0; i < 2; ++i) {
@@ -205,78 +214,91 @@ struct sort_bufs {
         }
         (void)hipFree(hist);
         (void)hipFree(partial);
-        (void)hipFree(max_dev);
+        (void)hipFree(mask_dev);
     }
 };
 
-}  // namespace
-
-// Order the node ids by (count descending, id ascending) on the context's stream.
-// *order points into b (rank -> node id) and is valid until b dies.  Waits once
-// (for the largest count, which fixes the number of radix passes).
-static int sort_by_count(tier_ctx *ctx, const uint32_t *counts, sort_bufs &b, int32_t **order_out)
+// Stable ascending sort of 0..n-1 by keys (b.keys[0], already filled) on the context's
+// stream.  *order_out points into b (position -> id) and is valid until b dies.  Waits
+// once (for the set of digits in which the keys differ).
+template <typename K>
+int sort_ids_by_keys(tier_ctx *ctx, sort_bufs &b, int32_t **order_out)
 {
     const int64_t n = ctx->n_nodes;
     hipStream_t st = ctx->stream;
-    TIER_HIP(ctx, hipMalloc(&b.max_dev, sizeof(uint32_t)));
-    k_zero_u32<<<1, 1, 0, st>>>(b.max_dev);
-    if (n > 0) k_max_u32<<<grid_for(n, 256, 2048), 256, 0, st>>>(counts, n, b.max_dev);
-    uint32_t max_count = 0;
-    TIER_HIP(ctx, hipMemcpyAsync(ctx->meta_host, b.max_dev, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    K *keys[2] = {(K *)b.keys[0], nullptr};
+    TIER_HIP(ctx, hipMalloc(&b.mask_dev, sizeof(unsigned long long)));
+    k_zero_u64<<<1, 1, 0, st>>>(b.mask_dev);
+    if (n > 0) k_varying_bits<K><<<grid_for(n, 256, 2048), 256, 0, st>>>(keys[0], n, b.mask_dev);
+    TIER_HIP(ctx, hipMemcpyAsync(ctx->meta_host, b.mask_dev, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
     TIER_HIP(ctx, hipStreamSynchronize(st));
-    max_count = *(uint32_t *)ctx->meta_host;
-    int passes = 0;
-    while (passes < 4 && (max_count >> (8 * passes)) != 0) ++passes;
+    const unsigned long long mask = *(unsigned long long *)ctx->meta_host;
+    int shifts[8], passes = 0;
+    for (int d = 0; d < (int)sizeof(K); ++d)
+        if ((mask >> (8 * d)) & 0xffull) shifts[passes++] = 8 * d;
 
     TIER_HIP(ctx, hipMalloc(&b.vals[0], (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
-    int32_t *order = b.vals[0];
     if (passes == 0) {
-        k_iota<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n);
-    } else {
-        int64_t share = (n + kMaxShares - 1) / kMaxShares;
-        if (share < 16 * kWave) share = 16 * kWave;
-        share = (share + kWave - 1) / kWave * kWave;
-        const int n_shares = (int)((n + share - 1) / share);
-        const int64_t n_hist = (int64_t)kDigits * n_shares;
-        const int scan_grid = grid_for(n_hist, 4 * kScanBlock, 1024);
-        TIER_HIP(ctx, hipMalloc(&b.hist, (size_t)n_hist * sizeof(uint32_t)));
-        TIER_HIP(ctx, hipMalloc(&b.partial, 1024 * sizeof(uint32_t)));
-        if (passes > 1) {
-            TIER_HIP(ctx, hipMalloc(&b.vals[1], (size_t)n * sizeof(int32_t)));
-            TIER_HIP(ctx, hipMalloc(&b.keys[0], (size_t)n * sizeof(uint32_t)));
-            if (passes > 2) TIER_HIP(ctx, hipMalloc(&b.keys[1], (size_t)n * sizeof(uint32_t)));
-        }
-        // ping-pong so that the last pass writes vals[0]
-        int dst = (passes % 2 == 1) ? 0 : 1;
-        const uint32_t *keys_in = nullptr;
-        const int32_t *vals_in = nullptr;
-        for (int p = 0; p < passes; ++p) {
-            const uint32_t *cnt = p == 0 ? counts : nullptr;
-            const bool last = p == passes - 1;
-            uint32_t *keys_out = last ? nullptr : b.keys[passes > 2 ? dst : 0];
-            k_radix_hist<<<n_shares, kWave, 0, st>>>(cnt, keys_in, max_count, n, share, 8 * p, b.hist, n_shares);
-            k_scan_partial<<<scan_grid, kScanBlock, 0, st>>>(b.hist, n_hist, b.partial);
-            k_scan_apply<<<scan_grid, kScanBlock, 0, st>>>(b.hist, n_hist, b.partial);
-            k_radix_scatter<<<n_shares, kWave, 0, st>>>(cnt, keys_in, vals_in, max_count, n, share, 8 * p, b.hist,
-                                                        n_shares, keys_out, b.vals[dst]);
-            keys_in = keys_out;
-            vals_in = b.vals[dst];
-            dst ^= 1;
-        }
+        k_iota<<<grid_for(n, 256, 4096), 256, 0, st>>>(b.vals[0], n);
+        TIER_HIP(ctx, hipGetLastError());
+        *order_out = b.vals[0];
+        return TIER_OK;
+    }
+    int64_t share = (n + kMaxShares - 1) / kMaxShares;
+    if (share < 16 * kWave) share = 16 * kWave;
+    share = (share + kWave - 1) / kWave * kWave;
+    const int n_shares = (int)((n + share - 1) / share);
+    const int64_t n_hist = (int64_t)kDigits * n_shares;
+    const int scan_grid = grid_for(n_hist, 4 * kScanBlock, 1024);
+    TIER_HIP(ctx, hipMalloc(&b.hist, (size_t)n_hist * sizeof(uint32_t)));
+    TIER_HIP(ctx, hipMalloc(&b.partial, 1024 * sizeof(uint32_t)));
+    if (passes > 1) {
+        TIER_HIP(ctx, hipMalloc(&b.vals[1], (size_t)n * sizeof(int32_t)));
+        TIER_HIP(ctx, hipMalloc(&b.keys[1], (size_t)n * sizeof(K)));
+        keys[1] = (K *)b.keys[1];
+    }
+    // pass j reads buffers j % 2 and writes buffers (j + 1) % 2; with one pass only ids move
+    for (int j = 0; j < passes; ++j) {
+        const int src = j % 2, dst = (j + 1) % 2;
+        const bool last = j == passes - 1;
+        int32_t *vals_out = passes == 1 ? b.vals[0] : b.vals[dst];
+        k_radix_hist<K><<<n_shares, kWave, 0, st>>>(keys[src], n, share, shifts[j], b.hist, n_shares);
+        k_scan_partial<<<scan_grid, kScanBlock, 0, st>>>(b.hist, n_hist, b.partial);
+        k_scan_apply<<<scan_grid, kScanBlock, 0, st>>>(b.hist, n_hist, b.partial);
+        k_radix_scatter<K><<<n_shares, kWave, 0, st>>>(keys[src], j == 0 ? nullptr : b.vals[src], n, share, shifts[j],
+                                                       b.hist, n_shares, last ? nullptr : keys[dst], vals_out);
     }
     TIER_HIP(ctx, hipGetLastError());
-    *order_out = order;
+    *order_out = passes == 1 ? b.vals[0] : b.vals[passes % 2];
     return TIER_OK;
 }
 
-extern "C" int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, int32_t *order)
+}  // namespace
+
+// Order the node ids by (count descending, id ascending).
+static int sort_by_count(tier_ctx *ctx, const uint32_t *counts, sort_bufs &b, int32_t **order_out)
 {
-    if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
     const int64_t n = ctx->n_nodes;
-    sort_bufs b;
-    int32_t *ord = nullptr;
-    int rc = sort_by_count(ctx, counts, b, &ord);
-    if (rc != TIER_OK) return rc;
+    TIER_HIP(ctx, hipMalloc(&b.keys[0], (size_t)(n > 0 ? n : 1) * sizeof(uint32_t)));
+    if (n > 0)
+        k_keys_from_counts<<<grid_for(n, 256, 4096), 256, 0, ctx->stream>>>(counts, n, (uint32_t *)b.keys[0]);
+    return sort_ids_by_keys<uint32_t>(ctx, b, order_out);
+}
+
+// Order the node ids by (score descending, id ascending); scores must not be NaN.
+static int sort_by_score(tier_ctx *ctx, const double *scores, sort_bufs &b, int32_t **order_out)
+{
+    const int64_t n = ctx->n_nodes;
+    TIER_HIP(ctx, hipMalloc(&b.keys[0], (size_t)(n > 0 ? n : 1) * sizeof(uint64_t)));
+    if (n > 0)
+        k_keys_from_scores<<<grid_for(n, 256, 4096), 256, 0, ctx->stream>>>(scores, n, (uint64_t *)b.keys[0]);
+    return sort_ids_by_keys<uint64_t>(ctx, b, order_out);
+}
+
+// rank / order outputs shared by tier_rank and tier_rank_scores
+static int emit_rank(tier_ctx *ctx, const int32_t *ord, int32_t *rank, int32_t *order)
+{
+    const int64_t n = ctx->n_nodes;
     if (rank && n > 0) k_slot_map<<<grid_for(n, 256, 4096), 256, 0, ctx->stream>>>(ord, n, n, rank);
     if (order && n > 0)
         TIER_HIP(ctx, hipMemcpyAsync(order, ord, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, ctx->stream));
@@ -285,19 +307,14 @@ extern "C" int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, i
     return TIER_OK;
 }
 
-extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes, int32_t *slot_map,
-                          int64_t *n_hot_out)
+// slot map + HBM cache from an order (rank -> node)
+static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget_bytes, int32_t *slot_map,
+                            int64_t *n_hot_out)
 {
-    if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
     const int64_t n = ctx->n_nodes;
     hipStream_t st = ctx->stream;
     int64_t n_hot = (int64_t)(budget_bytes / (uint64_t)ctx->row_bytes);
     if (n_hot > n) n_hot = n;
-
-    sort_bufs b;
-    int32_t *order = nullptr;
-    int rc = sort_by_count(ctx, counts, b, &order);
-    if (rc != TIER_OK) return rc;
     if (n > 0) k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n, n_hot, ctx->slot);
 
     // (re)build the HBM cache: cache row r = feature row of the node of rank r
@@ -309,16 +326,58 @@ extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget
     ctx->n_hot = 0;
     if (n_hot > 0) {
         TIER_HIP(ctx, hipMalloc(&ctx->cache, (size_t)n_hot * (size_t)ctx->row_bytes));
-        rc = tier_launch_gather(ctx, order, n_hot, GATHER_HOST, ctx->cache, false);
+        int rc = tier_launch_gather(ctx, order, n_hot, GATHER_HOST, ctx->cache, false);
         if (rc != TIER_OK) return rc;
     }
     ctx->n_hot = n_hot;
     if (slot_map && n > 0)
         TIER_HIP(ctx, hipMemcpyAsync(slot_map, ctx->slot, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
-    TIER_HIP(ctx, hipStreamSynchronize(st));   // `order` is freed on return
+    TIER_HIP(ctx, hipStreamSynchronize(st));   // `order` is freed by the caller after this
     ctx->placed = true;
     if (n_hot_out) *n_hot_out = n_hot;
     return TIER_OK;
+}
+
+extern "C" int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, int32_t *order)
+{
+    if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
+    sort_bufs b;
+    int32_t *ord = nullptr;
+    int rc = sort_by_count(ctx, counts, b, &ord);
+    if (rc != TIER_OK) return rc;
+    return emit_rank(ctx, ord, rank, order);
+}
+
+extern "C" int tier_rank_scores(tier_ctx *ctx, const double *scores, int32_t *rank, int32_t *order)
+{
+    if (!ctx || (!scores && ctx->n_nodes > 0)) return TIER_EINVAL;
+    sort_bufs b;
+    int32_t *ord = nullptr;
+    int rc = sort_by_score(ctx, scores, b, &ord);
+    if (rc != TIER_OK) return rc;
+    return emit_rank(ctx, ord, rank, order);
+}
+
+extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes, int32_t *slot_map,
+                          int64_t *n_hot_out)
+{
+    if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
+    sort_bufs b;
+    int32_t *order = nullptr;
+    int rc = sort_by_count(ctx, counts, b, &order);
+    if (rc != TIER_OK) return rc;
+    return place_from_order(ctx, order, budget_bytes, slot_map, n_hot_out);
+}
+
+extern "C" int tier_place_scores(tier_ctx *ctx, const double *scores, uint64_t budget_bytes, int32_t *slot_map,
+                                 int64_t *n_hot_out)
+{
+    if (!ctx || (!scores && ctx->n_nodes > 0)) return TIER_EINVAL;
+    sort_bufs b;
+    int32_t *order = nullptr;
+    int rc = sort_by_score(ctx, scores, b, &order);
+    if (rc != TIER_OK) return rc;
+    return place_from_order(ctx, order, budget_bytes, slot_map, n_hot_out);
 }
 
 // Placement for a graph and table already ordered by rank (Sec. 3.2 second method,

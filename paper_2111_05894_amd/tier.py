@@ -22,6 +22,7 @@ EXPORTS = (
     "tier_host_alloc", "tier_host_free", "tier_blocks_bounds", "tier_create", "tier_destroy",
     "tier_presample", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
     "tier_sample_minibatches", "tier_max_batches",
+    "tier_score_degree", "tier_score_wrpr", "tier_rank_scores", "tier_place_scores",
     "tier_rank", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
     "tier_gather_features", "tier_strerror", "tier_last_hip_error",
 )
@@ -83,6 +84,10 @@ def _load():
         lib.tier_sample_minibatches.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, i32p,
                                                 C.c_int32, C.POINTER(C.c_uint64), C.POINTER(_BlocksBatch)]
         lib.tier_max_batches.argtypes = [C.c_void_p]
+        lib.tier_score_degree.argtypes = [C.c_void_p, C.c_void_p]
+        lib.tier_score_wrpr.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_double, C.c_void_p]
+        lib.tier_rank_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.tier_place_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, i64p]
         lib.tier_rank.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tier_reorder_graph.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tier_reorder_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -223,6 +228,37 @@ def tier_place(ctx: Context, counts: torch.Tensor, budget_bytes: int, want_slot_
     rc = _load().tier_place(ctx.handle, _dev(counts, torch.int32, "counts"), budget_bytes,
                             _dev(slot, torch.int32, "slot_map") if want_slot_map else None, C.byref(n_hot))
     _check(rc, "tier_place")
+    return slot, n_hot.value
+
+
+def tier_score_degree(ctx: Context, device="cuda:0") -> torch.Tensor:
+    deg = torch.empty(ctx.n_nodes, dtype=torch.int32, device=device)
+    _check(_load().tier_score_degree(ctx.handle, _dev(deg, torch.int32, "degree")), "tier_score_degree")
+    return deg
+
+
+def tier_score_wrpr(ctx: Context, train_ids: torch.Tensor, iterations: int = 5, damp: float = 0.85) -> torch.Tensor:
+    score = torch.empty(ctx.n_nodes, dtype=torch.float64, device=train_ids.device)
+    _check(_load().tier_score_wrpr(ctx.handle, _dev(train_ids, torch.int32, "train_ids"), train_ids.numel(),
+                                   iterations, damp, _dev(score, torch.float64, "score")), "tier_score_wrpr")
+    return score
+
+
+def tier_rank_scores(ctx: Context, scores: torch.Tensor):
+    rank = torch.empty(ctx.n_nodes, dtype=torch.int32, device=scores.device)
+    order = torch.empty_like(rank)
+    _check(_load().tier_rank_scores(ctx.handle, _dev(scores, torch.float64, "scores"),
+                                    _dev(rank, torch.int32, "rank"), _dev(order, torch.int32, "order")),
+           "tier_rank_scores")
+    return rank, order
+
+
+def tier_place_scores(ctx: Context, scores: torch.Tensor, budget_bytes: int, want_slot_map: bool = True):
+    slot = torch.empty(ctx.n_nodes, dtype=torch.int32, device=scores.device) if want_slot_map else None
+    n_hot = C.c_int64(0)
+    rc = _load().tier_place_scores(ctx.handle, _dev(scores, torch.float64, "scores"), budget_bytes,
+                                   _dev(slot, torch.int32, "slot_map") if want_slot_map else None, C.byref(n_hot))
+    _check(rc, "tier_place_scores")
     return slot, n_hot.value
 
 
