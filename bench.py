@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--no-streams", action="store_true", help="skip the all-hit / all-miss gather runs")
     ap.add_argument("--no-reorder", action="store_true",
                     help="skip the reordered variant (graph and table renamed by rank, gather by boundary)")
+    ap.add_argument("--no-scores", action="store_true",
+                    help="skip the comparison of score functions (presampled counts vs the paper's scores)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink nodes, edges and budget alike")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for profiler byte counters)")
@@ -217,6 +219,10 @@ def main():
                                  "avg_launch_ms": round(ms / nl, 4), "launches": nl}
         roofline["streams"] = streams
 
+    scores = None
+    if not args.no_scores:
+        scores = score_comparison(tier, synth, torch, ctx, wl, counts, train, budget, groups, sample_group, L)
+
     reorder = None
     if not args.no_reorder:
         reorder = reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log)
@@ -240,10 +246,44 @@ def main():
         "host_link_reduction": round(h, 4),
         "phase_ms": {"presample": round(mean(rec["presample_ms"]), 3), "place": round(mean(rec["place_ms"]), 3),
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3)},
-        "roofline": roofline, "reordered": reorder, "cpu_baseline": cpu,
+        "roofline": roofline, "score_functions": scores, "reordered": reorder, "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
     ctx.close()
+
+
+def score_comparison(tier, synth, torch, ctx, wl, counts, train, budget, groups, sample_group, L):
+    """Hit fraction of the measured epoch when the same budget is filled by each score
+    (the paper's Sec. 5.2 question: how well does a score predict the measured accesses),
+    and the time each score takes.  Hits are counted from the slot map of each placement."""
+    def timed(f):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); r = f(); b.record(); torch.cuda.synchronize()
+        return r, round(a.elapsed_time(b), 3)
+
+    frontiers = []
+    for g in groups:
+        blk = sample_group(g)
+        frontiers += [blk.frontier(i).clone() for i in range(len(g))]
+    rows = sum(f.numel() for f in frontiers)
+    none = train[:0]
+    res = {}
+    _, t = timed(lambda: tier.tier_presample(ctx, train, wl.batch_size, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts))
+    makers = {
+        "presampled_counts": (lambda: counts, t, "int"),
+        "out_degree": (lambda: tier.tier_score_degree(ctx), None, "int"),
+        "reverse_pagerank_5": (lambda: tier.tier_score_wrpr(ctx, none, 5, 0.85), None, "real"),
+        "weighted_reverse_pagerank_5": (lambda: tier.tier_score_wrpr(ctx, train, 5, 0.85), None, "real"),
+    }
+    for name, (make, t_known, kind) in makers.items():
+        sc, t = timed(make)
+        place = tier.tier_place if kind == "int" else tier.tier_place_scores
+        slot, n_hot = place(ctx, sc, budget)
+        hits = sum(int((slot[f.long()] >= 0).sum()) for f in frontiers)
+        res[name] = {"score_ms": t_known if t_known is not None else t, "hit_fraction": round(hits / rows, 4)}
+    tier.tier_presample(ctx, train, wl.batch_size, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
+    tier.tier_place(ctx, counts, budget, want_slot_map=False)          # leave the context as the main run had it
+    return res
 
 
 def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log):
