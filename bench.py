@@ -94,18 +94,37 @@ def main():
     B = tier.tier_max_batches(ctx)                 # mini-batches sampled side by side per call
     groups = [list(range(g, min(g + B, n_batches))) for g in range(0, n_batches, B)]
     bseed = [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in range(n_batches)]
-    blocks = tier.BlocksBatch(n, bs, wl.fanouts, B, dev)
-    out = torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=dev)
+    # two sets of block buffers: while one group's mini-batches are gathered (gather stream,
+    # host-link bound) the next group is sampled (main stream, latency bound)
+    blocks2 = [tier.BlocksBatch(n, bs, wl.fanouts, B, dev) for _ in range(2)]
+    blocks = blocks2[0]
+    out_buf = [torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=dev)]
     counts = torch.empty(n, dtype=torch.int32, device=dev)
     L = len(wl.fanouts)
+    gs = torch.cuda.Stream()
+    tier.tier_set_gather_stream(ctx, gs)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    def sample_group(g):
+    def sample_group(g, into=None):
         lo = g[0] * bs
         hi = min(n_train, (g[-1] + 1) * bs)
-        return tier.tier_sample_minibatches(ctx, epoch_ids[lo:hi], bs, [bseed[b] for b in g], wl.fanouts, blocks)
+        return tier.tier_sample_minibatches(ctx, epoch_ids[lo:hi], bs, [bseed[b] for b in g], wl.fanouts,
+                                            into if into is not None else blocks)
+
+    def timed_gather(blk, nb):
+        """One gather launch (all nb mini-batches of a group) bracketed by events on its stream."""
+        rows = sum(blk.n_nodes[i][L] for i in range(nb))
+        if rows > out_buf[0].shape[0]:             # grows during warm-up only
+            torch.cuda.synchronize()
+            out_buf[0] = torch.empty((int(rows * 1.1), wl.dim), dtype=dtype, device=dev)
+        with torch.cuda.stream(gs):
+            a, b_ = ev(), ev()
+            a.record()
+            tier.tier_gather_minibatches(ctx, blk, nb, out_buf[0])
+            b_.record()
+        return a, b_, rows
 
     def step(record):
-        ev = lambda: torch.cuda.Event(enable_timing=True)
         e_begin, e_pre, e_place = ev(), ev(), ev()
         e_begin.record()
         tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
@@ -114,19 +133,22 @@ def main():
         e_place.record()
         rows = edges = 0
         s_pairs, g_pairs = [], []
-        for g in groups:
-            s0, s1 = ev(), ev()
-            s0.record()
-            blk = sample_group(g)
-            s1.record()
-            s_pairs.append((s0, s1))
-            for i, b in enumerate(g):
-                g0, g1 = ev(), ev()
-                g0.record()
-                tier.tier_gather_features(ctx, blk.frontier(i), out)
-                g1.record()
-                g_pairs.append((g0, g1))
-                rows += blk.n_nodes[i][L]; edges += sum(blk.n_edges[i])
+        s0, s1 = ev(), ev()
+        s0.record(); blk = sample_group(groups[0], blocks2[0]); s1.record()
+        s_pairs.append((s0, s1))
+        reads_done = [None, None]                  # last gather that reads blocks2[i]
+        for gi, g in enumerate(groups):
+            a, b_, r = timed_gather(blk, len(g))
+            g_pairs.append((a, b_))
+            rows += r; edges += sum(sum(blk.n_edges[i]) for i in range(len(g)))
+            reads_done[gi % 2] = b_
+            if gi + 1 < len(groups):
+                nxt = (gi + 1) % 2
+                if reads_done[nxt] is not None:
+                    reads_done[nxt].synchronize()  # its ids are about to be overwritten
+                s0, s1 = ev(), ev()
+                s0.record(); blk = sample_group(groups[gi + 1], blocks2[nxt]); s1.record()
+                s_pairs.append((s0, s1))
         torch.cuda.synchronize()
         if record is not None:
             record["presample_ms"].append(e_begin.elapsed_time(e_pre))
@@ -159,9 +181,8 @@ def main():
     hit_rows = 0
     for g in groups:
         blk = sample_group(g)
-        for i in range(len(g)):
-            _, h, m = tier.tier_gather_features(ctx, blk.frontier(i), out, want_stats=True)
-            hit_rows += h
+        _, _, h, m = tier.tier_gather_minibatches(ctx, blk, len(g), out_buf[0], want_stats=True)
+        hit_rows += h
     rows, edges = rec["rows"], rec["edges"]
     h = hit_rows / rows if rows else 0.0
     mean = lambda xs: sum(xs) / len(xs) if xs else 0.0
@@ -204,11 +225,9 @@ def main():
             ms = 0.0; nrows = 0; nl = 0
             for g in groups[:4]:
                 blk = sample_group(g)
-                for i in range(len(g)):
-                    a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record(); tier.tier_gather_features(ctx, blk.frontier(i), out); b_.record()
-                    torch.cuda.synchronize()
-                    ms += a.elapsed_time(b_); nrows += blk.n_nodes[i][L]; nl += 1
+                a, b_, r = timed_gather(blk, len(g))
+                torch.cuda.synchronize()
+                ms += a.elapsed_time(b_); nrows += r; nl += 1
             if name == "all_hit":
                 streams[name] = {"hbm_GBps": round(nrows * alg_bytes_row / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak":
                                  round(nrows * alg_bytes_row / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
@@ -220,6 +239,7 @@ def main():
         roofline["streams"] = streams
 
     scores = None
+    out = out_buf[0]
     if not args.no_scores:
         scores = score_comparison(tier, synth, torch, ctx, wl, counts, train, budget, groups, sample_group, L)
 
@@ -238,12 +258,13 @@ def main():
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"{wl.name}{'' if scale == 1.0 else f' at scale {scale:g}'}: {wl.graph} graph, {n} nodes, {indices.numel()} edges, "
                                f"{wl.dim} x {wl.dtype} features, fanout {list(wl.fanouts)}, batch {bs}, "
-                               f"{n_batches} mini-batches per epoch sampled {B} per call, HBM budget {budget} B ({rec['n_hot']} rows)"},
+                               f"{n_batches} mini-batches per epoch sampled and gathered {B} per call, HBM budget {budget} B ({rec['n_hot']} rows)"},
         "sampled_edges_per_s": round(edges / (sample_ms * 1e-3)) if sample_ms else None,
         "gather_GBps": round(gathered_bytes / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
         "rows_per_epoch": rows, "edges_per_epoch": edges, "hit_fraction": round(h, 4),
         "host_link_bytes_tiered": (rows - hit_rows) * R, "host_link_bytes_untiered": rows * R,
         "host_link_reduction": round(h, 4),
+        "phase_note": "sample and gather run on two streams and overlap; their sums are per-stream busy times",
         "phase_ms": {"presample": round(mean(rec["presample_ms"]), 3), "place": round(mean(rec["place_ms"]), 3),
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3)},
         "roofline": roofline, "score_functions": scores, "reordered": reorder, "cpu_baseline": cpu,
@@ -316,20 +337,20 @@ def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget,
         ep = train2[order_e].contiguous()
         B = tier.tier_max_batches(ctx2)
         blocks = tier.BlocksBatch(n, bs, wl.fanouts, B, dev)
-        out = torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=dev)
+        out = None
         rows = hits = 0; ms = 0.0; launches = 0
         for g0 in range(0, n_batches, B):
             g = list(range(g0, min(g0 + B, n_batches)))
             blk = tier.tier_sample_minibatches(ctx2, ep[g[0] * bs: min(n_train, (g[-1] + 1) * bs)], bs,
                                                [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in g], wl.fanouts,
                                                blocks)
-            evs = []
-            for i in range(len(g)):
-                a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(); tier.tier_gather_features(ctx2, blk.frontier(i), out); b_.record()
-                evs.append((a, b_)); rows += blk.n_nodes[i][L]
+            r = sum(blk.n_nodes[i][L] for i in range(len(g)))
+            if out is None or out.shape[0] < r:
+                out = torch.empty((int(r * 1.2), wl.dim), dtype=dtype, device=dev)
+            a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); tier.tier_gather_minibatches(ctx2, blk, len(g), out); b_.record()
             torch.cuda.synchronize()
-            ms += sum(a.elapsed_time(b_) for a, b_ in evs); launches += len(evs)
+            ms += a.elapsed_time(b_); launches += 1; rows += r
             hits += sum(int((blk.frontier(i) < n_hot).sum()) for i in range(len(g)))
         R = ctx2.row_bytes
         h = hits / rows if rows else 0.0

@@ -249,6 +249,26 @@ int tier_max_batches(const tier_ctx *ctx);
 int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n, void *out,
                          tier_gather_stats *stats);
 
+/* The gathers of several mini-batches in one launch (one mini-batch's rows are too few
+ * to keep the host link and the GPU busy across a launch boundary).  Mini-batch b reads the
+ * ids nodes[b * nodes_stride .. + n_rows[b]) (the layout of tier_blocks_batch) and writes
+ * its rows from row out_row_offset[b] of out on, n_rows[b] dense rows (the caller packs
+ * the mini-batches, e.g. at the running sum of n_rows).  nodes: (device); n_rows,
+ * out_row_offset: (host) n_batches entries; 1 <= n_batches <= TIER_MAX_BATCHES; out:
+ * (device) 16-byte aligned.  stats as in tier_gather_features, summed over the launch. */
+int tier_gather_minibatches(tier_ctx *ctx, const int32_t *nodes, int64_t nodes_stride, const int64_t *n_rows,
+                            const int64_t *out_row_offset, int32_t n_batches, void *out,
+                            tier_gather_stats *stats);
+
+/* Put the gathers of this context on a stream of their own (NULL = back to the stream of
+ * tier_create), so that a caller can sample the next mini-batches while the current ones
+ * are gathered (sampling is bound by launch and memory latency, the gather by the host
+ * link; they overlap well).  The gather reads only ids, the slot map and the two tiers,
+ * all of which sampling leaves alone; ordering between the two streams (ids complete
+ * before the gather, gather complete before the ids are overwritten) is the caller's,
+ * and tier_place / tier_place_boundary must not run while gathers are in flight. */
+int tier_set_gather_stream(tier_ctx *ctx, void *stream);
+
 const char *tier_strerror(int status);
 /* hipError_t value of the last failing HIP call seen by this context (0 if none). */
 int tier_last_hip_error(const tier_ctx *ctx);

@@ -120,6 +120,9 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipFree(ctx->summary);
     (void)hipFree(ctx->slot);
     (void)hipFree(ctx->cache);
+    (void)hipStreamSynchronize(ctx->gather_stream);
+    (void)hipFree(ctx->gmeta);
+    (void)hipHostFree(ctx->gmeta_host);
     (void)hipFree(ctx->meta);
     (void)hipHostFree(ctx->meta_host);
     (void)hipFree(ctx->partial_hop);
@@ -161,6 +164,8 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     TIER_HIP(c, hipMalloc(&c->slot, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->meta, S * META_WORDS * sizeof(int64_t)));
     TIER_HIP(c, hipHostMalloc((void **)&c->meta_host, S * META_WORDS * sizeof(int64_t), hipHostMallocDefault));
+    TIER_HIP(c, hipMalloc(&c->gmeta, META_WORDS * sizeof(int64_t)));
+    TIER_HIP(c, hipHostMalloc((void **)&c->gmeta_host, META_WORDS * sizeof(int64_t), hipHostMallocDefault));
     TIER_HIP(c, hipMalloc(&c->partial_hop, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->partial_bm, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
     k_fill_i32<<<grid_for(n * (int64_t)S, 256, 8192), 256, 0, c->stream>>>(c->local_idx, n * (int64_t)S, -1);
@@ -168,6 +173,7 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
                                                                                   c->n_words * (int64_t)S, 0);
     k_fill_i32<<<grid_for(c->n_sum * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->summary,
                                                                                 c->n_sum * (int64_t)S, 0);
+    k_fill_i32<<<1, 64, 0, c->stream>>>((int32_t *)c->gmeta, META_WORDS * 2, 0);
     k_fill_i32<<<4, 256, 0, c->stream>>>((int32_t *)c->meta, (int64_t)S * META_WORDS * 2, 0);
     TIER_HIP(c, hipGetLastError());
 
@@ -196,6 +202,7 @@ int tier_create(tier_ctx **out, const tier_csr *csr, const tier_feat *feat, void
     tier_ctx *c = new (std::nothrow) tier_ctx();
     if (!c) return TIER_ENOMEM;
     c->stream = (hipStream_t)stream;
+    c->gather_stream = c->stream;
     c->n_nodes = csr->n_nodes;
     c->n_edges = csr->n_edges;
     c->indptr = csr->indptr;
@@ -225,5 +232,13 @@ const char *tier_strerror(int status)
 }
 
 int tier_last_hip_error(const tier_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+int tier_set_gather_stream(tier_ctx *ctx, void *stream)
+{
+    if (!ctx) return TIER_EINVAL;
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+    ctx->gather_stream = stream ? (hipStream_t)stream : ctx->stream;
+    return TIER_OK;
+}
 
 }  // extern "C"

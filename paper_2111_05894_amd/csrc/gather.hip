@@ -12,20 +12,29 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kRowsInFlight = 4;
 
+// The id lists one launch serves (blockIdx.y picks one): a mini-batch each.
+struct id_lists_t {
+    const int32_t *ids[TIER_MAX_BATCHES];
+    int64_t n[TIER_MAX_BATCHES];
+    int64_t out_row[TIER_MAX_BATCHES];   // first output row of the list
+};
+
 // MODE: GATHER_SLOT     hot <=> slot[id] >= 0, cache row = slot[id]      (ids keep their meaning)
 //       GATHER_BOUNDARY hot <=> id < n_hot, cache row = id, cold row = id - n_hot of the cold
 //                       part (rows in rank order: the two-way branch of Listing 1)
 //       GATHER_HOST     every row from host memory: the untiered copy that fills the HBM
 //                       cache at placement time
 template <int LPR, int MODE>
-__global__ __launch_bounds__(kBlock) void k_gather(const int32_t *__restrict__ ids, int64_t n,
-                                                   const int32_t *__restrict__ slot,
+__global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32_t *__restrict__ slot,
                                                    const uint4 *__restrict__ cache,
                                                    const uint4 *__restrict__ host,
-                                                   uint4 *__restrict__ out, int cpr, int64_t n_nodes,
+                                                   uint4 *__restrict__ out_base, int cpr, int64_t n_nodes,
                                                    int64_t n_hot, int64_t *__restrict__ meta, int count_hits)
 {
     constexpr int kGroups = kBlock / LPR;
+    const int32_t *__restrict__ ids = lists.ids[blockIdx.y];
+    const int64_t n = lists.n[blockIdx.y];
+    uint4 *__restrict__ out = out_base + lists.out_row[blockIdx.y] * cpr;
     const int lane = threadIdx.x % LPR;
     const int64_t group = (int64_t)blockIdx.x * kGroups + threadIdx.x / LPR;
     const int64_t n_groups = (int64_t)gridDim.x * kGroups;
@@ -79,24 +88,31 @@ __global__ __launch_bounds__(kBlock) void k_gather(const int32_t *__restrict__ i
 }
 
 __global__ void k_clear_hits(int64_t *meta) { meta[META_HIT_ROWS] = 0; }
+__global__ void k_clear_gather_error(int64_t *meta) { meta[META_ERROR] = 0; }
 
 }  // namespace
 
-int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, void *out, bool count_hits)
+// Cache fills (GATHER_HOST) run on the context's main stream, gathers on the gather stream
+// with bookkeeping words of their own.
+static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, void *out,
+                        bool count_hits)
 {
-    if (n <= 0) return TIER_OK;
+    hipStream_t st = mode == GATHER_HOST ? ctx->stream : ctx->gather_stream;
+    int64_t *meta = mode == GATHER_HOST ? ctx->meta : ctx->gmeta;
+    if (count_hits) k_clear_hits<<<1, 1, 0, st>>>(meta);
+    if (n_max <= 0) return TIER_OK;
     const int cpr = (int)(ctx->row_bytes / 16);
     int lpr = 8;
     while (lpr < cpr && lpr < 64) lpr *= 2;
     const int groups = kBlock / lpr;
-    int64_t blocks = (n + (int64_t)groups * kRowsInFlight - 1) / ((int64_t)groups * kRowsInFlight);
+    int64_t blocks = (n_max + (int64_t)groups * kRowsInFlight - 1) / ((int64_t)groups * kRowsInFlight);
     const int64_t max_blocks = 256 * 64;
     if (blocks > max_blocks) blocks = max_blocks;
-    if (count_hits) k_clear_hits<<<1, 1, 0, ctx->stream>>>(ctx->meta);
+    const dim3 grid((unsigned)blocks, (unsigned)n_lists);
 #define GATHER_LAUNCH(L, M)                                                                          \
-    k_gather<L, M><<<(int)blocks, kBlock, 0, ctx->stream>>>(                                         \
-        ids, n, ctx->slot, (const uint4 *)ctx->cache, (const uint4 *)ctx->host_rows, (uint4 *)out,   \
-        cpr, ctx->n_nodes, ctx->n_hot, ctx->meta, count_hits ? 1 : 0)
+    k_gather<L, M><<<grid, kBlock, 0, st>>>(lists, ctx->slot, (const uint4 *)ctx->cache,             \
+                                            (const uint4 *)ctx->host_rows, (uint4 *)out, cpr,        \
+                                            ctx->n_nodes, ctx->n_hot, meta, count_hits ? 1 : 0)
 #define GATHER_CASE(L)                                                                               \
     case L:                                                                                          \
         if (mode == GATHER_SLOT) GATHER_LAUNCH(L, GATHER_SLOT);                                      \
@@ -115,6 +131,55 @@ int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, v
     return TIER_OK;
 }
 
+int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, void *out, bool count_hits)
+{
+    id_lists_t lists = {};
+    lists.ids[0] = ids;
+    lists.n[0] = n;
+    return launch_lists(ctx, lists, 1, n, mode, out, count_hits);
+}
+
+// hit / miss rows of the launch(es) since the last k_clear_hits on the gather stream
+static int read_stats(tier_ctx *ctx, int64_t n_total, tier_gather_stats *stats)
+{
+    TIER_HIP(ctx, hipMemcpyAsync(ctx->gmeta_host, ctx->gmeta, META_WORDS * sizeof(int64_t), hipMemcpyDeviceToHost,
+                                 ctx->gather_stream));
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+    if (ctx->gmeta_host[META_ERROR] != 0) {
+        k_clear_gather_error<<<1, 1, 0, ctx->gather_stream>>>(ctx->gmeta);
+        return TIER_EINVAL;
+    }
+    stats->hit_rows = ctx->gmeta_host[META_HIT_ROWS];
+    stats->miss_rows = n_total - stats->hit_rows;
+    return TIER_OK;
+}
+
+extern "C" int tier_gather_minibatches(tier_ctx *ctx, const int32_t *nodes, int64_t nodes_stride,
+                                       const int64_t *n_rows, const int64_t *out_row_offset, int32_t n_batches,
+                                       void *out, tier_gather_stats *stats)
+{
+    if (!ctx || !n_rows || !out_row_offset || n_batches < 1 || n_batches > TIER_MAX_BATCHES || nodes_stride < 0)
+        return TIER_EINVAL;
+    if (((uintptr_t)out & 15u) != 0) return TIER_EINVAL;
+    if (!ctx->placed) return TIER_ESTATE;
+    id_lists_t lists = {};
+    int64_t n_max = 0, n_total = 0;
+    for (int b = 0; b < n_batches; ++b) {
+        if (n_rows[b] < 0 || out_row_offset[b] < 0 || n_rows[b] > nodes_stride) return TIER_EINVAL;
+        lists.ids[b] = nodes + (int64_t)b * nodes_stride;
+        lists.n[b] = n_rows[b];
+        lists.out_row[b] = out_row_offset[b];
+        n_max = n_rows[b] > n_max ? n_rows[b] : n_max;
+        n_total += n_rows[b];
+    }
+    if (n_total > 0 && (!nodes || !out)) return TIER_EINVAL;
+    int rc = launch_lists(ctx, lists, n_batches, n_max, ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT, out,
+                          stats != nullptr);
+    if (rc != TIER_OK) return rc;
+    if (stats) return read_stats(ctx, n_total, stats);
+    return TIER_OK;
+}
+
 extern "C" int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n, void *out,
                                     tier_gather_stats *stats)
 {
@@ -123,15 +188,6 @@ extern "C" int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n
     if (!ctx->placed) return TIER_ESTATE;
     int rc = tier_launch_gather(ctx, ids, n, ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT, out, stats != nullptr);
     if (rc != TIER_OK) return rc;
-    if (stats) {
-        stats->hit_rows = 0;
-        stats->miss_rows = 0;
-        if (n > 0) {
-            rc = tier_sync_meta(ctx);
-            if (rc != TIER_OK) return rc;
-            stats->hit_rows = ctx->meta_host[META_HIT_ROWS];
-            stats->miss_rows = n - stats->hit_rows;
-        }
-    }
+    if (stats) return read_stats(ctx, n, stats);
     return TIER_OK;
 }

@@ -319,6 +319,7 @@ static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget
 
     // (re)build the HBM cache: cache row r = feature row of the node of rank r
     TIER_HIP(ctx, hipStreamSynchronize(st));
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));   // no gather may still read the old cache
     ctx->placed = false;
     ctx->boundary = false;
     if (ctx->cache) TIER_HIP(ctx, hipFree(ctx->cache));
@@ -389,6 +390,7 @@ extern "C" int tier_place_boundary(tier_ctx *ctx, uint64_t budget_bytes, int64_t
     int64_t n_hot = (int64_t)(budget_bytes / (uint64_t)ctx->row_bytes);
     if (n_hot > ctx->n_nodes) n_hot = ctx->n_nodes;
     TIER_HIP(ctx, hipStreamSynchronize(st));
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
     ctx->placed = false;
     if (ctx->cache) TIER_HIP(ctx, hipFree(ctx->cache));
     ctx->cache = nullptr;

@@ -21,6 +21,9 @@ enum {
 
 struct tier_ctx {
     hipStream_t stream;
+    hipStream_t gather_stream;   // stream of tier_gather_features (= stream unless set apart)
+    int64_t *gmeta;              // device: error flag and hit counter of the gather stream
+    int64_t *gmeta_host;         // pinned mirror
     int device;
     int last_hip;
     // graph and features (referenced, caller-owned)

@@ -24,7 +24,7 @@ EXPORTS = (
     "tier_sample_minibatches", "tier_max_batches",
     "tier_score_degree", "tier_score_wrpr", "tier_rank_scores", "tier_place_scores",
     "tier_rank", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
-    "tier_gather_features", "tier_strerror", "tier_last_hip_error",
+    "tier_gather_features", "tier_gather_minibatches", "tier_set_gather_stream", "tier_strerror", "tier_last_hip_error",
 )
 
 
@@ -94,6 +94,9 @@ def _load():
         lib.tier_relabel_ids.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         lib.tier_place_boundary.argtypes = [C.c_void_p, C.c_uint64, i64p]
         lib.tier_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(_Stats)]
+        lib.tier_gather_minibatches.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, i64p, i64p, C.c_int32, C.c_void_p,
+                                                C.POINTER(_Stats)]
+        lib.tier_set_gather_stream.argtypes = [C.c_void_p, C.c_void_p]
         lib.tier_strerror.argtypes = [C.c_int]; lib.tier_strerror.restype = C.c_char_p
         lib.tier_last_hip_error.argtypes = [C.c_void_p]
         _lib = lib
@@ -397,6 +400,35 @@ def tier_sample_minibatches(ctx: Context, seeds: torch.Tensor, batch_size: int, 
         blocks.n_nodes[s] = list(blocks._nn[s * (MAX_LAYERS + 1): s * (MAX_LAYERS + 1) + L + 1])
         blocks.n_edges[s] = list(blocks._ne[s * MAX_LAYERS: s * MAX_LAYERS + L])
     return blocks
+
+
+def tier_gather_minibatches(ctx: Context, blocks: "BlocksBatch", n_batches: int, out: torch.Tensor = None,
+                            want_stats: bool = False):
+    """Rows of the final frontiers of the first n_batches mini-batches of ``blocks`` in one
+    launch, packed back to back.  Returns (out, row_offsets) or (out, row_offsets, hit, miss)."""
+    L = len(blocks.fanouts)
+    n_rows = [blocks.n_nodes[b][L] for b in range(n_batches)]
+    offs = [0] * n_batches
+    for b in range(1, n_batches):
+        offs[b] = offs[b - 1] + n_rows[b - 1]
+    total = offs[-1] + n_rows[-1]
+    if out is None:
+        out = torch.empty((total, ctx.dim), dtype=ctx.dtype, device=blocks.nodes.device)
+    if not (out.is_cuda and out.is_contiguous() and out.numel() * out.element_size() >= total * ctx.row_bytes):
+        raise TypeError("out: contiguous device tensor of sum(n_rows) * row_bytes bytes")
+    nr = (C.c_int64 * n_batches)(*n_rows); of = (C.c_int64 * n_batches)(*offs)
+    st = _Stats()
+    rc = _load().tier_gather_minibatches(ctx.handle, C.c_void_p(blocks.nodes.data_ptr()), blocks.nodes.shape[1], nr, of,
+                                         n_batches, C.c_void_p(out.data_ptr()), C.byref(st) if want_stats else None)
+    _check(rc, "tier_gather_minibatches")
+    return (out, offs, st.hit_rows, st.miss_rows) if want_stats else (out, offs)
+
+
+def tier_set_gather_stream(ctx: Context, stream=None):
+    """stream: a torch.cuda.Stream (kept alive by the context) or None for the context's own."""
+    ctx._gather_stream = stream
+    _check(_load().tier_set_gather_stream(ctx.handle, C.c_void_p(stream.cuda_stream if stream is not None else 0)),
+           "tier_set_gather_stream")
 
 
 def tier_gather_features(ctx: Context, ids: torch.Tensor, out: torch.Tensor = None, want_stats: bool = False):

@@ -266,6 +266,31 @@ def test_gather_matches_oracle(dim, dtype):
         w.close()
 
 
+def test_batched_gather_equals_per_batch_gathers(small):
+    """One launch for several mini-batches: same rows as a gather per mini-batch and as the oracle."""
+    rng = np.random.default_rng(12)
+    counts = rng.integers(0, 30, small.n).astype(np.uint32)
+    slot, n_hot = tier.tier_place(small.ctx, torch.from_numpy(counts.view(np.int32)).to(DEV), 900 * small.row_bytes)
+    B = tier.tier_max_batches(small.ctx)
+    seeds = rng.choice(small.n, 100 * B - 37, replace=False).astype(np.int32)      # ragged last batch
+    bseeds = [tier.tier_batch_seed(5, 0, b) for b in range(B)]
+    blk = tier.tier_sample_minibatches(small.ctx, torch.from_numpy(seeds).to(DEV), 100, bseeds, (6, 4))
+    out, offs, hit, miss = tier.tier_gather_minibatches(small.ctx, blk, B, want_stats=True)
+    rb = small.row_bytes
+    got = out.view(torch.uint8).cpu().numpy().reshape(-1, rb)
+    hits = 0
+    for b in range(B):
+        ids = blk.frontier(b)
+        one, h, m = tier.tier_gather_features(small.ctx, ids, want_stats=True)
+        hits += h
+        rows = got[offs[b]: offs[b] + ids.numel()]
+        assert np.array_equal(rows, one.view(torch.uint8).cpu().numpy().reshape(-1, rb))
+        assert np.array_equal(rows, small.feat_bytes[ids.cpu().numpy()])
+    assert hit == hits and hit + miss == got.shape[0]
+    out1, offs1 = tier.tier_gather_minibatches(small.ctx, blk, 1)                 # a batch of one
+    assert offs1 == [0] and torch.equal(out1, out[: blk.n_nodes[0][2]])
+
+
 def test_hot_rows_come_from_the_cache():
     """After placement, change the host copy of the hot rows: the gather must still
     return the original bytes for them (read from HBM) and the new bytes for cold rows."""
