@@ -291,6 +291,41 @@ def test_batched_gather_equals_per_batch_gathers(small):
     assert offs1 == [0] and torch.equal(out1, out[: blk.n_nodes[0][2]])
 
 
+def test_gather_on_its_own_stream_while_sampling(small):
+    """Gathers of one group run on a second stream while the next group is sampled into the
+    other set of buffers; every group's rows still match the table."""
+    rng = np.random.default_rng(21)
+    counts = rng.integers(0, 30, small.n).astype(np.uint32)
+    tier.tier_place(small.ctx, torch.from_numpy(counts.view(np.int32)).to(DEV), 700 * small.row_bytes)
+    gs = torch.cuda.Stream()
+    tier.tier_set_gather_stream(small.ctx, gs)
+    try:
+        B = min(4, tier.tier_max_batches(small.ctx))
+        bufs = [tier.BlocksBatch(small.n, 128, (8, 4), B, DEV) for _ in range(2)]
+        seeds = [torch.from_numpy(rng.choice(small.n, 128 * B, replace=False).astype(np.int32)).to(DEV) for _ in range(6)]
+        outs = []
+        blk = tier.tier_sample_minibatches(small.ctx, seeds[0], 128, [g * 10 + b for g in [0] for b in range(B)], (8, 4), bufs[0])
+        done = [None, None]
+        for g in range(6):
+            with torch.cuda.stream(gs):
+                out, offs = tier.tier_gather_minibatches(small.ctx, blk, B)
+                ev = torch.cuda.Event(); ev.record()
+            ids = torch.cat([blk.frontier(b).clone() for b in range(B)])
+            outs.append((out, ids))
+            done[g % 2] = ev
+            if g + 1 < 6:
+                nxt = (g + 1) % 2
+                if done[nxt] is not None:
+                    done[nxt].synchronize()
+                blk = tier.tier_sample_minibatches(small.ctx, seeds[g + 1], 128, [(g + 1) * 10 + b for b in range(B)], (8, 4), bufs[nxt])
+        torch.cuda.synchronize()
+        for out, ids in outs:
+            assert np.array_equal(out.view(torch.uint8).cpu().numpy().reshape(-1, small.row_bytes),
+                                  small.feat_bytes[ids.cpu().numpy()])
+    finally:
+        tier.tier_set_gather_stream(small.ctx, None)
+
+
 def test_hot_rows_come_from_the_cache():
     """After placement, change the host copy of the hot rows: the gather must still
     return the original bytes for them (read from HBM) and the new bytes for cold rows."""
