@@ -44,6 +44,7 @@ struct wide_t {
     int64_t n_seeds_total;
     int32_t batch_size;
     int32_t n_slots;
+    int32_t count_edges;         // != 0: add the sampled edges to META_TOTAL_EDGES (costs an atomic per block)
     int64_t n_nodes;             // graph nodes
     int64_t n_words;             // bitmap words per slot
     int64_t n_sum;               // summary words per slot (one bit per bitmap word)
@@ -305,11 +306,11 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, const OffT *__r
         const int32_t d = (int32_t)(indptr[u + 1] - beg);
         int32_t rp = 0;
         if (BLOCKS) rp = row_ptr[i];
-        else if (lane == 0) edges += d < k ? d : k;
+        else if (w.count_edges && lane == 0) edges += d < k ? d : k;
         sample_one<G, BLOCKS, TWO_LEVEL, OffT>(lane, u, beg, d, k, layer, key0, key1, indices, v.local_idx, v.bitmap, v.summary,
                                     eid, col, rp);
     }
-    if (!BLOCKS) {
+    if (!BLOCKS && w.count_edges) {
         int tot = block_sum(edges, s_wave);
         if (threadIdx.x == 0 && tot)
             atomicAdd((unsigned long long *)&w.meta[META_TOTAL_EDGES], (unsigned long long)tot);
@@ -694,6 +695,7 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
             const int slots = (int)(n_batches - b < ctx->n_slots ? n_batches - b : ctx->n_slots);
             const int64_t lo = b * batch_size;
             wide_t w = make_wide(ctx, train_ids + lo, n_train - lo, batch_size, slots, ctx->ps_nodes, stride);
+            w.count_edges = total_edges != nullptr;
             for (int s = 0; s < slots; ++s) {
                 const uint64_t bs = tier_batch_seed(seed, (uint32_t)e, (uint32_t)(b + s));
                 w.key0[s] = (uint32_t)bs;
