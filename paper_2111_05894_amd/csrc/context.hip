@@ -164,8 +164,8 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     TIER_HIP(c, hipMalloc(&c->slot, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->meta, S * META_WORDS * sizeof(int64_t)));
     TIER_HIP(c, hipHostMalloc((void **)&c->meta_host, S * META_WORDS * sizeof(int64_t), hipHostMallocDefault));
-    TIER_HIP(c, hipMalloc(&c->gmeta, META_WORDS * sizeof(int64_t)));
-    TIER_HIP(c, hipHostMalloc((void **)&c->gmeta_host, META_WORDS * sizeof(int64_t), hipHostMallocDefault));
+    TIER_HIP(c, hipMalloc(&c->gmeta, GMETA_WORDS * sizeof(int64_t)));
+    TIER_HIP(c, hipHostMalloc((void **)&c->gmeta_host, GMETA_WORDS * sizeof(int64_t), hipHostMallocDefault));
     TIER_HIP(c, hipMalloc(&c->partial_hop, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->partial_bm, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
     k_fill_i32<<<grid_for(n * (int64_t)S, 256, 8192), 256, 0, c->stream>>>(c->local_idx, n * (int64_t)S, -1);
@@ -173,7 +173,7 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
                                                                                   c->n_words * (int64_t)S, 0);
     k_fill_i32<<<grid_for(c->n_sum * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->summary,
                                                                                 c->n_sum * (int64_t)S, 0);
-    k_fill_i32<<<1, 64, 0, c->stream>>>((int32_t *)c->gmeta, META_WORDS * 2, 0);
+    k_fill_i32<<<1, 64, 0, c->stream>>>((int32_t *)c->gmeta, GMETA_WORDS * 2, 0);
     k_fill_i32<<<4, 256, 0, c->stream>>>((int32_t *)c->meta, (int64_t)S * META_WORDS * 2, 0);
     TIER_HIP(c, hipGetLastError());
 

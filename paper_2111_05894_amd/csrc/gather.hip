@@ -85,13 +85,25 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
     }
     if (bad) atomicOr((int *)&meta[META_ERROR], 1);
     if (count_hits) {
-        // one atomic per wavefront
+        // one atomic per block, on one of META_HIT_STRIPES counters
+        __shared__ int s_hits[kBlock / 64];
         for (int off = 32; off > 0; off >>= 1) hits += __shfl_down(hits, off);
-        if ((threadIdx.x & 63) == 0 && hits) atomicAdd((unsigned long long *)&meta[META_HIT_ROWS], (unsigned long long)hits);
+        if ((threadIdx.x & 63) == 0) s_hits[threadIdx.x >> 6] = hits;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int t = 0;
+            for (int i = 0; i < kBlock / 64; ++i) t += s_hits[i];
+            if (t)
+                atomicAdd((unsigned long long *)&meta[META_HIT_ROWS + ((blockIdx.x + blockIdx.y) & (META_HIT_STRIPES - 1))],
+                          (unsigned long long)t);
+        }
     }
 }
 
-__global__ void k_clear_hits(int64_t *meta) { meta[META_HIT_ROWS] = 0; }
+__global__ void k_clear_hits(int64_t *meta)
+{
+    if (threadIdx.x < META_HIT_STRIPES) meta[META_HIT_ROWS + threadIdx.x] = 0;
+}
 __global__ void k_clear_gather_error(int64_t *meta) { meta[META_ERROR] = 0; }
 
 }  // namespace
@@ -103,7 +115,7 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
 {
     hipStream_t st = mode == GATHER_HOST ? ctx->stream : ctx->gather_stream;
     int64_t *meta = mode == GATHER_HOST ? ctx->meta : ctx->gmeta;
-    if (count_hits) k_clear_hits<<<1, 1, 0, st>>>(meta);
+    if (count_hits) k_clear_hits<<<1, META_HIT_STRIPES, 0, st>>>(meta);
     if (n_max <= 0) return TIER_OK;
     const int cpr = (int)(ctx->row_bytes / 16);
     int lpr = 8;
@@ -146,14 +158,15 @@ int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, v
 // hit / miss rows of the launch(es) since the last k_clear_hits on the gather stream
 static int read_stats(tier_ctx *ctx, int64_t n_total, tier_gather_stats *stats)
 {
-    TIER_HIP(ctx, hipMemcpyAsync(ctx->gmeta_host, ctx->gmeta, META_WORDS * sizeof(int64_t), hipMemcpyDeviceToHost,
+    TIER_HIP(ctx, hipMemcpyAsync(ctx->gmeta_host, ctx->gmeta, GMETA_WORDS * sizeof(int64_t), hipMemcpyDeviceToHost,
                                  ctx->gather_stream));
     TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
     if (ctx->gmeta_host[META_ERROR] != 0) {
         k_clear_gather_error<<<1, 1, 0, ctx->gather_stream>>>(ctx->gmeta);
         return TIER_EINVAL;
     }
-    stats->hit_rows = ctx->gmeta_host[META_HIT_ROWS];
+    stats->hit_rows = 0;
+    for (int i = 0; i < META_HIT_STRIPES; ++i) stats->hit_rows += ctx->gmeta_host[META_HIT_ROWS + i];
     stats->miss_rows = n_total - stats->hit_rows;
     return TIER_OK;
 }

@@ -13,9 +13,11 @@ enum {
     META_TOTAL_ROWS = META_NEDGES + TIER_MAX_LAYERS,
     META_TOTAL_EDGES,
     META_ERROR,                               // != 0: a kernel saw an id outside [0, n_nodes)
-    META_HIT_ROWS,
+    META_HIT_ROWS,                            // first of META_HIT_STRIPES counters (gather bookkeeping only)
     META_WORDS
 };
+#define META_HIT_STRIPES 64                   // hit counters are striped over blocks to keep the atomics apart
+#define GMETA_WORDS (META_WORDS + META_HIT_STRIPES)
 
 #define TIER_SCAN_BLOCKS 1024                 // upper limit of blocks in a two-phase scan
 
