@@ -45,6 +45,8 @@ def main():
                     help="skip the reordered variant (graph and table renamed by rank, gather by boundary)")
     ap.add_argument("--no-scores", action="store_true",
                     help="skip the comparison of score functions (presampled counts vs the paper's scores)")
+    ap.add_argument("--sweeps", action="store_true",
+                    help="also sweep the HBM budget and the sampling depth (analogues of the paper's Fig. 5 and 6)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink nodes, edges and budget alike")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for profiler byte counters)")
@@ -257,6 +259,10 @@ def main():
     if not args.no_scores:
         scores = score_comparison(tier, synth, torch, ctx, wl, counts, train, budget, groups, sample_group, L)
 
+    sweeps = None
+    if args.sweeps:
+        sweeps = run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_group, L, log)
+
     reorder = None
     if not args.no_reorder:
         reorder = reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log)
@@ -283,7 +289,7 @@ def main():
                       "sample_alone_ms is the same epoch's sampling with the GPU to itself (basis of sampled_edges_per_s)",
         "phase_ms": {"presample": round(mean(rec["presample_ms"]), 3), "place": round(mean(rec["place_ms"]), 3),
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3)},
-        "roofline": roofline, "score_functions": scores, "reordered": reorder, "cpu_baseline": cpu,
+        "roofline": roofline, "score_functions": scores, "sweeps": sweeps, "reordered": reorder, "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
     ctx.close()
@@ -321,6 +327,52 @@ def score_comparison(tier, synth, torch, ctx, wl, counts, train, budget, groups,
     tier.tier_presample(ctx, train, wl.batch_size, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
     tier.tier_place(ctx, counts, budget, want_slot_map=False)          # leave the context as the main run had it
     return res
+
+
+def run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_group, L, log):
+    """Harness-only analysis on the library's outputs.
+    budget: hit fraction of the measured epoch against the share of rows kept in HBM, for placement by
+    presampled counts and by weighted reverse PageRank (the paper's Fig. 6 sweeps the loaded share).
+    depth: share of all measured accesses that falls on the top 10 % of nodes by score, for fanouts
+    (10,10) .. (10,10,10,10,10) (the paper's Fig. 5), accesses measured by tier_presample with the
+    measured epoch's seed over at most 64 mini-batches."""
+    frontiers = []
+    for g in groups:
+        blk = sample_group(g)
+        frontiers += [blk.frontier(i).clone() for i in range(len(g))]
+    allf = torch.cat(frontiers).long()
+    rows = allf.numel()
+    tier.tier_presample(ctx, train, wl.batch_size, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
+    rank_c, _ = tier.tier_rank(ctx, counts)
+    wr = tier.tier_score_wrpr(ctx, train, 5, 0.85)
+    rank_w, _ = tier.tier_rank_scores(ctx, wr)
+    deg = tier.tier_score_degree(ctx)
+    rank_d, _ = tier.tier_rank(ctx, deg)
+    shares = [0.0, 0.01, 0.02, 0.05, 0.10, 0.15, 0.20, 0.25, 0.50, 1.0]
+    budget = []
+    for p in shares:
+        n_hot = int(p * n)
+        row = {"share_in_hbm": p}
+        for name, rk in (("counts", rank_c), ("wrpr", rank_w), ("degree", rank_d)):
+            h = float((rk[allf] < n_hot).sum()) / rows
+            row[f"hit_{name}"] = round(h, 4)
+        row["host_link_bytes_counts"] = int(round((1 - row["hit_counts"]) * rows)) * R
+        budget.append(row)
+    depth = []
+    sub = train[: min(train.numel(), 64 * wl.batch_size)].contiguous()
+    acc = torch.empty_like(counts)
+    for d in range(2, 6):
+        fan = (10,) * d
+        _, tot_rows, _ = tier.tier_presample(ctx, sub, wl.batch_size, fan, 1, synth.EPOCH_SEED, acc, want_totals=True)
+        a = acc.long()
+        top = int(0.10 * n)
+        row = {"fanouts": list(fan), "rows": tot_rows}
+        for name, rk in (("wrpr", rank_w), ("degree", rank_d)):
+            row[f"top10pct_share_{name}"] = round(float(a[rk < top].sum()) / max(tot_rows, 1), 4)
+        depth.append(row)
+        log(f"[bench] depth sweep {fan}: {row}")
+    tier.tier_presample(ctx, train, wl.batch_size, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
+    return {"budget": budget, "depth": depth}
 
 
 def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log):
