@@ -197,13 +197,15 @@ int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, int32_t *ord
 /* Graph reordering (Sec. 3.2, Alg. 2): the context's graph with every node renamed to
  * rank[node]: new node r has the neighbour list of order[r], in its old order, values
  * renamed.  indptr_new: (device) n_nodes + 1 offsets of the context graph's offset type;
- * indices_new: (device) n_edges ids.  rank/order as from tier_rank.  Waits. */
+ * indices_new: (device) n_edges ids.  rank/order as from tier_rank; TIER_EINVAL (and
+ * nothing written) unless rank is a permutation of 0..n_nodes-1 and order its inverse.  Waits. */
 int tier_reorder_graph(tier_ctx *ctx, const int32_t *rank, const int32_t *order, void *indptr_new,
                        int32_t *indices_new);
 
 /* Feature rows follow their nodes (Sec. 3.2): rows_new[rank[v]] = row v of the context's
  * table.  rows_new: (device-visible: pinned host or device) n_nodes * row_bytes bytes,
- * 16-byte aligned, not overlapping the table.  Asynchronous. */
+ * 16-byte aligned, not overlapping the table.  Waits for a check of rank (TIER_EINVAL
+ * unless it is a permutation), then the copy itself is asynchronous. */
 int tier_reorder_rows(tier_ctx *ctx, const int32_t *rank, void *rows_new);
 
 /* out[i] = rank[ids[i]] (e.g. the training ids of the reordered graph).  ids, out:

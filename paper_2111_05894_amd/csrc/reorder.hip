@@ -18,6 +18,40 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kSpan = 2048;        // edge positions per block of k_relocate
 
+// rank must be a permutation of 0..n-1 and order its inverse: everything below indexes
+// with their values unchecked.
+__global__ void k_check_permutation(const int32_t *__restrict__ rank, const int32_t *__restrict__ order, int64_t n,
+                                    int64_t *__restrict__ meta)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int bad = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint32_t r = (uint32_t)rank[i];
+        if (r >= (uint64_t)n || order[r] != (int32_t)i) bad = 1;      // order[rank[i]] == i for all i <=> bijection
+    }
+    if (bad) atomicOr((int *)&meta[META_ERROR], 1);
+}
+
+// without `order`: every rank in range and taken once (seen: n bits, zero on entry and on exit)
+__global__ void k_check_rank_marks(const int32_t *__restrict__ rank, int64_t n, uint32_t *__restrict__ seen,
+                                   int64_t *__restrict__ meta)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int bad = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint32_t r = (uint32_t)rank[i];
+        if (r >= (uint64_t)n) bad = 1;
+        else if (atomicOr(&seen[r >> 5], 1u << (r & 31)) & (1u << (r & 31))) bad = 1;
+    }
+    if (bad) atomicOr((int *)&meta[META_ERROR], 1);
+}
+
+__global__ void k_clear_words(uint32_t *__restrict__ p, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
 template <typename OffT>
 __global__ void k_scatter_len(const OffT *__restrict__ indptr, const int32_t *__restrict__ rank, int64_t n,
                               OffT *__restrict__ nd_new)
@@ -171,6 +205,10 @@ int reorder_graph(tier_ctx *c, const int32_t *rank, const int32_t *order, OffT *
 {
     const int64_t n = c->n_nodes, ne = c->n_edges;
     hipStream_t st = c->stream;
+    k_check_permutation<<<grid_for(n, kBlock, 4096), kBlock, 0, st>>>(rank, order, n, c->meta);
+    TIER_HIP(c, hipGetLastError());
+    int rc = tier_sync_meta(c);
+    if (rc != TIER_OK) return rc;
     OffT *partial = nullptr;
     TIER_HIP(c, hipMalloc(&partial, 1024 * sizeof(OffT)));
     k_scatter_len<OffT><<<grid_for(n, kBlock, 4096), kBlock, 0, st>>>((const OffT *)c->indptr, rank, n, nd_new);
@@ -205,6 +243,12 @@ int tier_reorder_rows(tier_ctx *ctx, const int32_t *rank, void *rows_new)
     if (!ctx || !rank || !rows_new || ((uintptr_t)rows_new & 15u)) return TIER_EINVAL;
     const int64_t n = ctx->n_nodes;
     if (n == 0) return TIER_OK;
+    // the first slot's bitmap (all zero between sampling calls) marks the ranks seen
+    k_check_rank_marks<<<grid_for(n, kBlock, 4096), kBlock, 0, ctx->stream>>>(rank, n, ctx->bitmap, ctx->meta);
+    k_clear_words<<<grid_for(ctx->n_words, kBlock, 4096), kBlock, 0, ctx->stream>>>(ctx->bitmap, ctx->n_words);
+    TIER_HIP(ctx, hipGetLastError());
+    int rc = tier_sync_meta(ctx);
+    if (rc != TIER_OK) return rc;
     const int cpr = (int)(ctx->row_bytes / 16);
     int lpr = 8;
     while (lpr < cpr && lpr < 64) lpr *= 2;

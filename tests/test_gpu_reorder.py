@@ -57,6 +57,18 @@ def test_reorder_matches_oracle(n, m, i64, dim):
     with pytest.raises(tier.TierError):
         tier.tier_relabel_ids(ctx, rank, torch.tensor([n], dtype=torch.int32, device=DEV))
 
+    # a rank that is no permutation is refused before any kernel indexes with it
+    broken = rank.clone(); broken[0] = broken[1]
+    with pytest.raises(tier.TierError):
+        tier.tier_reorder_graph(ctx, broken, order)
+    with pytest.raises(tier.TierError):
+        tier.tier_reorder_rows(ctx, broken, torch.empty_like(feat).pin_memory())
+    broken[0] = n
+    with pytest.raises(tier.TierError):
+        tier.tier_reorder_rows(ctx, broken, torch.empty_like(feat).pin_memory())
+    ip3, ix3 = tier.tier_reorder_graph(ctx, rank, order)                 # the context is still good
+    assert torch.equal(ip3, ip2) and torch.equal(ix3, ix2)
+
     # a context on the reordered data: boundary placement, gather, and sampling
     ctx2 = tier.tier_create(ip2, ix2, feat2)
     for rows in (0, 1, n // 10, n):
