@@ -133,7 +133,7 @@ int tier_blocks_bounds(int64_t n_graph_nodes, int64_t n_seeds, const int32_t *fa
  * outlive the context.  stream is a hipStream_t (NULL = the default stream).
  * Allocates scratch proportional to n_nodes: 4 bytes per node for the slot map and
  * about 4.2 bytes per node for each mini-batch that can be sampled at once (as many,
- * up to TIER_MAX_BATCHES, as fit in 4 GiB). */
+ * up to TIER_MAX_BATCHES, as fit in 8 GiB). */
 int tier_create(tier_ctx **out, const tier_csr *csr, const tier_feat *feat, void *stream);
 void tier_destroy(tier_ctx *ctx);
 

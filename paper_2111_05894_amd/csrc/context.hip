@@ -153,9 +153,9 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     const int64_t n = c->n_nodes;
     c->n_words = (n + 31) / 32;
     c->n_sum = (c->n_words + 31) / 32;
-    // as many mini-batch slots as fit in 4 GiB of per-node scratch
+    // as many mini-batch slots as fit in 8 GiB of per-node scratch (16 slots up to 121 M nodes)
     const int64_t per_slot = (n + c->n_words + c->n_sum + 1) * 4;
-    int64_t slots = (4LL << 30) / per_slot;
+    int64_t slots = (8LL << 30) / per_slot;
     c->n_slots = (int)(slots < 1 ? 1 : (slots > TIER_MAX_BATCHES ? TIER_MAX_BATCHES : slots));
     const size_t S = (size_t)c->n_slots;
     TIER_HIP(c, hipMalloc(&c->local_idx, S * (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
