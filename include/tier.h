@@ -114,7 +114,9 @@ typedef struct {
 
 typedef struct {
     int64_t hit_rows;    /* rows read from the HBM cache   */
-    int64_t miss_rows;   /* rows read from host memory     */
+    int64_t miss_rows;   /* rows not in the HBM cache      */
+    int64_t link_rows;   /* rows read over the host link: miss_rows, or the distinct ones among them
+                            when tier_set_gather_dedup is on */
 } tier_gather_stats;
 
 /* Pinned, GPU-mapped host memory for a feature table (the zero-copy space of
@@ -261,6 +263,15 @@ int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n, void *out
 int tier_gather_minibatches(tier_ctx *ctx, const int32_t *nodes, int64_t nodes_stride, const int64_t *n_rows,
                             const int64_t *out_row_offset, int32_t n_batches, void *out,
                             tier_gather_stats *stats);
+
+/* Shared misses.  With on != 0 every gather call first finds the distinct cold ids among
+ * all its requests, reads each of those rows over the host link once into an HBM staging
+ * area owned by the context (up to min(requests, n_nodes) rows, grown on demand; n_nodes
+ * bits and 4 n_nodes bytes of scratch besides), and serves all requests from HBM.  Results
+ * are the same; it pays when the mini-batches of one tier_gather_minibatches call overlap
+ * in their cold rows and costs three small kernels otherwise.  Off by default.  Waits for
+ * the gather stream. */
+int tier_set_gather_dedup(tier_ctx *ctx, int on);
 
 /* Put the gathers of this context on a stream of their own (NULL = back to the stream of
  * tier_create), so that a caller can sample the next mini-batches while the current ones

@@ -121,6 +121,11 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipFree(ctx->slot);
     (void)hipFree(ctx->cache);
     (void)hipStreamSynchronize(ctx->gather_stream);
+    (void)hipFree(ctx->gbitmap);
+    (void)hipFree(ctx->stage_slot);
+    (void)hipFree(ctx->gpartial);
+    (void)hipFree(ctx->uniq_ids);
+    (void)hipFree(ctx->stage);
     (void)hipFree(ctx->gmeta);
     (void)hipHostFree(ctx->gmeta_host);
     (void)hipFree(ctx->meta);

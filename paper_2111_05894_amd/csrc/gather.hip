@@ -5,6 +5,13 @@
 // host link) otherwise.  A group of LPR lanes copies one row in 16-byte pieces,
 // so a row is read and written with full-width coalesced accesses; several rows
 // per group are in flight to cover the host link's latency.
+//
+// Shared misses (tier_set_gather_dedup): the mini-batches gathered by one call overlap
+// (on a low-skew 10 M-node graph two thirds of a call's cold rows are requested more
+// than once), so the call can first mark its cold ids in a bitmap over all nodes, turn
+// the bitmap into an ascending list of distinct cold ids (k_gbm_*), fetch those rows
+// over the host link once into an HBM staging area, and then serve every request from
+// HBM: cache rows for hits, staged rows for misses.
 #include "tier_internal.h"
 
 namespace {
@@ -18,6 +25,7 @@ struct id_lists_t {
     const int32_t *ids[TIER_MAX_BATCHES];
     int64_t n[TIER_MAX_BATCHES];
     int64_t out_row[TIER_MAX_BATCHES];   // first output row of the list
+    const int64_t *n_dev;                // non-null: the length of list 0 is read from the device
 };
 
 // MODE: GATHER_SLOT     hot <=> slot[id] >= 0, cache row = slot[id]      (ids keep their meaning)
@@ -25,16 +33,19 @@ struct id_lists_t {
 //                       part (rows in rank order: the two-way branch of Listing 1)
 //       GATHER_HOST     every row from host memory: the untiered copy that fills the HBM
 //                       cache at placement time
-template <int LPR, int MODE>
+// STAGED: cold rows come from the staging area (row stage_slot[id]) instead of host memory.
+template <int LPR, int MODE, bool STAGED>
 __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32_t *__restrict__ slot,
                                                    const uint4 *__restrict__ cache,
                                                    const uint4 *__restrict__ host,
+                                                   const uint4 *__restrict__ stage,
+                                                   const int32_t *__restrict__ stage_slot,
                                                    uint4 *__restrict__ out_base, int cpr, int64_t n_nodes,
                                                    int64_t n_hot, int64_t *__restrict__ meta, int count_hits)
 {
     constexpr int kGroups = kBlock / LPR;
     const int32_t *__restrict__ ids = lists.ids[blockIdx.y];
-    const int64_t n = lists.n[blockIdx.y];
+    const int64_t n = lists.n_dev ? *lists.n_dev : lists.n[blockIdx.y];
     uint4 *__restrict__ out = out_base + lists.out_row[blockIdx.y] * cpr;
     const int lane = threadIdx.x % LPR;
     const int64_t group = (int64_t)blockIdx.x * kGroups + threadIdx.x / LPR;
@@ -59,6 +70,8 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
                     if (s >= 0) {
                         src[j] = cache + (int64_t)s * cpr;
                         hits += (lane == 0);
+                    } else if (STAGED) {
+                        src[j] = stage + (int64_t)stage_slot[id] * cpr;
                     } else if (MODE == GATHER_BOUNDARY) {
                         const uint4 *cold = host + n_hot * cpr;          // first row of the cold part
                         src[j] = cold + ((int64_t)id - n_hot) * cpr;
@@ -100,6 +113,112 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
     }
 }
 
+// ---- shared misses: distinct cold ids of a call ---------------------------------------
+
+template <int MODE>
+__global__ void k_mark_misses(id_lists_t lists, const int32_t *__restrict__ slot, int64_t n_nodes, int64_t n_hot,
+                              uint32_t *__restrict__ bitmap)
+{
+    const int32_t *__restrict__ ids = lists.ids[blockIdx.y];
+    const int64_t n = lists.n[blockIdx.y];
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n; r += stride) {
+        const int32_t id = ids[r];
+        if ((uint32_t)id >= (uint64_t)n_nodes) continue;            // reported by the gather itself
+        const bool hit = MODE == GATHER_SLOT ? slot[id] >= 0 : id < n_hot;
+        if (!hit) {
+            const uint32_t bit = 1u << (id & 31);
+            if (!(bitmap[id >> 5] & bit)) atomicOr(&bitmap[id >> 5], bit);   // most repeats stop at the read
+        }
+    }
+}
+
+__device__ inline int gblock_sum(int x, int *s_wave)
+{
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) s_wave[threadIdx.x >> 6] = x;
+    __syncthreads();
+    int t = 0;
+    for (int i = 0; i < kBlock / 64; ++i) t += s_wave[i];
+    return t;
+}
+
+__device__ inline void gblock_range(int64_t n, int64_t &lo, int64_t &hi)
+{
+    int64_t chunk = (n + gridDim.x - 1) / gridDim.x;
+    chunk = (chunk + kBlock - 1) / kBlock * kBlock;
+    lo = (int64_t)blockIdx.x * chunk;
+    if (lo > n) lo = n;
+    hi = lo + chunk;
+    if (hi > n) hi = n;
+}
+
+__global__ __launch_bounds__(kBlock) void k_gbm_partial(const uint32_t *__restrict__ bitmap, int64_t n_words,
+                                                        int32_t *__restrict__ partial)
+{
+    __shared__ int s_wave[kBlock / 64];
+    int64_t lo, hi;
+    gblock_range(n_words, lo, hi);
+    int sum = 0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) sum += __popc(bitmap[i]);
+    int tot = gblock_sum(sum, s_wave);
+    if (threadIdx.x == 0) partial[blockIdx.x] = tot;
+}
+
+// bitmap -> ascending list of distinct cold ids; stage_slot[id] = its row in the staging area
+__global__ __launch_bounds__(kBlock) void k_gbm_emit(uint32_t *__restrict__ bitmap, int64_t n_words,
+                                                     const int32_t *__restrict__ partial,
+                                                     int32_t *__restrict__ uniq, int32_t *__restrict__ stage_slot,
+                                                     int64_t *__restrict__ meta)
+{
+    __shared__ int s_wave[kBlock / 64];
+    int64_t lo, hi;
+    gblock_range(n_words, lo, hi);
+    int b4 = 0, all = 0;
+    for (int i = threadIdx.x; i < (int)gridDim.x; i += kBlock) {
+        int p = partial[i];
+        all += p;
+        b4 += (i < (int)blockIdx.x) ? p : 0;
+    }
+    int carry = gblock_sum(b4, s_wave);
+    all = gblock_sum(all, s_wave);
+    if (blockIdx.x == 0 && threadIdx.x == 0) meta[META_NFRONT] = all;      // distinct cold rows of this call
+    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    for (int64_t tile = lo; tile < hi; tile += kBlock) {
+        const int64_t i = tile + threadIdx.x;
+        uint32_t bits = i < hi ? bitmap[i] : 0u;
+        int incl = __popc(bits);
+        const int mine = incl;
+        for (int d = 1; d < 64; d <<= 1) {
+            int y = __shfl_up(incl, d);
+            if (l >= d) incl += y;
+        }
+        __syncthreads();
+        if (l == 63) s_wave[w] = incl;
+        __syncthreads();
+        int base = 0, tot = 0;
+        for (int q = 0; q < kBlock / 64; ++q) {
+            int t = s_wave[q];
+            base += q < w ? t : 0;
+            tot += t;
+        }
+        int pos = carry + base + incl - mine;
+        carry += tot;
+        if (bits) {
+            bitmap[i] = 0u;
+            while (bits) {
+                int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                int32_t u = (int32_t)(i * 32 + b);
+                uniq[pos] = u;
+                stage_slot[u] = pos;
+                ++pos;
+            }
+        }
+    }
+}
+
 __global__ void k_clear_hits(int64_t *meta)
 {
     if (threadIdx.x < META_HIT_STRIPES) meta[META_HIT_ROWS + threadIdx.x] = 0;
@@ -108,13 +227,11 @@ __global__ void k_clear_gather_error(int64_t *meta) { meta[META_ERROR] = 0; }
 
 }  // namespace
 
-// Cache fills (GATHER_HOST) run on the context's main stream, gathers on the gather stream
-// with bookkeeping words of their own.
-static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, void *out,
-                        bool count_hits)
+// One k_gather launch.  Cache fills (GATHER_HOST on the main stream) and gathers (on the
+// gather stream, with bookkeeping words of their own) say where they run.
+static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, bool staged,
+                        void *out, bool count_hits, hipStream_t st, int64_t *meta)
 {
-    hipStream_t st = mode == GATHER_HOST ? ctx->stream : ctx->gather_stream;
-    int64_t *meta = mode == GATHER_HOST ? ctx->meta : ctx->gmeta;
     if (count_hits) k_clear_hits<<<1, META_HIT_STRIPES, 0, st>>>(meta);
     if (n_max <= 0) return TIER_OK;
     const int cpr = (int)(ctx->row_bytes / 16);
@@ -125,15 +242,18 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
     const int64_t max_blocks = 1 << 18;     // beyond that groups loop; fewer blocks cost ~5 % of the all-hit rate
     if (blocks > max_blocks) blocks = max_blocks;
     const dim3 grid((unsigned)blocks, (unsigned)n_lists);
-#define GATHER_LAUNCH(L, M)                                                                          \
-    k_gather<L, M><<<grid, kBlock, 0, st>>>(lists, ctx->slot, (const uint4 *)ctx->cache,             \
-                                            (const uint4 *)ctx->host_rows, (uint4 *)out, cpr,        \
-                                            ctx->n_nodes, ctx->n_hot, meta, count_hits ? 1 : 0)
+#define GATHER_LAUNCH(L, M, S)                                                                       \
+    k_gather<L, M, S><<<grid, kBlock, 0, st>>>(lists, ctx->slot, (const uint4 *)ctx->cache,          \
+                                               (const uint4 *)ctx->host_rows, (const uint4 *)ctx->stage, \
+                                               ctx->stage_slot, (uint4 *)out, cpr, ctx->n_nodes,     \
+                                               ctx->n_hot, meta, count_hits ? 1 : 0)
 #define GATHER_CASE(L)                                                                               \
     case L:                                                                                          \
-        if (mode == GATHER_SLOT) GATHER_LAUNCH(L, GATHER_SLOT);                                      \
-        else if (mode == GATHER_BOUNDARY) GATHER_LAUNCH(L, GATHER_BOUNDARY);                         \
-        else GATHER_LAUNCH(L, GATHER_HOST);                                                          \
+        if (mode == GATHER_SLOT && staged) GATHER_LAUNCH(L, GATHER_SLOT, true);                      \
+        else if (mode == GATHER_SLOT) GATHER_LAUNCH(L, GATHER_SLOT, false);                          \
+        else if (mode == GATHER_BOUNDARY && staged) GATHER_LAUNCH(L, GATHER_BOUNDARY, true);         \
+        else if (mode == GATHER_BOUNDARY) GATHER_LAUNCH(L, GATHER_BOUNDARY, false);                  \
+        else GATHER_LAUNCH(L, GATHER_HOST, false);                                                   \
         break;
     switch (lpr) {
         GATHER_CASE(8)
@@ -152,7 +272,57 @@ int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, v
     id_lists_t lists = {};
     lists.ids[0] = ids;
     lists.n[0] = n;
-    return launch_lists(ctx, lists, 1, n, mode, out, count_hits);
+    const bool fill = mode == GATHER_HOST;
+    return launch_lists(ctx, lists, 1, n, mode, false, out, count_hits, fill ? ctx->stream : ctx->gather_stream,
+                        fill ? ctx->meta : ctx->gmeta);
+}
+
+static int grow(tier_ctx *ctx, void **buf, int64_t *cap, int64_t want, size_t elem)
+{
+    if (want <= *cap) return TIER_OK;
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+    if (*buf) TIER_HIP(ctx, hipFree(*buf));
+    *buf = nullptr;
+    *cap = 0;
+    TIER_HIP(ctx, hipMalloc(buf, (size_t)want * elem));
+    *cap = want;
+    return TIER_OK;
+}
+
+// The tiered gather of one call: plain, or with every distinct cold row fetched once.
+static int gather_call(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int64_t n_total, void *out,
+                       bool count_hits)
+{
+    const int mode = ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT;
+    hipStream_t st = ctx->gather_stream;
+    if (!ctx->dedup || n_total == 0)
+        return launch_lists(ctx, lists, n_lists, n_max, mode, false, out, count_hits, st, ctx->gmeta);
+
+    // at most min(requests, nodes) distinct cold rows
+    const int64_t cap = n_total < ctx->n_nodes ? n_total : ctx->n_nodes;
+    int rc = grow(ctx, (void **)&ctx->stage, &ctx->stage_cap, cap, (size_t)ctx->row_bytes);
+    if (rc == TIER_OK) rc = grow(ctx, (void **)&ctx->uniq_ids, &ctx->uniq_cap, cap, sizeof(int32_t));
+    if (rc != TIER_OK) return rc;
+    const dim3 mgrid((unsigned)((n_max + kBlock - 1) / kBlock < 4096 ? (n_max + kBlock - 1) / kBlock : 4096),
+                     (unsigned)n_lists);
+    if (mode == GATHER_SLOT)
+        k_mark_misses<GATHER_SLOT><<<mgrid, kBlock, 0, st>>>(lists, ctx->slot, ctx->n_nodes, ctx->n_hot, ctx->gbitmap);
+    else
+        k_mark_misses<GATHER_BOUNDARY><<<mgrid, kBlock, 0, st>>>(lists, ctx->slot, ctx->n_nodes, ctx->n_hot,
+                                                                 ctx->gbitmap);
+    int64_t g = (ctx->n_words + 4 * kBlock - 1) / (4 * kBlock);
+    const int bgrid = (int)(g < 1 ? 1 : (g > TIER_SCAN_BLOCKS ? TIER_SCAN_BLOCKS : g));
+    k_gbm_partial<<<bgrid, kBlock, 0, st>>>(ctx->gbitmap, ctx->n_words, ctx->gpartial);
+    k_gbm_emit<<<bgrid, kBlock, 0, st>>>(ctx->gbitmap, ctx->n_words, ctx->gpartial, ctx->uniq_ids, ctx->stage_slot,
+                                         ctx->gmeta);
+    TIER_HIP(ctx, hipGetLastError());
+    id_lists_t fetch = {};
+    fetch.ids[0] = ctx->uniq_ids;
+    fetch.n[0] = cap;
+    fetch.n_dev = &ctx->gmeta[META_NFRONT];
+    rc = launch_lists(ctx, fetch, 1, cap, GATHER_HOST, false, ctx->stage, false, st, ctx->gmeta);
+    if (rc != TIER_OK) return rc;
+    return launch_lists(ctx, lists, n_lists, n_max, mode, true, out, count_hits, st, ctx->gmeta);
 }
 
 // hit / miss rows of the launch(es) since the last k_clear_hits on the gather stream
@@ -168,6 +338,7 @@ static int read_stats(tier_ctx *ctx, int64_t n_total, tier_gather_stats *stats)
     stats->hit_rows = 0;
     for (int i = 0; i < META_HIT_STRIPES; ++i) stats->hit_rows += ctx->gmeta_host[META_HIT_ROWS + i];
     stats->miss_rows = n_total - stats->hit_rows;
+    stats->link_rows = ctx->dedup && n_total > 0 ? ctx->gmeta_host[META_NFRONT] : stats->miss_rows;
     return TIER_OK;
 }
 
@@ -190,8 +361,7 @@ extern "C" int tier_gather_minibatches(tier_ctx *ctx, const int32_t *nodes, int6
         n_total += n_rows[b];
     }
     if (n_total > 0 && (!nodes || !out)) return TIER_EINVAL;
-    int rc = launch_lists(ctx, lists, n_batches, n_max, ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT, out,
-                          stats != nullptr);
+    int rc = gather_call(ctx, lists, n_batches, n_max, n_total, out, stats != nullptr);
     if (rc != TIER_OK) return rc;
     if (stats) return read_stats(ctx, n_total, stats);
     return TIER_OK;
@@ -203,8 +373,27 @@ extern "C" int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n
     if (!ctx || n < 0 || (n > 0 && (!ids || !out))) return TIER_EINVAL;
     if (((uintptr_t)out & 15u) != 0) return TIER_EINVAL;
     if (!ctx->placed) return TIER_ESTATE;
-    int rc = tier_launch_gather(ctx, ids, n, ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT, out, stats != nullptr);
+    id_lists_t lists = {};
+    lists.ids[0] = ids;
+    lists.n[0] = n;
+    int rc = gather_call(ctx, lists, 1, n, n, out, stats != nullptr);
     if (rc != TIER_OK) return rc;
     if (stats) return read_stats(ctx, n, stats);
+    return TIER_OK;
+}
+
+extern "C" int tier_set_gather_dedup(tier_ctx *ctx, int on)
+{
+    if (!ctx) return TIER_EINVAL;
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+    if (on && !ctx->gbitmap) {
+        const size_t words = (size_t)(ctx->n_words > 0 ? ctx->n_words : 1);
+        TIER_HIP(ctx, hipMalloc(&ctx->gbitmap, words * sizeof(uint32_t)));
+        TIER_HIP(ctx, hipMemsetAsync(ctx->gbitmap, 0, words * sizeof(uint32_t), ctx->gather_stream));
+        TIER_HIP(ctx, hipMalloc(&ctx->stage_slot, (size_t)(ctx->n_nodes > 0 ? ctx->n_nodes : 1) * sizeof(int32_t)));
+        TIER_HIP(ctx, hipMalloc(&ctx->gpartial, TIER_SCAN_BLOCKS * sizeof(int32_t)));
+        TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+    }
+    ctx->dedup = on != 0;
     return TIER_OK;
 }

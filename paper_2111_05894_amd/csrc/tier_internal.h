@@ -26,6 +26,15 @@ struct tier_ctx {
     hipStream_t gather_stream;   // stream of tier_gather_features (= stream unless set apart)
     int64_t *gmeta;              // device: error flag and hit counter of the gather stream
     int64_t *gmeta_host;         // pinned mirror
+    // shared misses (tier_set_gather_dedup): scratch of the gather stream
+    bool dedup;
+    uint32_t *gbitmap;           // n_words; cold ids requested by the current call, zero between calls
+    int32_t *stage_slot;         // n_nodes; row of a cold id in the staging area (valid for the current call's ids)
+    int32_t *gpartial;           // TIER_SCAN_BLOCKS
+    int32_t *uniq_ids;           // distinct cold ids of the current call, ascending
+    int64_t uniq_cap;
+    uint8_t *stage;              // their rows, fetched once
+    int64_t stage_cap;           // in rows
     int device;
     int last_hip;
     // graph and features (referenced, caller-owned)

@@ -24,7 +24,7 @@ EXPORTS = (
     "tier_sample_minibatches", "tier_max_batches",
     "tier_score_degree", "tier_score_wrpr", "tier_rank_scores", "tier_place_scores",
     "tier_rank", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
-    "tier_gather_features", "tier_gather_minibatches", "tier_set_gather_stream", "tier_strerror", "tier_last_hip_error",
+    "tier_gather_features", "tier_gather_minibatches", "tier_set_gather_stream", "tier_set_gather_dedup", "tier_strerror", "tier_last_hip_error",
 )
 
 
@@ -60,7 +60,7 @@ class _BlocksBatch(C.Structure):
 
 
 class _Stats(C.Structure):
-    _fields_ = [("hit_rows", C.c_int64), ("miss_rows", C.c_int64)]
+    _fields_ = [("hit_rows", C.c_int64), ("miss_rows", C.c_int64), ("link_rows", C.c_int64)]
 
 
 def _load():
@@ -96,6 +96,7 @@ def _load():
         lib.tier_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(_Stats)]
         lib.tier_gather_minibatches.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, i64p, i64p, C.c_int32, C.c_void_p,
                                                 C.POINTER(_Stats)]
+        lib.tier_set_gather_dedup.argtypes = [C.c_void_p, C.c_int]
         lib.tier_set_gather_stream.argtypes = [C.c_void_p, C.c_void_p]
         lib.tier_strerror.argtypes = [C.c_int]; lib.tier_strerror.restype = C.c_char_p
         lib.tier_last_hip_error.argtypes = [C.c_void_p]
@@ -421,7 +422,15 @@ def tier_gather_minibatches(ctx: Context, blocks: "BlocksBatch", n_batches: int,
     rc = _load().tier_gather_minibatches(ctx.handle, C.c_void_p(blocks.nodes.data_ptr()), blocks.nodes.shape[1], nr, of,
                                          n_batches, C.c_void_p(out.data_ptr()), C.byref(st) if want_stats else None)
     _check(rc, "tier_gather_minibatches")
+    if want_stats:
+        ctx.last_link_rows = st.link_rows
     return (out, offs, st.hit_rows, st.miss_rows) if want_stats else (out, offs)
+
+
+def tier_set_gather_dedup(ctx: Context, on: bool):
+    """Fetch every distinct cold row of a gather call over the host link once (see tier.h)."""
+    _check(_load().tier_set_gather_dedup(ctx.handle, 1 if on else 0), "tier_set_gather_dedup")
+    ctx.last_link_rows = None
 
 
 def tier_set_gather_stream(ctx: Context, stream=None):
@@ -441,4 +450,6 @@ def tier_gather_features(ctx: Context, ids: torch.Tensor, out: torch.Tensor = No
     rc = _load().tier_gather_features(ctx.handle, _dev(ids, torch.int32, "ids"), n, C.c_void_p(out.data_ptr()),
                                       C.byref(st) if want_stats else None)
     _check(rc, "tier_gather_features")
+    if want_stats:
+        ctx.last_link_rows = st.link_rows
     return (out, st.hit_rows, st.miss_rows) if want_stats else out

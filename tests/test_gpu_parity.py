@@ -291,6 +291,50 @@ def test_batched_gather_equals_per_batch_gathers(small):
     assert offs1 == [0] and torch.equal(out1, out[: blk.n_nodes[0][2]])
 
 
+@pytest.mark.parametrize("dim,boundary", [(32, False), (100, False), (8, True)])
+def test_shared_misses_give_the_same_rows(dim, boundary):
+    """With tier_set_gather_dedup every distinct cold row crosses the host link once; the rows
+    delivered, the hit/miss counts and the oracle's gather are unchanged, and the rows read
+    over the link are exactly the distinct cold ids of the call."""
+    ip, ix = synth.rmat_csr(6000, 80_000, 5, "cpu")
+    w = World(ip, ix, dim=dim)
+    try:
+        rng = np.random.default_rng(dim)
+        counts = rng.integers(0, 20, w.n).astype(np.uint32)
+        if boundary:
+            n_hot = tier.tier_place_boundary(w.ctx, 500 * w.row_bytes)
+            hot = np.arange(w.n) < n_hot
+        else:
+            slot, n_hot = tier.tier_place(w.ctx, torch.from_numpy(counts.view(np.int32)).to(DEV), 500 * w.row_bytes)
+            hot = slot.cpu().numpy() >= 0
+        B = tier.tier_max_batches(w.ctx)
+        seeds = rng.choice(w.n, 64 * B, replace=False).astype(np.int32)
+        blk = tier.tier_sample_minibatches(w.ctx, torch.from_numpy(seeds).to(DEV), 64, list(range(B)), (10, 6))
+        plain, offs, hit0, miss0 = tier.tier_gather_minibatches(w.ctx, blk, B, want_stats=True)
+        assert w.ctx.last_link_rows == miss0
+        tier.tier_set_gather_dedup(w.ctx, True)
+        for rep in range(2):                                         # scratch is clean for the next call
+            got, offs2, hit, miss = tier.tier_gather_minibatches(w.ctx, blk, B, want_stats=True)
+            assert offs2 == offs and (hit, miss) == (hit0, miss0) and torch.equal(got, plain)
+            ids = torch.cat([blk.frontier(b) for b in range(B)]).cpu().numpy()
+            assert np.array_equal(got.view(torch.uint8).cpu().numpy().reshape(-1, w.row_bytes), w.feat_bytes[ids])
+            cold = ids[~hot[ids]]
+            assert miss == len(cold) and w.ctx.last_link_rows == len(np.unique(cold)) < miss
+        one, h1, m1 = tier.tier_gather_features(w.ctx, torch.from_numpy(ids[:5000]).to(DEV), want_stats=True)
+        assert np.array_equal(one.view(torch.uint8).cpu().numpy().reshape(-1, w.row_bytes), w.feat_bytes[ids[:5000]])
+        assert w.ctx.last_link_rows == len(np.unique(ids[:5000][~hot[ids[:5000]]]))
+        empty, _, _ = tier.tier_gather_features(w.ctx, torch.zeros(0, dtype=torch.int32, device=DEV), want_stats=True)
+        assert empty.shape[0] == 0
+        bad = torch.tensor([0, w.n, 3], dtype=torch.int32, device=DEV)
+        with pytest.raises(tier.TierError):
+            tier.tier_gather_features(w.ctx, bad, want_stats=True)
+        tier.tier_set_gather_dedup(w.ctx, False)
+        again, _, _, _ = tier.tier_gather_minibatches(w.ctx, blk, B, want_stats=True)
+        assert torch.equal(again, plain) and w.ctx.last_link_rows == miss0
+    finally:
+        w.close()
+
+
 def test_gather_on_its_own_stream_while_sampling(small):
     """Gathers of one group run on a second stream while the next group is sampled into the
     other set of buffers; every group's rows still match the table."""
