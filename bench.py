@@ -253,32 +253,37 @@ def main():
                                  round(nrows * R / (ms * 1e-3) / 1e9 / LINK_PEAK_GBPS, 4),
                                  "avg_launch_ms": round(ms / nl, 4), "launches": nl}
         roofline["streams"] = streams
+        untiered_ms = rows * R / (streams["all_miss"]["host_link_GBps"] * 1e9) * 1e3
+        roofline["untiered_epoch_gather_ms"] = round(untiered_ms, 2)
+        roofline["gather_speedup_vs_untiered"] = round(untiered_ms / gather_ms, 2) if gather_ms else None
 
     scores = None
     # the same epoch gathered alone (no sampling beside it), plain and with shared misses
-    shared = {}
-    tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
-    tier.tier_place(ctx, counts, budget, want_slot_map=False)
-    for name, on in (("plain", False), ("shared_misses", True)):
-        tier.tier_set_gather_dedup(ctx, on)
-        for timed in (False, True):                 # first pass grows the staging area and counts, second times
-            ms = 0.0; link_rows = 0
-            for g in groups:
-                blk = sample_group(g)
-                if timed:
-                    a, b_, r = timed_gather(blk, len(g))
-                    torch.cuda.synchronize()
-                    ms += a.elapsed_time(b_)
-                else:
-                    tier.tier_gather_minibatches(ctx, blk, len(g), out_buf[0], want_stats=True)
-                    link_rows += ctx.last_link_rows
-            if not timed:
-                links = link_rows
-        shared[name] = {"gather_ms": round(ms, 3), "host_link_bytes": links * R,
-                        "gathered_GBps": round(rows * R / (ms * 1e-3) / 1e9, 2) if ms else None}
-    tier.tier_set_gather_dedup(ctx, False)
-    shared["note"] = ("one pass over the measured epoch, gathers only; shared_misses reads every distinct cold row "
-                      "of a call (16 mini-batches) over the host link once")
+    shared = None
+    if not args.no_streams:
+        shared = {}
+        tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
+        tier.tier_place(ctx, counts, budget, want_slot_map=False)
+        for name, on in (("plain", False), ("shared_misses", True)):
+            tier.tier_set_gather_dedup(ctx, on)
+            for timed in (False, True):                 # first pass grows the staging area and counts, second times
+                ms = 0.0; link_rows = 0
+                for g in groups:
+                    blk = sample_group(g)
+                    if timed:
+                        a, b_, r = timed_gather(blk, len(g))
+                        torch.cuda.synchronize()
+                        ms += a.elapsed_time(b_)
+                    else:
+                        tier.tier_gather_minibatches(ctx, blk, len(g), out_buf[0], want_stats=True)
+                        link_rows += ctx.last_link_rows
+                if not timed:
+                    links = link_rows
+            shared[name] = {"gather_ms": round(ms, 3), "host_link_bytes": links * R,
+                            "gathered_GBps": round(rows * R / (ms * 1e-3) / 1e9, 2) if ms else None}
+        tier.tier_set_gather_dedup(ctx, False)
+        shared["note"] = ("one pass over the measured epoch, gathers only; shared_misses reads every distinct cold row "
+                          "of a call (16 mini-batches) over the host link once")
 
     out = out_buf[0]
     if not args.no_scores:
