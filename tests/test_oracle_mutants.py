@@ -2,10 +2,13 @@
 sign or index, a swapped operand) must each fail at least one pin.  Every mutant is the
 oracle's C file with one edit, compiled into a scratch library and swapped in for the run
 of the pin tests (CPU only; nothing here touches the GPU path).  The edits are chosen to
-stay inside the arrays, so a mutant computes a wrong answer rather than crashing."""
+stay inside the arrays, so a mutant computes a wrong answer rather than crashing; the one
+that cannot (marked "isolate") runs its checks in a process of its own, where a crash
+counts as noticed."""
 import ctypes
 import os
 import subprocess
+import sys
 
 import pytest
 
@@ -65,7 +68,7 @@ MUTANTS = [
      "row = cache + (size_t)(v % 2) * (size_t)row_bytes; ++hit;",
      [pins.test_gather_equals_fancy_indexing_for_any_budget]),
     ("reorder: lengths placed at the old id", "nd_new[srt_idx[i] + 1] = nd[i + 1] - nd[i];", "nd_new[i + 1] = nd[i + 1] - nd[i];",
-     [rpins.test_reorder_hand_worked_example]),
+     [rpins.test_reorder_hand_worked_example], "isolate"),      # may write past a list's end: own process
     ("reorder: values not renamed", "relabelled[e] = srt_idx[edg[e]];", "relabelled[e] = edg[e];",
      [rpins.test_reorder_hand_worked_example, rpins.test_reorder_is_a_relabelling]),
     ("reorder: lists reversed while moving", "= relabelled[nd[i] + j];", "= relabelled[nd[i] + len - 1 - j];",
@@ -98,9 +101,23 @@ def _build(tmp_path, text, tag):
 
 @pytest.mark.parametrize("idx", range(len(MUTANTS)), ids=[m[0] for m in MUTANTS])
 def test_planted_mistake_is_caught(idx, tmp_path):
-    name, old, new, checks = MUTANTS[idx]
+    name, old, new, checks = MUTANTS[idx][:4]
     assert SRC.count(old) == 1, f"mutation site not unique for: {name}"
-    lib = ctypes.CDLL(_build(tmp_path, SRC.replace(old, new), idx))
+    lib_path = _build(tmp_path, SRC.replace(old, new), idx)
+    if len(MUTANTS[idx]) > 4:
+        code = (f"import sys; sys.path[:0] = {[os.path.dirname(__file__), os.path.dirname(os.path.dirname(__file__))]!r}\n"
+                f"import test_oracle_mutants as m\n"
+                f"sys.exit(0 if m.run_checks({lib_path!r}, {idx}) >= 1 else 3)\n")
+        rc = subprocess.run([sys.executable, "-c", code], capture_output=True).returncode
+        assert rc != 3, f"no pin noticed: {name}"                   # 0 = caught by a pin, anything else = crashed
+        return
+    assert run_checks(lib_path, idx) >= 1, f"no pin noticed: {name}"
+
+
+def run_checks(lib_path, idx):
+    """Swap the mutant library in, run the mutant's pin tests, return how many failed."""
+    checks = MUTANTS[idx][3]
+    lib = ctypes.CDLL(lib_path)
     good = orc._load()
     # give the mutant the same prototypes as the real library
     for sym in ("orc_bounded", "orc_batch_seed", "orc_philox4x32_10", "orc_draw_positions", "orc_sample_minibatch",
@@ -118,10 +135,10 @@ def test_planted_mistake_is_caught(idx, tmp_path):
                 caught += 1
     finally:
         orc._lib = good
-    assert caught >= 1, f"no pin noticed: {name}"
+    return caught
 
 
 def test_unmutated_oracle_passes_the_same_checks():
-    for _, _, _, checks in MUTANTS:
-        for check in checks:
+    for m in MUTANTS:
+        for check in m[3]:
             check()
