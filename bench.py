@@ -319,6 +319,8 @@ def main():
                       "sample_alone_ms is the same epoch's sampling with the GPU to itself (basis of sampled_edges_per_s)",
         "phase_ms": {"presample": round(mean(rec["presample_ms"]), 3), "place": round(mean(rec["place_ms"]), 3),
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3)},
+        "paper_context": "paper (2x Xeon 6230 + V100 32 GB, OGB datasets, DGL): 87-95 % less PCIe traffic with 10 % of the "
+                         "features on the GPU and 1.6-2.1x faster training than zero-copy only; context, not a target",
         "roofline": roofline, "shared_misses": shared, "score_functions": scores, "sweeps": sweeps, "reordered": reorder, "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
