@@ -26,6 +26,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 LINK_PEAK_GBPS = 64.0           # PCIe Gen5 x16, one direction, nominal
+SPLIT_MIN_ROWS = 1 << 17        # gather calls below this many rows keep the uniform launch
 
 
 def log(*a):
@@ -47,6 +48,8 @@ def main():
                     help="skip the comparison of score functions (presampled counts vs the paper's scores)")
     ap.add_argument("--sweeps", action="store_true",
                     help="also sweep the HBM budget and the sampling depth (analogues of the paper's Fig. 5 and 6)")
+    ap.add_argument("--link-blocks", type=int, default=64,
+                    help="blocks of the cold-row launch of the split gather (0: one uniform launch per call)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink nodes, edges and budget alike")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for profiler byte counters)")
@@ -96,15 +99,16 @@ def main():
     B = tier.tier_max_batches(ctx)                 # mini-batches sampled side by side per call
     groups = [list(range(g, min(g + B, n_batches))) for g in range(0, n_batches, B)]
     bseed = [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in range(n_batches)]
-    # two sets of block buffers: while one group's mini-batches are gathered (gather stream,
-    # host-link bound) the next group is sampled (main stream, latency bound)
-    blocks2 = [tier.BlocksBatch(n, bs, wl.fanouts, B, dev) for _ in range(2)]
+    # three sets of block buffers: while up to two groups of mini-batches wait for or run their
+    # gather (gather stream, host-link bound) the next group is sampled (main stream, latency bound)
+    blocks2 = [tier.BlocksBatch(n, bs, wl.fanouts, B, dev) for _ in range(3)]
     blocks = blocks2[0]
     out_buf = [torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=dev)]
     counts = torch.empty(n, dtype=torch.int32, device=dev)
     L = len(wl.fanouts)
     gs = torch.cuda.Stream()
     tier.tier_set_gather_stream(ctx, gs)
+    tier.tier_set_gather_split(ctx, args.link_blocks, SPLIT_MIN_ROWS)
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
     def sample_group(g, into=None):
@@ -126,6 +130,35 @@ def main():
             b_.record()
         return a, b_, rows
 
+    def epoch(record):
+        """The measured epoch: every group of mini-batches sampled (main stream) and gathered (gather stream)."""
+        t_epoch = time.perf_counter()
+        rows = edges = 0
+        s_pairs, g_pairs = [], []
+        NB = len(blocks2)
+        reads_done = [None] * NB                   # last gather that reads blocks2[i]
+        for gi, g in enumerate(groups):
+            # a group's gather is launched as soon as the group is sampled; the host then sits in the
+            # next (synchronous) sampling call while that gather runs, so the gather stream always has
+            # a launch waiting, and the third buffer keeps the host from waiting for a gather to end
+            if reads_done[gi % NB] is not None:
+                reads_done[gi % NB].synchronize()  # its ids are about to be overwritten
+            s0, s1 = ev(), ev()
+            s0.record(); blk = sample_group(g, blocks2[gi % NB]); s1.record()
+            s_pairs.append((s0, s1))
+            a, b_, r = timed_gather(blk, len(g))
+            g_pairs.append((a, b_))
+            rows += r; edges += sum(sum(blk.n_edges[i]) for i in range(len(g)))
+            reads_done[gi % NB] = b_
+        torch.cuda.synchronize()
+        if record is not None:
+            record["epoch_wall_ms"].append((time.perf_counter() - t_epoch) * 1e3)
+            record["sample_ms"].append(sum(a.elapsed_time(b_) for a, b_ in s_pairs))
+            record["gather_ms"].append(sum(a.elapsed_time(b_) for a, b_ in g_pairs))
+            record["rows"] = rows; record["edges"] = edges
+            record["gather_launches"] = len(g_pairs)
+        return rows, edges
+
     def step(record):
         e_begin, e_pre, e_place = ev(), ev(), ev()
         e_begin.record()
@@ -133,34 +166,11 @@ def main():
         e_pre.record()
         _, n_hot = tier.tier_place(ctx, counts, budget, want_slot_map=False)
         e_place.record()
-        t_epoch = time.perf_counter()
-        rows = edges = 0
-        s_pairs, g_pairs = [], []
-        s0, s1 = ev(), ev()
-        s0.record(); blk = sample_group(groups[0], blocks2[0]); s1.record()
-        s_pairs.append((s0, s1))
-        reads_done = [None, None]                  # last gather that reads blocks2[i]
-        for gi, g in enumerate(groups):
-            a, b_, r = timed_gather(blk, len(g))
-            g_pairs.append((a, b_))
-            rows += r; edges += sum(sum(blk.n_edges[i]) for i in range(len(g)))
-            reads_done[gi % 2] = b_
-            if gi + 1 < len(groups):
-                nxt = (gi + 1) % 2
-                if reads_done[nxt] is not None:
-                    reads_done[nxt].synchronize()  # its ids are about to be overwritten
-                s0, s1 = ev(), ev()
-                s0.record(); blk = sample_group(groups[gi + 1], blocks2[nxt]); s1.record()
-                s_pairs.append((s0, s1))
-        torch.cuda.synchronize()
+        rows, edges = epoch(record)
         if record is not None:
-            record["epoch_wall_ms"].append((time.perf_counter() - t_epoch) * 1e3)
             record["presample_ms"].append(e_begin.elapsed_time(e_pre))
             record["place_ms"].append(e_pre.elapsed_time(e_place))
-            record["sample_ms"].append(sum(a.elapsed_time(b_) for a, b_ in s_pairs))
-            record["gather_ms"].append(sum(a.elapsed_time(b_) for a, b_ in g_pairs))
-            record["rows"] = rows; record["edges"] = edges; record["n_hot"] = n_hot
-            record["gather_launches"] = len(g_pairs)
+            record["n_hot"] = n_hot
         return rows, edges
 
     if args.calibrate_copy:
@@ -180,6 +190,19 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_begin
     ms_per_step = wall * 1e3 / max(args.steps, 1)
+
+    # the same epoch with the uniform gather launch (every block copies hot and cold rows)
+    uniform = None
+    if args.link_blocks > 0:
+        tier.tier_set_gather_split(ctx, 0, 0)
+        urec = {"sample_ms": [], "gather_ms": [], "epoch_wall_ms": []}
+        epoch(None)
+        for _ in range(max(args.steps, 1)):
+            epoch(urec)
+        tier.tier_set_gather_split(ctx, args.link_blocks, SPLIT_MIN_ROWS)
+        uniform = {"epoch_wall_ms": round(sum(urec["epoch_wall_ms"]) / len(urec["epoch_wall_ms"]), 3),
+                   "gather_ms": round(sum(urec["gather_ms"]) / len(urec["gather_ms"]), 3),
+                   "sample_ms": round(sum(urec["sample_ms"]) / len(urec["sample_ms"]), 3)}
 
     # hit / miss rows of the measured epoch (outside the timed region: asking for them waits per batch)
     hit_rows = 0
@@ -322,6 +345,10 @@ def main():
         "phase_ms": {"presample": round(mean(rec["presample_ms"]), 3), "place": round(mean(rec["place_ms"]), 3),
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3),
                      "epoch_wall": round(mean(rec["epoch_wall_ms"]), 3)},
+        "gather_launch": {"link_blocks": args.link_blocks, "min_rows": SPLIT_MIN_ROWS,
+                          "note": "split launch: the first link_blocks blocks copy the cold rows (host link), all others the "
+                                  "hot rows (HBM); uniform_launch_epoch is the same epoch with every block copying both",
+                          "uniform_launch_epoch": uniform},
         "paper_context": "paper (2x Xeon 6230 + V100 32 GB, OGB datasets, DGL): 87-95 % less PCIe traffic with 10 % of the "
                          "features on the GPU and 1.6-2.1x faster training than zero-copy only; context, not a target",
         "roofline": roofline, "shared_misses": shared, "score_functions": scores, "sweeps": sweeps, "reordered": reorder, "cpu_baseline": cpu,

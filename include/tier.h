@@ -264,6 +264,18 @@ int tier_gather_minibatches(tier_ctx *ctx, const int32_t *nodes, int64_t nodes_s
                             const int64_t *out_row_offset, int32_t n_batches, void *out,
                             tier_gather_stats *stats);
 
+/* Split gather (Sec. 4.1: the cold tier is read in place over the host link, whose
+ * bandwidth the requests of a few dozen blocks already fill).  With link_blocks > 0, in a
+ * gather call of at least min_rows rows in total the first link_blocks blocks of the
+ * launch look through the requests and copy the cold rows, staying until the link has
+ * delivered them; every other block copies hot rows only and leaves at HBM speed.  Same
+ * results as the uniform launch (link_blocks = 0, the default), in which every block waits
+ * on host reads and the kernels of other streams wait for the whole launch: use it when
+ * something else (sampling, training) should run beside the gather.  0 <= link_blocks <=
+ * 65536, min_rows >= 0.  Ignored while tier_set_gather_dedup is on.  Waits for the gather
+ * stream. */
+int tier_set_gather_split(tier_ctx *ctx, int32_t link_blocks, int64_t min_rows);
+
 /* Shared misses.  With on != 0 every gather call first finds the distinct cold ids among
  * all its requests, reads each of those rows over the host link once into an HBM staging
  * area owned by the context (up to min(requests, n_nodes) rows, grown on demand; n_nodes

@@ -12,6 +12,16 @@
 // the bitmap into an ascending list of distinct cold ids (k_gbm_*), fetch those rows
 // over the host link once into an HBM staging area, and then serve every request from
 // HBM: cache rows for hits, staged rows for misses.
+//
+// Split gather (tier_set_gather_split): the host link is saturated by the requests of a
+// few dozen blocks.  A full grid that queues megabytes of host reads gains nothing on the
+// link, holds every compute unit's slots until the link has served them, and makes
+// everything else that crosses the link wait behind its queue (the command processor
+// fetching the packets of other streams' kernels included: ~0.3 ms per launch at 16 MB
+// in flight).  A call can therefore leave its cold rows to the first few blocks of the
+// launch (row 0 of the grid, dispatched first): they look through the requests, copy the
+// cold ones and stay until the link has delivered them, while all other blocks copy hot
+// rows only and drain at HBM speed, leaving the chip to whoever else has work.
 #include "tier_internal.h"
 
 namespace {
@@ -28,25 +38,128 @@ struct id_lists_t {
     const int64_t *n_dev;                // non-null: the length of list 0 is read from the device
 };
 
+// An id outside the graph is nobody's cold row: the hot launch writes its row of zeros.
+template <int MODE>
+__device__ inline int is_cold(int32_t id, const int32_t *__restrict__ slot, int64_t n_nodes, int64_t n_hot)
+{
+    if ((uint32_t)id >= (uint64_t)n_nodes) return 0;
+    return MODE == GATHER_SLOT ? slot[id] < 0 : id >= n_hot;
+}
+
+// The cold workers of a split launch: the first `workers` blocks of grid row 0.  A wave
+// takes the next chunk of 64 requests off a counter (chunks numbered list by list), finds
+// the cold ones among them with one ballot and copies those, kRowsInFlight per group of
+// LPR lanes at a time.  The counter makes the waves finish together whatever the mix of
+// hot and cold in their chunks; the last wave to run dry leaves both counters at zero for
+// the next launch on the stream.
+template <int LPR, int MODE>
+__device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, const int32_t *__restrict__ slot,
+                                      int64_t n_nodes, int64_t n_hot, int workers,
+                                      const uint4 *__restrict__ host, uint4 *__restrict__ out_base, int cpr,
+                                      int64_t *__restrict__ meta)
+{
+    constexpr int kGroupsPerWave = 64 / LPR;
+    constexpr int kPerPass = kGroupsPerWave * kRowsInFlight;
+    if ((int)blockIdx.x >= workers) return;
+    const int lane64 = threadIdx.x & 63;
+    const int g = lane64 / LPR, lane = lane64 % LPR;
+    const unsigned long long n_waves = (unsigned long long)workers * (kBlock / 64);
+    unsigned long long *next = (unsigned long long *)&meta[META_COLD_NEXT];
+    unsigned long long *done = (unsigned long long *)&meta[META_COLD_DONE];
+    int64_t total = 0;
+    for (int b = 0; b < n_lists; ++b) total += (lists.n[b] + 63) / 64;
+
+    auto grab = [&]() -> int64_t {
+        unsigned long long q = 0;
+        if (lane64 == 0) q = atomicAdd(next, 1ull);
+        return (int64_t)__shfl(q, 0);
+    };
+    int64_t q = grab();
+    while (q < total) {
+        const int64_t q_next = grab();             // in flight while this chunk is copied
+        int b = 0;
+        int64_t c = q;
+        for (;; ++b) {                              // q < total: ends inside the lists
+            const int64_t nc = (lists.n[b] + 63) / 64;
+            if (c < nc) break;
+            c -= nc;
+        }
+        const int32_t *__restrict__ ids = lists.ids[b];
+        const int64_t n = lists.n[b];
+        uint4 *__restrict__ out = out_base + lists.out_row[b] * cpr;
+        const int64_t i = c * 64 + lane64;
+        const int32_t id = i < n ? ids[i] : -1;
+        const int cold = i < n ? is_cold<MODE>(id, slot, n_nodes, n_hot) : 0;
+        unsigned long long mask = __ballot(cold);
+        while (mask) {
+            const uint4 *src[kRowsInFlight];
+            uint4 *dst[kRowsInFlight];
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j) {
+                src[j] = nullptr;
+                dst[j] = nullptr;
+            }
+#pragma unroll
+            for (int k = 0; k < kPerPass; ++k) {   // the k-th cold request of the pass goes to group k / kRowsInFlight
+                const int bit = mask ? __ffsll((long long)mask) - 1 : -1;
+                mask = mask ? mask & (mask - 1) : 0;
+                const int32_t sid = __shfl(id, bit < 0 ? 0 : bit);
+                if (bit >= 0 && k / kRowsInFlight == g) {
+                    src[k % kRowsInFlight] = host + (int64_t)sid * cpr;
+                    dst[k % kRowsInFlight] = out + (c * 64 + bit) * cpr;
+                }
+            }
+            for (int cc = lane; cc < cpr; cc += LPR) {
+                uint4 v[kRowsInFlight];
+#pragma unroll
+                for (int j = 0; j < kRowsInFlight; ++j) {
+                    v[j] = make_uint4(0, 0, 0, 0);
+                    if (src[j]) v[j] = src[j][cc];
+                }
+#pragma unroll
+                for (int j = 0; j < kRowsInFlight; ++j)
+                    if (dst[j]) {
+                        u32x4 t = {v[j].x, v[j].y, v[j].z, v[j].w};
+                        __builtin_nontemporal_store(t, (u32x4 *)&dst[j][cc]);
+                    }
+            }
+        }
+        q = q_next;
+    }
+    if (lane64 == 0 && atomicAdd(done, 1ull) == n_waves - 1) {    // every other wave has made its last grab
+        atomicExch(next, 0ull);
+        atomicExch(done, 0ull);
+    }
+}
+
 // MODE: GATHER_SLOT     hot <=> slot[id] >= 0, cache row = slot[id]      (ids keep their meaning)
 //       GATHER_BOUNDARY hot <=> id < n_hot, cache row = id, cold row = id - n_hot of the cold
 //                       part (rows in rank order: the two-way branch of Listing 1)
 //       GATHER_HOST     every row from host memory: the untiered copy that fills the HBM
 //                       cache at placement time
 // STAGED: cold rows come from the staging area (row stage_slot[id]) instead of host memory.
-template <int LPR, int MODE, bool STAGED>
+// SPLIT:  grid row 0 holds the cold workers (copy_cold_rows), list b is served by grid row b + 1
+//         and skips its cold rows.
+template <int LPR, int MODE, bool STAGED, bool SPLIT>
 __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32_t *__restrict__ slot,
                                                    const uint4 *__restrict__ cache,
                                                    const uint4 *__restrict__ host,
                                                    const uint4 *__restrict__ stage,
                                                    const int32_t *__restrict__ stage_slot,
                                                    uint4 *__restrict__ out_base, int cpr, int64_t n_nodes,
-                                                   int64_t n_hot, int64_t *__restrict__ meta, int count_hits)
+                                                   int64_t n_hot, int64_t *__restrict__ meta, int count_hits,
+                                                   int cold_workers)
 {
     constexpr int kGroups = kBlock / LPR;
-    const int32_t *__restrict__ ids = lists.ids[blockIdx.y];
-    const int64_t n = lists.n_dev ? *lists.n_dev : lists.n[blockIdx.y];
-    uint4 *__restrict__ out = out_base + lists.out_row[blockIdx.y] * cpr;
+    if (SPLIT && blockIdx.y == 0) {
+        scan_cold_rows<LPR, MODE>(lists, (int)gridDim.y - 1, slot, n_nodes, n_hot, cold_workers, host, out_base, cpr,
+                                  meta);
+        return;
+    }
+    const int list = SPLIT ? blockIdx.y - 1 : blockIdx.y;
+    const int32_t *__restrict__ ids = lists.ids[list];
+    const int64_t n = lists.n_dev ? *lists.n_dev : lists.n[list];
+    uint4 *__restrict__ out = out_base + lists.out_row[list] * cpr;
     const int lane = threadIdx.x % LPR;
     const int64_t group = (int64_t)blockIdx.x * kGroups + threadIdx.x / LPR;
     const int64_t n_groups = (int64_t)gridDim.x * kGroups;
@@ -55,10 +168,12 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
 
     for (int64_t r0 = group * kRowsInFlight; r0 < n; r0 += n_groups * kRowsInFlight) {
         const uint4 *src[kRowsInFlight];
+        bool put[kRowsInFlight];
 #pragma unroll
         for (int j = 0; j < kRowsInFlight; ++j) {
             int64_t r = r0 + j;
             src[j] = nullptr;
+            put[j] = r < n;
             if (r < n) {
                 int32_t id = ids[r];
                 if ((uint32_t)id >= (uint64_t)n_nodes) {
@@ -70,6 +185,8 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
                     if (s >= 0) {
                         src[j] = cache + (int64_t)s * cpr;
                         hits += (lane == 0);
+                    } else if (SPLIT) {
+                        put[j] = false;
                     } else if (STAGED) {
                         src[j] = stage + (int64_t)stage_slot[id] * cpr;
                     } else if (MODE == GATHER_BOUNDARY) {
@@ -90,7 +207,7 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
             }
 #pragma unroll
             for (int j = 0; j < kRowsInFlight; ++j)
-                if (r0 + j < n) {                  // streaming store: the output is not read back here
+                if (put[j]) {                      // streaming store: the output is not read back here
                     u32x4 t = {v[j].x, v[j].y, v[j].z, v[j].w};
                     __builtin_nontemporal_store(t, (u32x4 *)&out[(r0 + j) * cpr + c]);
                 }
@@ -115,24 +232,6 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
 
 // ---- shared misses: distinct cold ids of a call ---------------------------------------
 
-template <int MODE>
-__global__ void k_mark_misses(id_lists_t lists, const int32_t *__restrict__ slot, int64_t n_nodes, int64_t n_hot,
-                              uint32_t *__restrict__ bitmap)
-{
-    const int32_t *__restrict__ ids = lists.ids[blockIdx.y];
-    const int64_t n = lists.n[blockIdx.y];
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n; r += stride) {
-        const int32_t id = ids[r];
-        if ((uint32_t)id >= (uint64_t)n_nodes) continue;            // reported by the gather itself
-        const bool hit = MODE == GATHER_SLOT ? slot[id] >= 0 : id < n_hot;
-        if (!hit) {
-            const uint32_t bit = 1u << (id & 31);
-            if (!(bitmap[id >> 5] & bit)) atomicOr(&bitmap[id >> 5], bit);   // most repeats stop at the read
-        }
-    }
-}
-
 __device__ inline int gblock_sum(int x, int *s_wave)
 {
     for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
@@ -152,6 +251,24 @@ __device__ inline void gblock_range(int64_t n, int64_t &lo, int64_t &hi)
     if (lo > n) lo = n;
     hi = lo + chunk;
     if (hi > n) hi = n;
+}
+
+template <int MODE>
+__global__ void k_mark_misses(id_lists_t lists, const int32_t *__restrict__ slot, int64_t n_nodes, int64_t n_hot,
+                              uint32_t *__restrict__ bitmap)
+{
+    const int32_t *__restrict__ ids = lists.ids[blockIdx.y];
+    const int64_t n = lists.n[blockIdx.y];
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n; r += stride) {
+        const int32_t id = ids[r];
+        if ((uint32_t)id >= (uint64_t)n_nodes) continue;            // reported by the gather itself
+        const bool hit = MODE == GATHER_SLOT ? slot[id] >= 0 : id < n_hot;
+        if (!hit) {
+            const uint32_t bit = 1u << (id & 31);
+            if (!(bitmap[id >> 5] & bit)) atomicOr(&bitmap[id >> 5], bit);   // most repeats stop at the read
+        }
+    }
 }
 
 __global__ __launch_bounds__(kBlock) void k_gbm_partial(const uint32_t *__restrict__ bitmap, int64_t n_words,
@@ -230,7 +347,7 @@ __global__ void k_clear_gather_error(int64_t *meta) { meta[META_ERROR] = 0; }
 // One k_gather launch.  Cache fills (GATHER_HOST on the main stream) and gathers (on the
 // gather stream, with bookkeeping words of their own) say where they run.
 static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, bool staged,
-                        void *out, bool count_hits, hipStream_t st, int64_t *meta)
+                        void *out, bool count_hits, hipStream_t st, int64_t *meta, bool split = false)
 {
     if (count_hits) k_clear_hits<<<1, META_HIT_STRIPES, 0, st>>>(meta);
     if (n_max <= 0) return TIER_OK;
@@ -241,19 +358,22 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
     int64_t blocks = (n_max + (int64_t)groups * kRowsInFlight - 1) / ((int64_t)groups * kRowsInFlight);
     const int64_t max_blocks = 1 << 18;     // beyond that groups loop; fewer blocks cost ~5 % of the all-hit rate
     if (blocks > max_blocks) blocks = max_blocks;
-    const dim3 grid((unsigned)blocks, (unsigned)n_lists);
-#define GATHER_LAUNCH(L, M, S)                                                                       \
-    k_gather<L, M, S><<<grid, kBlock, 0, st>>>(lists, ctx->slot, (const uint4 *)ctx->cache,          \
-                                               (const uint4 *)ctx->host_rows, (const uint4 *)ctx->stage, \
-                                               ctx->stage_slot, (uint4 *)out, cpr, ctx->n_nodes,     \
-                                               ctx->n_hot, meta, count_hits ? 1 : 0)
+    const int cold_workers = split ? (int)(ctx->link_blocks < blocks ? ctx->link_blocks : blocks) : 0;
+    const dim3 grid((unsigned)blocks, (unsigned)(n_lists + (split ? 1 : 0)));
+#define GATHER_LAUNCH(L, M, S, P)                                                                    \
+    k_gather<L, M, S, P><<<grid, kBlock, 0, st>>>(lists, ctx->slot, (const uint4 *)ctx->cache,       \
+                                                  (const uint4 *)ctx->host_rows, (const uint4 *)ctx->stage, \
+                                                  ctx->stage_slot, (uint4 *)out, cpr, ctx->n_nodes,  \
+                                                  ctx->n_hot, meta, count_hits ? 1 : 0, cold_workers)
 #define GATHER_CASE(L)                                                                               \
     case L:                                                                                          \
-        if (mode == GATHER_SLOT && staged) GATHER_LAUNCH(L, GATHER_SLOT, true);                      \
-        else if (mode == GATHER_SLOT) GATHER_LAUNCH(L, GATHER_SLOT, false);                          \
-        else if (mode == GATHER_BOUNDARY && staged) GATHER_LAUNCH(L, GATHER_BOUNDARY, true);         \
-        else if (mode == GATHER_BOUNDARY) GATHER_LAUNCH(L, GATHER_BOUNDARY, false);                  \
-        else GATHER_LAUNCH(L, GATHER_HOST, false);                                                   \
+        if (mode == GATHER_SLOT && split) GATHER_LAUNCH(L, GATHER_SLOT, false, true);                \
+        else if (mode == GATHER_BOUNDARY && split) GATHER_LAUNCH(L, GATHER_BOUNDARY, false, true);   \
+        else if (mode == GATHER_SLOT && staged) GATHER_LAUNCH(L, GATHER_SLOT, true, false);          \
+        else if (mode == GATHER_SLOT) GATHER_LAUNCH(L, GATHER_SLOT, false, false);                   \
+        else if (mode == GATHER_BOUNDARY && staged) GATHER_LAUNCH(L, GATHER_BOUNDARY, true, false);  \
+        else if (mode == GATHER_BOUNDARY) GATHER_LAUNCH(L, GATHER_BOUNDARY, false, false);           \
+        else GATHER_LAUNCH(L, GATHER_HOST, false, false);                                            \
         break;
     switch (lpr) {
         GATHER_CASE(8)
@@ -289,12 +409,15 @@ static int grow(tier_ctx *ctx, void **buf, int64_t *cap, int64_t want, size_t el
     return TIER_OK;
 }
 
-// The tiered gather of one call: plain, or with every distinct cold row fetched once.
+// The tiered gather of one call: one uniform launch, one launch with cold workers apart, or
+// every distinct cold row fetched once.
 static int gather_call(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int64_t n_total, void *out,
                        bool count_hits)
 {
     const int mode = ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT;
     hipStream_t st = ctx->gather_stream;
+    if (!ctx->dedup && ctx->link_blocks > 0 && n_total > 0 && n_total >= ctx->split_min_rows)
+        return launch_lists(ctx, lists, n_lists, n_max, mode, false, out, count_hits, st, ctx->gmeta, true);
     if (!ctx->dedup || n_total == 0)
         return launch_lists(ctx, lists, n_lists, n_max, mode, false, out, count_hits, st, ctx->gmeta);
 
@@ -379,6 +502,15 @@ extern "C" int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n
     int rc = gather_call(ctx, lists, 1, n, n, out, stats != nullptr);
     if (rc != TIER_OK) return rc;
     if (stats) return read_stats(ctx, n, stats);
+    return TIER_OK;
+}
+
+extern "C" int tier_set_gather_split(tier_ctx *ctx, int32_t link_blocks, int64_t min_rows)
+{
+    if (!ctx || link_blocks < 0 || link_blocks > 65536 || min_rows < 0) return TIER_EINVAL;
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+    ctx->link_blocks = link_blocks;
+    ctx->split_min_rows = min_rows;
     return TIER_OK;
 }
 

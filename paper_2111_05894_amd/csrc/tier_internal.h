@@ -13,6 +13,8 @@ enum {
     META_TOTAL_ROWS = META_NEDGES + TIER_MAX_LAYERS,
     META_TOTAL_EDGES,
     META_ERROR,                               // != 0: a kernel saw an id outside [0, n_nodes)
+    META_COLD_NEXT,                           // split gather: next chunk of requests for the cold workers,
+    META_COLD_DONE,                           //   workers' waves that ran dry; both zero between launches
     META_HIT_ROWS,                            // first of META_HIT_STRIPES counters (gather bookkeeping only)
     META_WORDS
 };
@@ -35,6 +37,9 @@ struct tier_ctx {
     int64_t uniq_cap;
     uint8_t *stage;              // their rows, fetched once
     int64_t stage_cap;           // in rows
+    // split gather (tier_set_gather_split): the cold rows of a call go to a few blocks of the launch
+    int link_blocks;             // how many; 0 = every block copies hot and cold rows alike
+    int64_t split_min_rows;      // calls with fewer rows keep the uniform launch
     int device;
     int last_hip;
     // graph and features (referenced, caller-owned)

@@ -24,7 +24,8 @@ EXPORTS = (
     "tier_sample_minibatches", "tier_max_batches",
     "tier_score_degree", "tier_score_wrpr", "tier_rank_scores", "tier_place_scores",
     "tier_rank", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
-    "tier_gather_features", "tier_gather_minibatches", "tier_set_gather_stream", "tier_set_gather_dedup", "tier_strerror", "tier_last_hip_error",
+    "tier_gather_features", "tier_gather_minibatches", "tier_set_gather_stream", "tier_set_gather_dedup", "tier_set_gather_split",
+    "tier_strerror", "tier_last_hip_error",
 )
 
 
@@ -97,6 +98,7 @@ def _load():
         lib.tier_gather_minibatches.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, i64p, i64p, C.c_int32, C.c_void_p,
                                                 C.POINTER(_Stats)]
         lib.tier_set_gather_dedup.argtypes = [C.c_void_p, C.c_int]
+        lib.tier_set_gather_split.argtypes = [C.c_void_p, C.c_int32, C.c_int64]
         lib.tier_set_gather_stream.argtypes = [C.c_void_p, C.c_void_p]
         lib.tier_strerror.argtypes = [C.c_int]; lib.tier_strerror.restype = C.c_char_p
         lib.tier_last_hip_error.argtypes = [C.c_void_p]
@@ -431,6 +433,12 @@ def tier_set_gather_dedup(ctx: Context, on: bool):
     """Fetch every distinct cold row of a gather call over the host link once (see tier.h)."""
     _check(_load().tier_set_gather_dedup(ctx.handle, 1 if on else 0), "tier_set_gather_dedup")
     ctx.last_link_rows = None
+
+
+def tier_set_gather_split(ctx: Context, link_blocks: int, min_rows: int = 0):
+    """Copy the cold rows of every gather call of >= min_rows rows with a launch of link_blocks
+    blocks of its own, beside the full-width launch for the hot rows (see tier.h); 0 = one launch."""
+    _check(_load().tier_set_gather_split(ctx.handle, link_blocks, min_rows), "tier_set_gather_split")
 
 
 def tier_set_gather_stream(ctx: Context, stream=None):

@@ -335,6 +335,63 @@ def test_shared_misses_give_the_same_rows(dim, boundary):
         w.close()
 
 
+@pytest.mark.parametrize("dim,boundary,link_blocks", [(100, False, 128), (32, False, 3), (8, True, 64), (768, False, 16)])
+def test_split_gather_gives_the_same_rows(dim, boundary, link_blocks):
+    """With tier_set_gather_split the cold rows of a call are listed and copied by a small launch
+    on a stream of the context's own, beside the launch for the hot rows: rows, counts and the
+    oracle's gather are unchanged, whatever the budget (none hot .. all hot), on either stream."""
+    ip, ix = synth.rmat_csr(6000, 80_000, 7, "cpu")
+    w = World(ip, ix, dim=dim)
+    try:
+        rng = np.random.default_rng(dim + link_blocks)
+        counts = rng.integers(0, 20, w.n).astype(np.uint32)
+        B = tier.tier_max_batches(w.ctx)
+        seeds = rng.choice(w.n, 64 * B - 11, replace=False).astype(np.int32)
+        blk = tier.tier_sample_minibatches(w.ctx, torch.from_numpy(seeds).to(DEV), 64, list(range(B)), (10, 6))
+        ids = torch.cat([blk.frontier(b) for b in range(B)]).cpu().numpy()
+        gs = torch.cuda.Stream()
+        for hot_rows in (0, 1, 500, w.n):
+            if boundary:
+                n_hot = tier.tier_place_boundary(w.ctx, hot_rows * w.row_bytes)
+                oslot = np.where(np.arange(w.n) < n_hot, np.arange(w.n), -1).astype(np.int32)
+            else:
+                slot, n_hot = tier.tier_place(w.ctx, torch.from_numpy(counts.view(np.int32)).to(DEV), hot_rows * w.row_bytes)
+                _, oslot, _ = orc.place(counts, w.row_bytes, hot_rows * w.row_bytes)
+            cache = orc.fill_cache(w.feat_bytes, oslot, n_hot)
+            want, whit, wmiss = orc.gather(w.feat_bytes, cache, oslot, ids)
+            tier.tier_set_gather_split(w.ctx, 0)
+            plain, offs, hit0, miss0 = tier.tier_gather_minibatches(w.ctx, blk, B, want_stats=True)
+            assert (hit0, miss0) == (whit, wmiss)
+            tier.tier_set_gather_split(w.ctx, link_blocks, 0)
+            for stream in (None, gs, None):
+                tier.tier_set_gather_stream(w.ctx, stream)
+                for rep in range(2):                                     # the cold list is rebuilt per call
+                    got, offs2, hit, miss = tier.tier_gather_minibatches(w.ctx, blk, B, want_stats=True)
+                    assert offs2 == offs and (hit, miss) == (whit, wmiss) and torch.equal(got, plain)
+                    assert np.array_equal(got.view(torch.uint8).cpu().numpy().reshape(-1, w.row_bytes), want)
+                m = 4999                                                 # a smaller call right after a larger one
+                one, h1, m1 = tier.tier_gather_features(w.ctx, torch.from_numpy(ids[:m]).to(DEV), want_stats=True)
+                w1, wh1, wm1 = orc.gather(w.feat_bytes, cache, oslot, ids[:m])
+                assert (h1, m1) == (wh1, wm1)
+                assert np.array_equal(one.view(torch.uint8).cpu().numpy().reshape(-1, w.row_bytes), w1)
+        # below min_rows the uniform launch serves the call; empty and bad calls behave as before
+        tier.tier_set_gather_split(w.ctx, link_blocks, 10**9)
+        got, _, _, _ = tier.tier_gather_minibatches(w.ctx, blk, B, want_stats=True)
+        assert torch.equal(got, plain)
+        tier.tier_set_gather_split(w.ctx, link_blocks, 0)
+        empty, _, _ = tier.tier_gather_features(w.ctx, torch.zeros(0, dtype=torch.int32, device=DEV), want_stats=True)
+        assert empty.shape[0] == 0
+        bad = torch.tensor([0, w.n, 3], dtype=torch.int32, device=DEV)
+        with pytest.raises(tier.TierError):
+            tier.tier_gather_features(w.ctx, bad, want_stats=True)
+        ok, _, _ = tier.tier_gather_features(w.ctx, torch.from_numpy(ids[:100]).to(DEV), want_stats=True)   # flag cleared
+        assert np.array_equal(ok.view(torch.uint8).cpu().numpy().reshape(-1, w.row_bytes), w.feat_bytes[ids[:100]])
+        with pytest.raises(tier.TierError):
+            tier.tier_set_gather_split(w.ctx, -1, 0)
+    finally:
+        w.close()
+
+
 def test_gather_on_its_own_stream_while_sampling(small):
     """Gathers of one group run on a second stream while the next group is sampled into the
     other set of buffers; every group's rows still match the table."""
