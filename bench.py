@@ -320,7 +320,7 @@ def main():
 
     reorder = None
     if not args.no_reorder:
-        reorder = reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log)
+        reorder = reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, args.link_blocks)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -437,7 +437,7 @@ def run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_
     return {"budget": budget, "depth": depth}
 
 
-def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log):
+def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, link_blocks):
     """The paper's own layout (Sec. 3.2, Alg. 2): graph and table renamed by rank, hot part =
     ids below the boundary, gather without a map.  Times the reordering and one sampled and
     gathered epoch on the reordered data (its draws differ: they are keyed by node id)."""
@@ -460,6 +460,7 @@ def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget,
         _, res["rows_ms"] = timed(lambda: tier.tier_reorder_rows(ctx, rank, table2))
         train2 = tier.tier_relabel_ids(ctx, rank, train)
         ctx2 = tier.tier_create(ip2, ix2, table2)
+        tier.tier_set_gather_split(ctx2, link_blocks, SPLIT_MIN_ROWS)
         n_hot, res["place_boundary_ms"] = timed(lambda: tier.tier_place_boundary(ctx2, budget))
         bs = wl.batch_size; L = len(wl.fanouts)
         n_train = train2.numel(); n_batches = -(-n_train // bs)

@@ -46,12 +46,14 @@ __device__ inline int is_cold(int32_t id, const int32_t *__restrict__ slot, int6
     return MODE == GATHER_SLOT ? slot[id] < 0 : id >= n_hot;
 }
 
-// The cold workers of a split launch: the first `workers` blocks of grid row 0.  A wave
-// takes the next chunk of 64 requests off a counter (chunks numbered list by list), finds
-// the cold ones among them with one ballot and copies those, kRowsInFlight per group of
-// LPR lanes at a time.  The counter makes the waves finish together whatever the mix of
-// hot and cold in their chunks; the last wave to run dry leaves both counters at zero for
-// the next launch on the stream.
+// The cold workers of a split launch: the first `workers` blocks of grid row 0.  The
+// requests are numbered in units of 64 (list by list); a wave takes the next unit off a
+// counter, which makes the waves finish together whatever the mix of hot and cold in
+// their units, finds the unit's cold requests with one ballot and copies them,
+// kRowsInFlight per group of LPR lanes at a time.  The counter is read two units ahead and
+// the ids one unit ahead, so that a call with few cold rows is paced by one lookup per
+// unit, not by three dependent ones.  The last wave to run dry leaves both counters at
+// zero for the next launch on the stream.
 template <int LPR, int MODE>
 __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, const int32_t *__restrict__ slot,
                                       int64_t n_nodes, int64_t n_hot, int workers,
@@ -69,27 +71,32 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
     int64_t total = 0;
     for (int b = 0; b < n_lists; ++b) total += (lists.n[b] + 63) / 64;
 
-    auto grab = [&]() -> int64_t {
-        unsigned long long q = 0;
-        if (lane64 == 0) q = atomicAdd(next, 1ull);
-        return (int64_t)__shfl(q, 0);
-    };
-    int64_t q = grab();
-    while (q < total) {
-        const int64_t q_next = grab();             // in flight while this chunk is copied
+    // the counter's value arrives in lane 0; it is broadcast only where it is needed, an
+    // iteration later, so that the atomic's latency hides behind the work in between
+    auto grab = [&]() -> unsigned long long { return lane64 == 0 ? atomicAdd(next, 1ull) : 0ull; };
+    auto bcast = [&](unsigned long long raw) -> int64_t { return (int64_t)__shfl(raw, 0); };
+    // this lane's id of unit u (-1 beyond the list or the call) and the output row of the unit's first request
+    auto load_unit = [&](int64_t u, uint4 *&out) -> int32_t {
+        out = nullptr;
+        if (u >= total) return -1;
         int b = 0;
-        int64_t c = q;
-        for (;; ++b) {                              // q < total: ends inside the lists
-            const int64_t nc = (lists.n[b] + 63) / 64;
-            if (c < nc) break;
-            c -= nc;
+        for (;; ++b) {                              // u < total: ends inside the lists
+            const int64_t nu = (lists.n[b] + 63) / 64;
+            if (u < nu) break;
+            u -= nu;
         }
-        const int32_t *__restrict__ ids = lists.ids[b];
-        const int64_t n = lists.n[b];
-        uint4 *__restrict__ out = out_base + lists.out_row[b] * cpr;
-        const int64_t i = c * 64 + lane64;
-        const int32_t id = i < n ? ids[i] : -1;
-        const int cold = i < n ? is_cold<MODE>(id, slot, n_nodes, n_hot) : 0;
+        out = out_base + (lists.out_row[b] + u * 64) * cpr;
+        const int64_t i = u * 64 + lane64;
+        return i < lists.n[b] ? lists.ids[b][i] : -1;
+    };
+
+    int64_t q = bcast(grab()), q1 = bcast(grab());
+    uint4 *out = nullptr, *out1 = nullptr;
+    int32_t id = load_unit(q, out);
+    while (q < total) {
+        const unsigned long long raw2 = grab();
+        const int32_t id1 = load_unit(q1, out1);
+        const int cold = id >= 0 ? is_cold<MODE>(id, slot, n_nodes, n_hot) : 0;
         unsigned long long mask = __ballot(cold);
         while (mask) {
             const uint4 *src[kRowsInFlight];
@@ -106,7 +113,7 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
                 const int32_t sid = __shfl(id, bit < 0 ? 0 : bit);
                 if (bit >= 0 && k / kRowsInFlight == g) {
                     src[k % kRowsInFlight] = host + (int64_t)sid * cpr;
-                    dst[k % kRowsInFlight] = out + (c * 64 + bit) * cpr;
+                    dst[k % kRowsInFlight] = out + (int64_t)bit * cpr;
                 }
             }
             for (int cc = lane; cc < cpr; cc += LPR) {
@@ -119,12 +126,15 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
 #pragma unroll
                 for (int j = 0; j < kRowsInFlight; ++j)
                     if (dst[j]) {
-                        u32x4 t = {v[j].x, v[j].y, v[j].z, v[j].w};
-                        __builtin_nontemporal_store(t, (u32x4 *)&dst[j][cc]);
+                        u32x4 t4 = {v[j].x, v[j].y, v[j].z, v[j].w};
+                        __builtin_nontemporal_store(t4, (u32x4 *)&dst[j][cc]);
                     }
             }
         }
-        q = q_next;
+        q = q1;
+        q1 = bcast(raw2);
+        id = id1;
+        out = out1;
     }
     if (lane64 == 0 && atomicAdd(done, 1ull) == n_waves - 1) {    // every other wave has made its last grab
         atomicExch(next, 0ull);
@@ -416,7 +426,9 @@ static int gather_call(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int6
 {
     const int mode = ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT;
     hipStream_t st = ctx->gather_stream;
-    if (!ctx->dedup && ctx->link_blocks > 0 && n_total > 0 && n_total >= ctx->split_min_rows)
+    // nothing to split off when every row is in the cache
+    if (!ctx->dedup && ctx->link_blocks > 0 && n_total > 0 && n_total >= ctx->split_min_rows &&
+        ctx->n_hot < ctx->n_nodes)
         return launch_lists(ctx, lists, n_lists, n_max, mode, false, out, count_hits, st, ctx->gmeta, true);
     if (!ctx->dedup || n_total == 0)
         return launch_lists(ctx, lists, n_lists, n_max, mode, false, out, count_hits, st, ctx->gmeta);
