@@ -160,7 +160,12 @@ uint64_t tier_batch_seed(uint64_t seed, uint32_t epoch, uint32_t batch);
  * copied into an HBM cache owned by the context (cache row = rank) and the
  * node->slot map becomes slot[v] = rank[v] if rank[v] < n_hot, else -1.  Replaces
  * any earlier placement.  counts: (device) n_nodes entries.  slot_map (device,
- * optional): receives a copy of the map.  n_hot (host, optional).  Waits. */
+ * optional): receives a copy of the map.  n_hot (host, optional).  Waits once inside
+ * the sort (and first for gathers still running on the gather stream), then returns with
+ * the map enqueued on the context's stream and the cache fill enqueued on the gather
+ * stream (tier_set_gather_stream), ahead of every later gather: the caller may go on
+ * sampling while the hot rows cross the host link.  The host table must not change
+ * before that fill is done (synchronize the gather stream first). */
 int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes,
                int32_t *slot_map, int64_t *n_hot);
 
@@ -193,7 +198,8 @@ int tier_place_scores(tier_ctx *ctx, const double *scores, uint64_t budget_bytes
  * descending order, and the old-id -> new-id map built from them).  counts: (device)
  * n_nodes scores.  rank (device, optional): rank[v] = position of v in the order (count
  * descending, id ascending) = the new id of v.  order (device, optional): order[r] = the
- * node of rank r.  Waits. */
+ * node of rank r.  Waits once inside the sort; the outputs are complete in the order of
+ * the context's stream. */
 int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, int32_t *order);
 
 /* Graph reordering (Sec. 3.2, Alg. 2): the context's graph with every node renamed to

@@ -126,6 +126,14 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipFree(ctx->gpartial);
     (void)hipFree(ctx->uniq_ids);
     (void)hipFree(ctx->stage);
+    for (int i = 0; i < 2; ++i) {
+        (void)hipFree(ctx->sort.keys[i]);
+        (void)hipFree(ctx->sort.vals[i]);
+    }
+    (void)hipFree(ctx->sort.hist);
+    (void)hipFree(ctx->sort.partial);
+    (void)hipFree(ctx->sort.mask);
+    if (ctx->ev_place) (void)hipEventDestroy(ctx->ev_place);
     (void)hipFree(ctx->gmeta);
     (void)hipHostFree(ctx->gmeta_host);
     (void)hipFree(ctx->meta);
@@ -147,6 +155,7 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
         attr.type != hipMemoryTypeManaged)
         return TIER_EINVAL;
     void *dev_view = nullptr;
+    c->rows_on_host = attr.type == hipMemoryTypeHost;
     if (attr.type == hipMemoryTypeHost) {
         TIER_HIP(c, hipHostGetDevicePointer(&dev_view, const_cast<void *>(feat->host_rows), 0));
     } else {
@@ -171,6 +180,7 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     TIER_HIP(c, hipHostMalloc((void **)&c->meta_host, S * META_WORDS * sizeof(int64_t), hipHostMallocDefault));
     TIER_HIP(c, hipMalloc(&c->gmeta, GMETA_WORDS * sizeof(int64_t)));
     TIER_HIP(c, hipHostMalloc((void **)&c->gmeta_host, GMETA_WORDS * sizeof(int64_t), hipHostMallocDefault));
+    TIER_HIP(c, hipEventCreateWithFlags(&c->ev_place, hipEventDisableTiming));
     TIER_HIP(c, hipMalloc(&c->partial_hop, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->partial_bm, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
     k_fill_i32<<<grid_for(n * (int64_t)S, 256, 8192), 256, 0, c->stream>>>(c->local_idx, n * (int64_t)S, -1);
@@ -222,6 +232,24 @@ int tier_create(tier_ctx **out, const tier_csr *csr, const tier_feat *feat, void
     *out = c;
     return TIER_OK;
 }
+
+}  // extern "C"
+
+int tier_ensure(tier_ctx *ctx, void **buf, size_t *cap, size_t bytes)
+{
+    if (bytes == 0) bytes = 1;
+    if (*buf && *cap >= bytes) return TIER_OK;
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+    if (*buf) TIER_HIP(ctx, hipFree(*buf));
+    *buf = nullptr;
+    *cap = 0;
+    TIER_HIP(ctx, hipMalloc(buf, bytes));
+    *cap = bytes;
+    return TIER_OK;
+}
+
+extern "C" {
 
 const char *tier_strerror(int status)
 {

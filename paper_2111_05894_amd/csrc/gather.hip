@@ -28,6 +28,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kRowsInFlight = 4;        // measured best of 2 / 4 / 8 on MI355X
+constexpr int kLinkBlocks = 64;         // blocks of a launch that reads host rows only (best of 32 .. 512, full grid)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // The id lists one launch serves (blockIdx.y picks one): a mini-batch each.
@@ -354,8 +355,7 @@ __global__ void k_clear_gather_error(int64_t *meta) { meta[META_ERROR] = 0; }
 
 }  // namespace
 
-// One k_gather launch.  Cache fills (GATHER_HOST on the main stream) and gathers (on the
-// gather stream, with bookkeeping words of their own) say where they run.
+// One k_gather launch on stream st, bookkeeping words in meta.
 static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, bool staged,
                         void *out, bool count_hits, hipStream_t st, int64_t *meta, bool split = false)
 {
@@ -368,6 +368,10 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
     int64_t blocks = (n_max + (int64_t)groups * kRowsInFlight - 1) / ((int64_t)groups * kRowsInFlight);
     const int64_t max_blocks = 1 << 18;     // beyond that groups loop; fewer blocks cost ~5 % of the all-hit rate
     if (blocks > max_blocks) blocks = max_blocks;
+    if (mode == GATHER_HOST && ctx->rows_on_host) {
+        // every row over the host link: a few dozen blocks fill it, more only queue up
+        if (blocks > kLinkBlocks) blocks = kLinkBlocks;
+    }
     const int cold_workers = split ? (int)(ctx->link_blocks < blocks ? ctx->link_blocks : blocks) : 0;
     const dim3 grid((unsigned)blocks, (unsigned)(n_lists + (split ? 1 : 0)));
 #define GATHER_LAUNCH(L, M, S, P)                                                                    \
@@ -402,9 +406,7 @@ int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, v
     id_lists_t lists = {};
     lists.ids[0] = ids;
     lists.n[0] = n;
-    const bool fill = mode == GATHER_HOST;
-    return launch_lists(ctx, lists, 1, n, mode, false, out, count_hits, fill ? ctx->stream : ctx->gather_stream,
-                        fill ? ctx->meta : ctx->gmeta);
+    return launch_lists(ctx, lists, 1, n, mode, false, out, count_hits, ctx->gather_stream, ctx->gmeta);
 }
 
 static int grow(tier_ctx *ctx, void **buf, int64_t *cap, int64_t want, size_t elem)

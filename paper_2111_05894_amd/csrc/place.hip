@@ -200,44 +200,39 @@ int grid_for(int64_t n, int block, int cap)
     return (int)g;
 }
 
-struct sort_bufs {
-    void *keys[2] = {nullptr, nullptr};
-    int32_t *vals[2] = {nullptr, nullptr};
-    uint32_t *hist = nullptr;
-    uint32_t *partial = nullptr;
-    unsigned long long *mask_dev = nullptr;
-    ~sort_bufs()
-    {
-        for (int i = 0; i < 2; ++i) {
-            (void)hipFree(keys[i]);
-            (void)hipFree(vals[i]);
-        }
-        (void)hipFree(hist);
-        (void)hipFree(partial);
-        (void)hipFree(mask_dev);
+typedef tier_sort_bufs sort_bufs;     // owned by the context, reused by every placement
+
+// The previous placement's cache fill reads the old order on the gather stream.
+int release_sort_bufs(tier_ctx *ctx)
+{
+    if (ctx->fill_pending) {
+        TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+        ctx->fill_pending = false;
     }
-};
+    return TIER_OK;
+}
 
 // Stable ascending sort of 0..n-1 by keys (b.keys[0], already filled) on the context's
-// stream.  *order_out points into b (position -> id) and is valid until b dies.  Waits
-// once (for the set of digits in which the keys differ).
+// stream.  *order_out points into b (position -> id) and is valid until the next sort.
+// Waits once (for the set of digits in which the keys differ).
 template <typename K>
 int sort_ids_by_keys(tier_ctx *ctx, sort_bufs &b, int32_t **order_out)
 {
     const int64_t n = ctx->n_nodes;
     hipStream_t st = ctx->stream;
     K *keys[2] = {(K *)b.keys[0], nullptr};
-    TIER_HIP(ctx, hipMalloc(&b.mask_dev, sizeof(unsigned long long)));
-    k_zero_u64<<<1, 1, 0, st>>>(b.mask_dev);
-    if (n > 0) k_varying_bits<K><<<grid_for(n, 256, 2048), 256, 0, st>>>(keys[0], n, b.mask_dev);
-    TIER_HIP(ctx, hipMemcpyAsync(ctx->meta_host, b.mask_dev, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    if (!b.mask) TIER_HIP(ctx, hipMalloc(&b.mask, sizeof(unsigned long long)));
+    k_zero_u64<<<1, 1, 0, st>>>(b.mask);
+    if (n > 0) k_varying_bits<K><<<grid_for(n, 256, 2048), 256, 0, st>>>(keys[0], n, b.mask);
+    TIER_HIP(ctx, hipMemcpyAsync(ctx->meta_host, b.mask, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
     TIER_HIP(ctx, hipStreamSynchronize(st));
     const unsigned long long mask = *(unsigned long long *)ctx->meta_host;
     int shifts[8], passes = 0;
     for (int d = 0; d < (int)sizeof(K); ++d)
         if ((mask >> (8 * d)) & 0xffull) shifts[passes++] = 8 * d;
 
-    TIER_HIP(ctx, hipMalloc(&b.vals[0], (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
+    int rc = tier_ensure(ctx, (void **)&b.vals[0], &b.vals_cap[0], (size_t)n * sizeof(int32_t));
+    if (rc != TIER_OK) return rc;
     if (passes == 0) {
         k_iota<<<grid_for(n, 256, 4096), 256, 0, st>>>(b.vals[0], n);
         TIER_HIP(ctx, hipGetLastError());
@@ -250,11 +245,13 @@ int sort_ids_by_keys(tier_ctx *ctx, sort_bufs &b, int32_t **order_out)
     const int n_shares = (int)((n + share - 1) / share);
     const int64_t n_hist = (int64_t)kDigits * n_shares;
     const int scan_grid = grid_for(n_hist, 4 * kScanBlock, 1024);
-    TIER_HIP(ctx, hipMalloc(&b.hist, (size_t)n_hist * sizeof(uint32_t)));
-    TIER_HIP(ctx, hipMalloc(&b.partial, 1024 * sizeof(uint32_t)));
+    rc = tier_ensure(ctx, (void **)&b.hist, &b.hist_cap, (size_t)n_hist * sizeof(uint32_t));
+    if (rc != TIER_OK) return rc;
+    if (!b.partial) TIER_HIP(ctx, hipMalloc(&b.partial, 1024 * sizeof(uint32_t)));
     if (passes > 1) {
-        TIER_HIP(ctx, hipMalloc(&b.vals[1], (size_t)n * sizeof(int32_t)));
-        TIER_HIP(ctx, hipMalloc(&b.keys[1], (size_t)n * sizeof(K)));
+        rc = tier_ensure(ctx, (void **)&b.vals[1], &b.vals_cap[1], (size_t)n * sizeof(int32_t));
+        if (rc == TIER_OK) rc = tier_ensure(ctx, &b.keys[1], &b.keys_cap[1], (size_t)n * sizeof(K));
+        if (rc != TIER_OK) return rc;
         keys[1] = (K *)b.keys[1];
     }
     // pass j reads buffers j % 2 and writes buffers (j + 1) % 2; with one pass only ids move
@@ -279,7 +276,9 @@ int sort_ids_by_keys(tier_ctx *ctx, sort_bufs &b, int32_t **order_out)
 static int sort_by_count(tier_ctx *ctx, const uint32_t *counts, sort_bufs &b, int32_t **order_out)
 {
     const int64_t n = ctx->n_nodes;
-    TIER_HIP(ctx, hipMalloc(&b.keys[0], (size_t)(n > 0 ? n : 1) * sizeof(uint32_t)));
+    int rc = release_sort_bufs(ctx);
+    if (rc == TIER_OK) rc = tier_ensure(ctx, &b.keys[0], &b.keys_cap[0], (size_t)n * sizeof(uint32_t));
+    if (rc != TIER_OK) return rc;
     if (n > 0)
         k_keys_from_counts<<<grid_for(n, 256, 4096), 256, 0, ctx->stream>>>(counts, n, (uint32_t *)b.keys[0]);
     return sort_ids_by_keys<uint32_t>(ctx, b, order_out);
@@ -289,7 +288,9 @@ static int sort_by_count(tier_ctx *ctx, const uint32_t *counts, sort_bufs &b, in
 static int sort_by_score(tier_ctx *ctx, const double *scores, sort_bufs &b, int32_t **order_out)
 {
     const int64_t n = ctx->n_nodes;
-    TIER_HIP(ctx, hipMalloc(&b.keys[0], (size_t)(n > 0 ? n : 1) * sizeof(uint64_t)));
+    int rc = release_sort_bufs(ctx);
+    if (rc == TIER_OK) rc = tier_ensure(ctx, &b.keys[0], &b.keys_cap[0], (size_t)n * sizeof(uint64_t));
+    if (rc != TIER_OK) return rc;
     if (n > 0)
         k_keys_from_scores<<<grid_for(n, 256, 4096), 256, 0, ctx->stream>>>(scores, n, (uint64_t *)b.keys[0]);
     return sort_ids_by_keys<uint64_t>(ctx, b, order_out);
@@ -303,37 +304,41 @@ static int emit_rank(tier_ctx *ctx, const int32_t *ord, int32_t *rank, int32_t *
     if (order && n > 0)
         TIER_HIP(ctx, hipMemcpyAsync(order, ord, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, ctx->stream));
     TIER_HIP(ctx, hipGetLastError());
-    TIER_HIP(ctx, hipStreamSynchronize(ctx->stream));   // the sort buffers are freed on return
     return TIER_OK;
 }
 
-// slot map + HBM cache from an order (rank -> node)
+// slot map + HBM cache from an order (rank -> node, in the context's sort scratch).  The map
+// is written on the context's stream, the cache filled on the gather stream behind it; the
+// call does not wait for either.
 static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget_bytes, int32_t *slot_map,
                             int64_t *n_hot_out)
 {
     const int64_t n = ctx->n_nodes;
-    hipStream_t st = ctx->stream;
+    hipStream_t st = ctx->stream, gs = ctx->gather_stream;
     int64_t n_hot = (int64_t)(budget_bytes / (uint64_t)ctx->row_bytes);
     if (n_hot > n) n_hot = n;
-    if (n > 0) k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n, n_hot, ctx->slot);
-
-    // (re)build the HBM cache: cache row r = feature row of the node of rank r
-    TIER_HIP(ctx, hipStreamSynchronize(st));
-    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));   // no gather may still read the old cache
+    if (gs != st) TIER_HIP(ctx, hipStreamSynchronize(gs));   // no gather may still read the old map or cache
     ctx->placed = false;
     ctx->boundary = false;
-    if (ctx->cache) TIER_HIP(ctx, hipFree(ctx->cache));
-    ctx->cache = nullptr;
     ctx->n_hot = 0;
+    if (n > 0) k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n, n_hot, ctx->slot);
+    TIER_HIP(ctx, hipGetLastError());
+
+    // (re)build the HBM cache: cache row r = feature row of the node of rank r
     if (n_hot > 0) {
-        TIER_HIP(ctx, hipMalloc(&ctx->cache, (size_t)n_hot * (size_t)ctx->row_bytes));
-        int rc = tier_launch_gather(ctx, order, n_hot, GATHER_HOST, ctx->cache, false);
+        int rc = tier_ensure(ctx, (void **)&ctx->cache, &ctx->cache_cap, (size_t)n_hot * (size_t)ctx->row_bytes);
+        if (rc != TIER_OK) return rc;
+        if (gs != st) {
+            TIER_HIP(ctx, hipEventRecord(ctx->ev_place, st));
+            TIER_HIP(ctx, hipStreamWaitEvent(gs, ctx->ev_place, 0));
+            ctx->fill_pending = true;
+        }
+        rc = tier_launch_gather(ctx, order, n_hot, GATHER_HOST, ctx->cache, false);
         if (rc != TIER_OK) return rc;
     }
     ctx->n_hot = n_hot;
     if (slot_map && n > 0)
         TIER_HIP(ctx, hipMemcpyAsync(slot_map, ctx->slot, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
-    TIER_HIP(ctx, hipStreamSynchronize(st));   // `order` is freed by the caller after this
     ctx->placed = true;
     if (n_hot_out) *n_hot_out = n_hot;
     return TIER_OK;
@@ -342,7 +347,7 @@ static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget
 extern "C" int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, int32_t *order)
 {
     if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
-    sort_bufs b;
+    sort_bufs &b = ctx->sort;
     int32_t *ord = nullptr;
     int rc = sort_by_count(ctx, counts, b, &ord);
     if (rc != TIER_OK) return rc;
@@ -352,7 +357,7 @@ extern "C" int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, i
 extern "C" int tier_rank_scores(tier_ctx *ctx, const double *scores, int32_t *rank, int32_t *order)
 {
     if (!ctx || (!scores && ctx->n_nodes > 0)) return TIER_EINVAL;
-    sort_bufs b;
+    sort_bufs &b = ctx->sort;
     int32_t *ord = nullptr;
     int rc = sort_by_score(ctx, scores, b, &ord);
     if (rc != TIER_OK) return rc;
@@ -363,7 +368,7 @@ extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget
                           int64_t *n_hot_out)
 {
     if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
-    sort_bufs b;
+    sort_bufs &b = ctx->sort;
     int32_t *order = nullptr;
     int rc = sort_by_count(ctx, counts, b, &order);
     if (rc != TIER_OK) return rc;
@@ -374,7 +379,7 @@ extern "C" int tier_place_scores(tier_ctx *ctx, const double *scores, uint64_t b
                                  int64_t *n_hot_out)
 {
     if (!ctx || (!scores && ctx->n_nodes > 0)) return TIER_EINVAL;
-    sort_bufs b;
+    sort_bufs &b = ctx->sort;
     int32_t *order = nullptr;
     int rc = sort_by_score(ctx, scores, b, &order);
     if (rc != TIER_OK) return rc;
@@ -392,11 +397,11 @@ extern "C" int tier_place_boundary(tier_ctx *ctx, uint64_t budget_bytes, int64_t
     TIER_HIP(ctx, hipStreamSynchronize(st));
     TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
     ctx->placed = false;
-    if (ctx->cache) TIER_HIP(ctx, hipFree(ctx->cache));
-    ctx->cache = nullptr;
+    ctx->fill_pending = false;
     ctx->n_hot = 0;
     if (n_hot > 0) {
-        TIER_HIP(ctx, hipMalloc(&ctx->cache, (size_t)n_hot * (size_t)ctx->row_bytes));
+        int rc = tier_ensure(ctx, (void **)&ctx->cache, &ctx->cache_cap, (size_t)n_hot * (size_t)ctx->row_bytes);
+        if (rc != TIER_OK) return rc;
         TIER_HIP(ctx, hipMemcpyAsync(ctx->cache, ctx->host_rows, (size_t)n_hot * (size_t)ctx->row_bytes,
                                      hipMemcpyDefault, st));
         TIER_HIP(ctx, hipStreamSynchronize(st));

@@ -23,6 +23,19 @@ enum {
 
 #define TIER_SCAN_BLOCKS 1024                 // upper limit of blocks in a two-phase scan
 
+// Scratch of the placement sort, kept by the context between calls.  `vals` of the last
+// sort holds the order (rank -> node) that the cache fill reads on the gather stream.
+struct tier_sort_bufs {
+    void *keys[2];
+    size_t keys_cap[2];          // bytes
+    int32_t *vals[2];
+    size_t vals_cap[2];
+    uint32_t *hist;
+    size_t hist_cap;
+    uint32_t *partial;           // 1024 words
+    unsigned long long *mask;    // one word
+};
+
 struct tier_ctx {
     hipStream_t stream;
     hipStream_t gather_stream;   // stream of tier_gather_features (= stream unless set apart)
@@ -48,6 +61,7 @@ struct tier_ctx {
     bool indptr_i64;
     const int32_t *indices;
     const uint8_t *host_rows;
+    bool rows_on_host;       // the table is host memory read over the link (not a device allocation)
     int64_t row_bytes;
     // per-node scratch, one copy per slot (mini-batch sampled side by side)
     int n_slots;
@@ -59,6 +73,10 @@ struct tier_ctx {
     // placement
     int32_t *slot;           // n_nodes
     uint8_t *cache;          // n_hot * row_bytes
+    size_t cache_cap;        // bytes allocated (kept across placements, grown on demand)
+    tier_sort_bufs sort;
+    hipEvent_t ev_place;     // orders the cache fill (gather stream) after the slot map (main stream)
+    bool fill_pending;       // a cache fill may still be reading sort.vals on the gather stream
     int64_t n_hot;
     bool placed;
     bool boundary;           // true: rows are in rank order, hot <=> id < n_hot (no slot map)
@@ -85,6 +103,9 @@ struct tier_ctx {
 // mode 0: every row from host_rows; 1: through the slot map; 2: by the boundary n_hot.
 enum { GATHER_HOST = 0, GATHER_SLOT = 1, GATHER_BOUNDARY = 2 };
 int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, void *out, bool count_hits);
+
+// context.hip: make *buf at least `bytes` long (contents are not kept).  Growing waits for both streams.
+int tier_ensure(tier_ctx *ctx, void **buf, size_t *cap, size_t bytes);
 
 // context.hip: copy the bookkeeping array into ctx->meta_host and wait for the
 // stream.  Returns TIER_EINVAL once (and clears the flag) when a kernel met an id

@@ -437,6 +437,7 @@ def test_hot_rows_come_from_the_cache():
         counts = np.arange(n, dtype=np.uint32)[::-1].copy()          # node 0 hottest
         slot, n_hot = tier.tier_place(w.ctx, torch.from_numpy(counts.view(np.int32)).to(DEV), 1000 * w.row_bytes)
         orig = w.feat.clone()
+        torch.cuda.synchronize()                                     # the cache fill is asynchronous
         w.feat += 1.0                                                # host copy changes after placement
         ids = torch.arange(n, dtype=torch.int32, device=DEV)
         out = tier.tier_gather_features(w.ctx, ids).cpu()
