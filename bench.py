@@ -540,10 +540,23 @@ def cpu_baseline(args, wl, indptr, indices, train, epoch_ids, table, budget, bse
     with ThreadPoolExecutor(threads) as ex:
         rows = sum(ex.map(one, range(nb)))
     dt = time.perf_counter() - t0
+    # one thread: sample + gather of a sixteenth of those mini-batches (placement as above)
+    nb1 = max(1, nb // 16)
+    t1 = time.perf_counter()
+    rows1 = sum(one(b) for b in range(nb1))
+    dt1 = time.perf_counter() - t1
+    t2 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        rows_sg = sum(ex.map(one, range(nb)))
+    dt_sg = time.perf_counter() - t2
     return {"value": round(rows * R / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"first {nb} of the mini-batches: presample of {nb} batches, placement of all {n} nodes, "
                       f"then sample + gather of {nb} batches; {dt:.1f} s wall on {threads} threads",
-            "seconds": round(dt, 2)}
+            "seconds": round(dt, 2),
+            "sample_gather_only": {"value": round(rows_sg * R / dt_sg / 1e9, 4), "cores": threads,
+                                   "sample": f"sample + gather of the same {nb} mini-batches, {dt_sg:.1f} s"},
+            "single_thread": {"value": round(rows1 * R / dt1 / 1e9, 4), "cores": 1,
+                              "sample": f"sample + gather of the first {nb1} mini-batches, {dt1:.1f} s"}}
 
 
 def measured_traffic(workload):

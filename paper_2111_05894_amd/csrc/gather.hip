@@ -50,11 +50,13 @@ __device__ inline int is_cold(int32_t id, const int32_t *__restrict__ slot, int6
 // The cold workers of a split launch: the first `workers` blocks of grid row 0.  The
 // requests are numbered in units of 64 (list by list); a wave takes the next unit off a
 // counter, which makes the waves finish together whatever the mix of hot and cold in
-// their units, finds the unit's cold requests with one ballot and copies them,
-// kRowsInFlight per group of LPR lanes at a time.  The counter is read two units ahead and
-// the ids one unit ahead, so that a call with few cold rows is paced by one lookup per
-// unit, not by three dependent ones.  The last wave to run dry leaves both counters at
-// zero for the next launch on the stream.
+// their units, and appends the unit's cold requests (one ballot) to a small queue of its
+// own in LDS.  Whenever the queue holds a full pass - kRowsInFlight rows for each group of
+// LPR lanes - the wave copies one, so the bytes it keeps in flight on the host link do not
+// depend on how many of the requests are cold.  Three stages run ahead of that: the
+// counter is read three units ahead, the ids two, the slot lookups one, so the copies
+// never wait for a lookup.  The last wave to run dry leaves both counters at zero for the
+// next launch on the stream.
 template <int LPR, int MODE>
 __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, const int32_t *__restrict__ slot,
                                       int64_t n_nodes, int64_t n_hot, int workers,
@@ -63,9 +65,14 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
 {
     constexpr int kGroupsPerWave = 64 / LPR;
     constexpr int kPerPass = kGroupsPerWave * kRowsInFlight;
+    constexpr int kQueue = 128;                       // ring: at most kPerPass - 1 + 64 entries wait
+    __shared__ int32_t s_src[kBlock / 64][kQueue];    // host row of a waiting cold request
+    __shared__ int64_t s_dst[kBlock / 64][kQueue];    // its output row
     if ((int)blockIdx.x >= workers) return;
     const int lane64 = threadIdx.x & 63;
     const int g = lane64 / LPR, lane = lane64 % LPR;
+    int32_t *q_src = s_src[threadIdx.x >> 6];
+    int64_t *q_dst = s_dst[threadIdx.x >> 6];
     const unsigned long long n_waves = (unsigned long long)workers * (kBlock / 64);
     unsigned long long *next = (unsigned long long *)&meta[META_COLD_NEXT];
     unsigned long long *done = (unsigned long long *)&meta[META_COLD_DONE];
@@ -76,9 +83,9 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
     // iteration later, so that the atomic's latency hides behind the work in between
     auto grab = [&]() -> unsigned long long { return lane64 == 0 ? atomicAdd(next, 1ull) : 0ull; };
     auto bcast = [&](unsigned long long raw) -> int64_t { return (int64_t)__shfl(raw, 0); };
-    // this lane's id of unit u (-1 beyond the list or the call) and the output row of the unit's first request
-    auto load_unit = [&](int64_t u, uint4 *&out) -> int32_t {
-        out = nullptr;
+    // this lane's request of unit u (-1 beyond the list or the call) and the unit's first output row
+    auto load_unit = [&](int64_t u, int64_t &row0) -> int32_t {
+        row0 = 0;
         if (u >= total) return -1;
         int b = 0;
         for (;; ++b) {                              // u < total: ends inside the lists
@@ -86,57 +93,78 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
             if (u < nu) break;
             u -= nu;
         }
-        out = out_base + (lists.out_row[b] + u * 64) * cpr;
+        row0 = lists.out_row[b] + u * 64;
         const int64_t i = u * 64 + lane64;
         return i < lists.n[b] ? lists.ids[b][i] : -1;
     };
-
-    int64_t q = bcast(grab()), q1 = bcast(grab());
-    uint4 *out = nullptr, *out1 = nullptr;
-    int32_t id = load_unit(q, out);
-    while (q < total) {
-        const unsigned long long raw2 = grab();
-        const int32_t id1 = load_unit(q1, out1);
-        const int cold = id >= 0 ? is_cold<MODE>(id, slot, n_nodes, n_hot) : 0;
-        unsigned long long mask = __ballot(cold);
-        while (mask) {
-            const uint4 *src[kRowsInFlight];
-            uint4 *dst[kRowsInFlight];
+    // copy the n (<= kPerPass) requests at the head of the queue
+    auto copy_pass = [&](unsigned head, int n) {
+        const uint4 *src[kRowsInFlight];
+        uint4 *dst[kRowsInFlight];
 #pragma unroll
-            for (int j = 0; j < kRowsInFlight; ++j) {
-                src[j] = nullptr;
-                dst[j] = nullptr;
-            }
-#pragma unroll
-            for (int k = 0; k < kPerPass; ++k) {   // the k-th cold request of the pass goes to group k / kRowsInFlight
-                const int bit = mask ? __ffsll((long long)mask) - 1 : -1;
-                mask = mask ? mask & (mask - 1) : 0;
-                const int32_t sid = __shfl(id, bit < 0 ? 0 : bit);
-                if (bit >= 0 && k / kRowsInFlight == g) {
-                    src[k % kRowsInFlight] = host + (int64_t)sid * cpr;
-                    dst[k % kRowsInFlight] = out + (int64_t)bit * cpr;
-                }
-            }
-            for (int cc = lane; cc < cpr; cc += LPR) {
-                uint4 v[kRowsInFlight];
-#pragma unroll
-                for (int j = 0; j < kRowsInFlight; ++j) {
-                    v[j] = make_uint4(0, 0, 0, 0);
-                    if (src[j]) v[j] = src[j][cc];
-                }
-#pragma unroll
-                for (int j = 0; j < kRowsInFlight; ++j)
-                    if (dst[j]) {
-                        u32x4 t4 = {v[j].x, v[j].y, v[j].z, v[j].w};
-                        __builtin_nontemporal_store(t4, (u32x4 *)&dst[j][cc]);
-                    }
+        for (int j = 0; j < kRowsInFlight; ++j) {
+            const int k = g * kRowsInFlight + j;
+            src[j] = nullptr;
+            dst[j] = nullptr;
+            if (k < n) {
+                const unsigned e = (head + (unsigned)k) % kQueue;
+                src[j] = host + (int64_t)q_src[e] * cpr;
+                dst[j] = out_base + q_dst[e] * cpr;
             }
         }
-        q = q1;
-        q1 = bcast(raw2);
-        id = id1;
-        out = out1;
+        for (int cc = lane; cc < cpr; cc += LPR) {
+            uint4 v[kRowsInFlight];
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j) {
+                v[j] = make_uint4(0, 0, 0, 0);
+                if (src[j]) v[j] = src[j][cc];
+            }
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j)
+                if (dst[j]) {
+                    u32x4 t4 = {v[j].x, v[j].y, v[j].z, v[j].w};
+                    __builtin_nontemporal_store(t4, (u32x4 *)&dst[j][cc]);
+                }
+        }
+    };
+
+    unsigned head = 0, waiting = 0;                   // wave-uniform state of the queue
+    int64_t q0 = bcast(grab()), q1 = bcast(grab());
+    unsigned long long raw2 = grab();
+    int64_t row0, row1, row2;
+    int32_t id0 = load_unit(q0, row0), id1 = load_unit(q1, row1);
+    int cold0 = id0 >= 0 ? is_cold<MODE>(id0, slot, n_nodes, n_hot) : 0;
+    while (q0 < total) {
+        const unsigned long long raw3 = grab();
+        const int64_t q2 = bcast(raw2);
+        const int32_t id2 = load_unit(q2, row2);
+        const int cold1 = id1 >= 0 ? is_cold<MODE>(id1, slot, n_nodes, n_hot) : 0;
+        // the cold requests of unit 0 join the queue in request order
+        const unsigned long long mask = __ballot(cold0);
+        if (cold0) {
+            const unsigned before = __popcll(mask & ((1ull << lane64) - 1ull));
+            const unsigned e = (head + waiting + before) % kQueue;
+            q_src[e] = id0;
+            q_dst[e] = row0 + lane64;
+        }
+        waiting += (unsigned)__popcll(mask);
+        __builtin_amdgcn_wave_barrier();
+        while (waiting >= (unsigned)kPerPass) {
+            copy_pass(head, kPerPass);
+            head = (head + kPerPass) % kQueue;
+            waiting -= kPerPass;
+        }
+        __builtin_amdgcn_wave_barrier();
+        q0 = q1;
+        q1 = q2;
+        raw2 = raw3;
+        id0 = id1;
+        id1 = id2;
+        row0 = row1;
+        row1 = row2;
+        cold0 = cold1;
     }
+    if (waiting) copy_pass(head, (int)waiting);       // fewer than a pass left
     if (lane64 == 0 && atomicAdd(done, 1ull) == n_waves - 1) {    // every other wave has made its last grab
         atomicExch(next, 0ull);
         atomicExch(done, 0ull);

@@ -26,8 +26,9 @@
 //                   the sampled neighbour (col[] held its node id until then)
 //
 // tier_presample runs the same chain without materialising blocks (no offsets,
-// no edge ids, no relabel) and ends every mini-batch with one atomic increment
-// per frontier node.  Within a mini-batch the frontier nodes are distinct, so
+// no edge ids, no relabel) and gives every node of the final frontier one atomic
+// increment: those reached at the last hop straight from the bitmap (k_bm_count,
+// never listed), the earlier ones when they leave local_idx[] (k_finish).  Within a mini-batch the frontier nodes are distinct, so
 // only mini-batches of different slots can meet on one counter; global atomics
 // handle that (the counters are spread over all nodes, there is no hot spot an
 // LDS staging could absorb).
@@ -424,6 +425,61 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int layer)
     }
 }
 
+// Access counting, last hop: the nodes reached there are neither listed nor indexed (no
+// further hop, no relabelling), each takes its one access straight from the bitmap.
+__global__ __launch_bounds__(kBlock) void k_bm_count_flat(wide_t w, uint32_t *__restrict__ counts)
+{
+    __shared__ int s_wave[kBlock / 64];
+    const slot_view v = view_of(w);
+    int64_t lo, hi;
+    block_range(w.n_words, lo, hi);
+    int sum = 0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
+        uint32_t bits = v.bitmap[i];
+        if (bits) {
+            v.bitmap[i] = 0u;
+            sum += __popc(bits);
+            while (bits) {
+                int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                atomicAdd(&counts[i * 32 + b], 1u);
+            }
+        }
+    }
+    const int tot = block_sum(sum, s_wave);
+    if (threadIdx.x == 0 && tot)
+        atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)tot);
+}
+
+__global__ __launch_bounds__(kBlock) void k_bm_count(wide_t w, uint32_t *__restrict__ counts)
+{
+    __shared__ int s_wave[kBlock / 64];
+    const slot_view v = view_of(w);
+    int64_t lo, hi;
+    block_range(w.n_sum, lo, hi);
+    int sum = 0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
+        uint32_t live = v.summary[i];
+        if (live) v.summary[i] = 0u;
+        while (live) {
+            int j = __ffs(live) - 1;
+            live &= live - 1;
+            const int64_t word = i * 32 + j;
+            uint32_t bits = v.bitmap[word];
+            v.bitmap[word] = 0u;
+            sum += __popc(bits);
+            while (bits) {
+                int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                atomicAdd(&counts[word * 32 + b], 1u);
+            }
+        }
+    }
+    const int tot = block_sum(sum, s_wave);
+    if (threadIdx.x == 0 && tot)
+        atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)tot);
+}
+
 __global__ void k_relabel(wide_t w, relabel_t r)
 {
     const slot_view v = view_of(w);
@@ -436,13 +492,14 @@ __global__ void k_relabel(wide_t w, relabel_t r)
     }
 }
 
-// End of a mini-batch: take its nodes out of local_idx[]; with COUNT, one access
-// per node of the final frontier (the rows a gather for this mini-batch reads).
+// End of a mini-batch: take the nodes of frontier `layer` out of local_idx[]; with COUNT,
+// one access per node (the rows a gather for this mini-batch reads).  Access counting
+// passes the frontier before the last hop: k_bm_count has dealt with the rest.
 template <bool COUNT>
-__global__ void k_finish(wide_t w, int n_layers, uint32_t *__restrict__ counts)
+__global__ void k_finish(wide_t w, int layer, uint32_t *__restrict__ counts)
 {
     const slot_view v = view_of(w);
-    const int64_t n = v.meta[META_NFRONT + n_layers];
+    const int64_t n = v.meta[META_NFRONT + layer];
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t i = t; i < n; i += stride) {
@@ -532,7 +589,10 @@ int enqueue_wide(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_lay
     for (int l = 0; l < n_layers; ++l) {
         if (c->indptr_i64) launch_hop<int64_t>(c, w, cap_nodes[l], l, fanouts[l], o);
         else launch_hop<int32_t>(c, w, cap_nodes[l], l, fanouts[l], o);
-        if (tl) {
+        if (o.counts && l == n_layers - 1) {
+            if (tl) k_bm_count<<<bm_grid, kBlock, 0, c->stream>>>(w, o.counts);
+            else k_bm_count_flat<<<bm_grid, kBlock, 0, c->stream>>>(w, o.counts);
+        } else if (tl) {
             k_bm_partial<<<bm_grid, kBlock, 0, c->stream>>>(w);
             k_bm_emit<<<bm_grid, kBlock, 0, c->stream>>>(w, l);
         } else {
@@ -551,9 +611,10 @@ int enqueue_wide(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_lay
         }
         k_relabel<<<dim3(clamp_grid(most, kBlock, 4096), slots), kBlock, 0, c->stream>>>(w, r);
     }
-    const dim3 fgrid(clamp_grid(cap_nodes[n_layers], kBlock, 4096), slots);
-    if (o.counts) k_finish<true><<<fgrid, kBlock, 0, c->stream>>>(w, n_layers, o.counts);
-    else k_finish<false><<<fgrid, kBlock, 0, c->stream>>>(w, n_layers, nullptr);
+    const int last = o.counts ? n_layers - 1 : n_layers;       // last frontier that was listed
+    const dim3 fgrid(clamp_grid(cap_nodes[last], kBlock, 4096), slots);
+    if (o.counts) k_finish<true><<<fgrid, kBlock, 0, c->stream>>>(w, last, o.counts);
+    else k_finish<false><<<fgrid, kBlock, 0, c->stream>>>(w, last, nullptr);
     TIER_HIP(c, hipGetLastError());
     return TIER_OK;
 }
