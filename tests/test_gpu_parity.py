@@ -427,6 +427,47 @@ def test_gather_on_its_own_stream_while_sampling(small):
         tier.tier_set_gather_stream(small.ctx, None)
 
 
+def test_placements_and_gathers_back_to_back_on_two_streams():
+    """tier_place returns with the cache fill still running on the gather stream: gathers
+    enqueued right after it, and a new placement enqueued right after those, must still
+    see a complete cache each (rows from the oracle's gather, hits from its slot map)."""
+    ip, ix = synth.rmat_csr(30_000, 300_000, 11, "cpu")
+    w = World(ip, ix, dim=100)
+    gs = torch.cuda.Stream()
+    tier.tier_set_gather_stream(w.ctx, gs)
+    tier.tier_set_gather_split(w.ctx, 8, 0)
+    try:
+        rng = np.random.default_rng(4)
+        ids = rng.integers(0, w.n, 200_000).astype(np.int32)
+        ids_d = torch.from_numpy(ids).to(DEV)
+        outs = []
+        for rep, hot_rows in enumerate((20_000, 100, 29_999, 0, 5_000)):
+            counts = rng.integers(0, 50, w.n).astype(np.uint32)
+            cd = torch.from_numpy(counts.view(np.int32)).to(DEV)
+            slot, n_hot = tier.tier_place(w.ctx, cd, hot_rows * w.row_bytes)          # no wait for the fill
+            with torch.cuda.stream(gs):
+                out = tier.tier_gather_features(w.ctx, ids_d)                         # no wait either
+            _, oslot, ohot = orc.place(counts, w.row_bytes, hot_rows * w.row_bytes)
+            outs.append((out, slot, oslot, n_hot, ohot))
+        torch.cuda.synchronize()
+        for out, slot, oslot, n_hot, ohot in outs:
+            assert n_hot == ohot and np.array_equal(slot.cpu().numpy(), oslot)
+            assert np.array_equal(out.view(torch.uint8).cpu().numpy().reshape(-1, w.row_bytes), w.feat_bytes[ids])
+        # the last placement's cache really is what the gather reads
+        orig = w.feat.clone()
+        w.feat += 1.0
+        with torch.cuda.stream(gs):
+            out, hit, miss = tier.tier_gather_features(w.ctx, ids_d, want_stats=True)
+        hot = outs[-1][2][ids] >= 0
+        assert hit == int(hot.sum()) and hit + miss == len(ids)
+        got = out.cpu()
+        idx = torch.from_numpy(ids.astype(np.int64)); hot_t = torch.from_numpy(hot)
+        assert torch.equal(got[hot_t], orig[idx[hot_t]]) and torch.equal(got[~hot_t], w.feat[idx[~hot_t]])
+    finally:
+        tier.tier_set_gather_stream(w.ctx, None)
+        w.close()
+
+
 def test_hot_rows_come_from_the_cache():
     """After placement, change the host copy of the hot rows: the gather must still
     return the original bytes for them (read from HBM) and the new bytes for cold rows."""
