@@ -375,6 +375,7 @@ def score_comparison(tier, synth, torch, ctx, wl, counts, train, budget, groups,
     and the time each score takes.  Hits are counted from the slot map of each placement."""
     def timed(f):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()                    # e.g. a cache fill still running on the gather stream
         a.record(); r = f(); b.record(); torch.cuda.synchronize()
         return r, round(a.elapsed_time(b), 3)
 
@@ -455,6 +456,7 @@ def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget,
     gathered epoch on the reordered data (its draws differ: they are keyed by node id)."""
     def timed(f):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()                    # e.g. a cache fill still running on the gather stream
         a.record(); r = f(); b.record(); torch.cuda.synchronize()
         return r, a.elapsed_time(b)
 

@@ -117,6 +117,7 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     (void)hipFree(ctx->local_idx);
     (void)hipFree(ctx->bitmap);
+    (void)hipFree(ctx->prev);
     (void)hipFree(ctx->summary);
     (void)hipFree(ctx->slot);
     (void)hipFree(ctx->cache);
@@ -168,12 +169,15 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     c->n_words = (n + 31) / 32;
     c->n_sum = (c->n_words + 31) / 32;
     // as many mini-batch slots as fit in 8 GiB of per-node scratch (16 slots up to 121 M nodes)
-    const int64_t per_slot = (n + c->n_words + c->n_sum + 1) * 4;
+    const int64_t per_slot = (n + c->n_words + c->n_sum + 1) * 4;     // + n_words for `prev` on graphs of up to 32 M nodes
     int64_t slots = (8LL << 30) / per_slot;
     c->n_slots = (int)(slots < 1 ? 1 : (slots > TIER_MAX_BATCHES ? TIER_MAX_BATCHES : slots));
     const size_t S = (size_t)c->n_slots;
     TIER_HIP(c, hipMalloc(&c->local_idx, S * (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->bitmap, S * (size_t)(c->n_words > 0 ? c->n_words : 1) * sizeof(uint32_t)));
+    const bool frontier_bits = c->n_words <= (1 << 20);      // as sampler.hip's two_level(): `prev` serves the smaller graphs
+    const int64_t prev_words = frontier_bits && c->n_words > 0 ? c->n_words * (int64_t)S : 1;
+    TIER_HIP(c, hipMalloc(&c->prev, (size_t)prev_words * sizeof(uint32_t)));
     TIER_HIP(c, hipMalloc(&c->summary, S * (size_t)(c->n_sum > 0 ? c->n_sum : 1) * sizeof(uint32_t)));
     TIER_HIP(c, hipMalloc(&c->slot, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->meta, S * META_WORDS * sizeof(int64_t)));
@@ -186,6 +190,7 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     k_fill_i32<<<grid_for(n * (int64_t)S, 256, 8192), 256, 0, c->stream>>>(c->local_idx, n * (int64_t)S, -1);
     k_fill_i32<<<grid_for(c->n_words * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->bitmap,
                                                                                   c->n_words * (int64_t)S, 0);
+    k_fill_i32<<<grid_for(prev_words, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->prev, prev_words, 0);
     k_fill_i32<<<grid_for(c->n_sum * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->summary,
                                                                                 c->n_sum * (int64_t)S, 0);
     k_fill_i32<<<1, 64, 0, c->stream>>>((int32_t *)c->gmeta, GMETA_WORDS * 2, 0);

@@ -15,23 +15,42 @@
 //                   draw i, the Floyd collision rule is resolved with in-group
 //                   shuffles; every neighbour not yet in the frontier sets its
 //                   bit in a bitmap over all nodes
-//   k_bm_partial    popcounts of the bitmap, visiting only its non-zero words: a
-//                   summary bitmap holds one bit per bitmap word (set by whoever
-//                   sets the first bit of that word), so the cost follows the
-//                   mini-batch, not the graph
+//   k_bm_partial    popcounts of the nodes reached at this hop
 //   k_bm_emit       bitmap -> ascending list of new nodes appended to the
 //                   frontier (dedup and sort in one pass), their frontier index
-//                   recorded in local_idx[], both bitmaps cleared
+//                   recorded in local_idx[] where it is needed
 //   k_relabel       once per mini-batch, all hops: col[e] = frontier index of
 //                   the sampled neighbour (col[] held its node id until then)
+//   k_finish        takes the mini-batch's nodes out of local_idx[] and the bitmaps
+//
+// Two layouts of that bookkeeping, by graph size:
+//
+// Up to 32 M nodes (bitmap of up to 4 MB per slot: walking it whole is cheap and it
+// stays in the L2 caches): two bitmaps per slot, `seen` = frontier + nodes reached at
+// this hop and `prev` = the frontier before the hop.  The hop kernel asks `prev`
+// whether a neighbour is in the frontier - one bit per node instead of a 4-byte
+// local_idx[] entry, whose 128-byte line came from HBM or the last-level cache for
+// most sampled edges - and sets the bit in `seen` otherwise; `prev` does not change
+// during the hop, so the words of the hubs, which most edges lead to, stay in each
+// compute unit's own cache.  New nodes = seen ^ prev, then prev = seen.  (Asking
+// `seen` itself, to skip the atomic for neighbours already marked at this hop, was
+// slower either way: cached reads see stale zeros and the hubs' words drown in
+// atomics, device-scope reads pile up on the L2 channels of those same words.)
+//
+// Above 32 M nodes: membership from local_idx[] (a bitmap of that size is no more
+// cache-friendly), the bitmap holds this hop's new nodes only and a summary bitmap
+// holds one bit per bitmap word (set by whoever sets the first bit of that word), so
+// that the kernels reading the bitmap visit only its non-zero words and their cost
+// follows the mini-batch, not the graph.
 //
 // tier_presample runs the same chain without materialising blocks (no offsets,
-// no edge ids, no relabel) and gives every node of the final frontier one atomic
-// increment: those reached at the last hop straight from the bitmap (k_bm_count,
-// never listed), the earlier ones when they leave local_idx[] (k_finish).  Within a mini-batch the frontier nodes are distinct, so
-// only mini-batches of different slots can meet on one counter; global atomics
-// handle that (the counters are spread over all nodes, there is no hot spot an
-// LDS staging could absorb).
+// no edge ids, no relabel; on the smaller graphs no local_idx[] either) and gives
+// every node of the final frontier one atomic increment: those reached at the last
+// hop straight from the bitmap (k_bm_count, never listed), the earlier ones from the
+// list (k_finish).  Within a mini-batch the frontier nodes are distinct, so only
+// mini-batches of different slots can meet on one counter; global atomics handle that
+// (the counters are spread over all nodes, there is no hot spot an LDS staging could
+// absorb).
 #include "rng.h"
 #include "tier_internal.h"
 
@@ -52,8 +71,12 @@ struct wide_t {
     int32_t *nodes;              // slot s: nodes + s * nodes_stride
     int64_t nodes_stride;
     int32_t *local_idx;          // [slot][n_nodes]
-    uint32_t *bitmap;            // [slot][n_words]
+    uint32_t *bitmap;            // [slot][n_words]  "seen": frontier + reached at this hop
+    uint32_t *prev;              // [slot][n_words]  the frontier before this hop
     uint32_t *summary;           // [slot][n_sum]
+    int32_t frontier_bits;       // != 0 (graphs of up to 32 M nodes): the bitmaps hold the frontier too, see k_hop_sample
+    int32_t index_nodes;         // != 0: local_idx[] records every frontier node's index (blocks; membership on large graphs)
+    int32_t clear_by_list;       // != 0: k_finish clears the bitmaps node by node (k_bm_count_flat clears them whole)
     int64_t *meta;               // [slot][META_WORDS]; totals and the error flag live in slot 0
     int32_t *partial_hop;        // [slot][TIER_SCAN_BLOCKS]
     int32_t *partial_bm;         // [slot][TIER_SCAN_BLOCKS]
@@ -78,6 +101,7 @@ struct slot_view {
     int32_t *nodes;
     int32_t *local_idx;
     uint32_t *bitmap;
+    uint32_t *prev;
     uint32_t *summary;
     int64_t *meta;
     int32_t *partial_hop;
@@ -91,6 +115,7 @@ __device__ inline slot_view view_of(const wide_t &w)
     v.nodes = w.nodes + s * w.nodes_stride;
     v.local_idx = w.local_idx + s * w.n_nodes;
     v.bitmap = w.bitmap + s * w.n_words;
+    v.prev = w.prev + s * w.n_words;
     v.summary = w.summary + s * w.n_sum;
     v.meta = w.meta + s * META_WORDS;
     v.partial_hop = w.partial_hop + s * TIER_SCAN_BLOCKS;
@@ -181,7 +206,11 @@ __global__ void k_init_seeds(wide_t w)
             u = 0;                                   // keep every later index in range
         }
         v.nodes[i] = u;
-        v.local_idx[u] = (int32_t)i;
+        if (w.index_nodes) v.local_idx[u] = (int32_t)i;
+        if (w.frontier_bits) {
+            atomicOr(&v.bitmap[(uint32_t)u >> 5], 1u << (u & 31));
+            atomicOr(&v.prev[(uint32_t)u >> 5], 1u << (u & 31));
+        }
     }
 }
 
@@ -242,8 +271,8 @@ __global__ __launch_bounds__(kBlock) void k_hop_rowptr(wide_t w, const OffT *__r
 template <int G, bool BLOCKS, bool TWO_LEVEL, typename OffT>
 __device__ inline void sample_one(int lane, int32_t v, OffT beg, int32_t d, int k, int layer, uint32_t key0,
                                   uint32_t key1, const int32_t *__restrict__ indices,
-                                  const int32_t *__restrict__ local_idx, uint32_t *__restrict__ bitmap,
-                                  uint32_t *__restrict__ summary, int64_t *__restrict__ eid,
+                                  const int32_t *__restrict__ local_idx, uint32_t *__restrict__ seen,
+                                  const uint32_t *__restrict__ prev, uint32_t *__restrict__ summary, int64_t *__restrict__ eid,
                                   int32_t *__restrict__ col, int32_t rp)
 {
     const bool draw = d > k;
@@ -271,14 +300,15 @@ __device__ inline void sample_one(int lane, int32_t v, OffT beg, int32_t d, int 
             eid[rp + lane] = (int64_t)e;
             col[rp + lane] = u;                     // node id for now; k_relabel turns it into an index
         }
-        if (local_idx[u] < 0) {
-            const uint32_t word = (uint32_t)u >> 5;
-            if (TWO_LEVEL) {
-                if (atomicOr(&bitmap[word], 1u << (u & 31)) == 0u)  // first bit of this word
-                    atomicOr(&summary[word >> 5], 1u << (word & 31));
-            } else {
-                atomicOr(&bitmap[word], 1u << (u & 31));
-            }
+        const uint32_t word = (uint32_t)u >> 5, bit = 1u << (u & 31);
+        if (TWO_LEVEL) {
+            // large graph: membership from local_idx[], `seen` holds this hop's new nodes only
+            if (local_idx[u] < 0 && atomicOr(&seen[word], bit) == 0u)       // first bit of this word
+                atomicOr(&summary[word >> 5], 1u << (word & 31));
+        } else {
+            // one bit per node: in the frontier already?  `prev` does not change during the hop, so
+            // the words of the hubs, which most edges lead to, stay in the compute unit's own cache
+            if (!(prev[word] & bit)) atomicOr(&seen[word], bit);
         }
     }
 }
@@ -308,7 +338,7 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, const OffT *__r
         int32_t rp = 0;
         if (BLOCKS) rp = row_ptr[i];
         else if (w.count_edges && lane == 0) edges += d < k ? d : k;
-        sample_one<G, BLOCKS, TWO_LEVEL, OffT>(lane, u, beg, d, k, layer, key0, key1, indices, v.local_idx, v.bitmap, v.summary,
+        sample_one<G, BLOCKS, TWO_LEVEL, OffT>(lane, u, beg, d, k, layer, key0, key1, indices, v.local_idx, v.bitmap, v.prev, v.summary,
                                     eid, col, rp);
     }
     if (!BLOCKS && w.count_edges) {
@@ -390,7 +420,7 @@ __global__ __launch_bounds__(kBlock) void k_bm_partial_flat(wide_t w)
     int64_t lo, hi;
     block_range(w.n_words, lo, hi);
     int sum = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) sum += __popc(v.bitmap[i]);
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) sum += __popc(v.bitmap[i] ^ v.prev[i]);
     int tot = block_sum(sum, s_wave);
     if (threadIdx.x == 0) v.partial_bm[blockIdx.x] = tot;
 }
@@ -407,18 +437,19 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int layer)
     if (blockIdx.x == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all;
     for (int64_t tile = lo; tile < hi; tile += kBlock) {
         const int64_t i = tile + threadIdx.x;
-        uint32_t bits = i < hi ? v.bitmap[i] : 0u;
+        const uint32_t cur = i < hi ? v.bitmap[i] : 0u;
+        uint32_t bits = i < hi ? cur ^ v.prev[i] : 0u;
         int tot;
         int64_t pos = base + carry + block_excl_scan(__popc(bits), tot, s_wave);
         carry += tot;
         if (bits) {
-            v.bitmap[i] = 0u;
+            v.prev[i] = cur;
             while (bits) {
                 int b = __ffs(bits) - 1;
                 bits &= bits - 1;
                 int32_t u = (int32_t)(i * 32 + b);
                 v.nodes[pos] = u;
-                v.local_idx[u] = (int32_t)pos;
+                if (w.index_nodes) v.local_idx[u] = (int32_t)pos;
                 ++pos;
             }
         }
@@ -435,9 +466,11 @@ __global__ __launch_bounds__(kBlock) void k_bm_count_flat(wide_t w, uint32_t *__
     block_range(w.n_words, lo, hi);
     int sum = 0;
     for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
-        uint32_t bits = v.bitmap[i];
-        if (bits) {
-            v.bitmap[i] = 0u;
+        const uint32_t cur = v.bitmap[i];
+        if (cur) {
+            uint32_t bits = cur ^ v.prev[i];
+            v.bitmap[i] = 0u;                   // the mini-batch ends here: both bitmaps back to zero
+            v.prev[i] = 0u;
             sum += __popc(bits);
             while (bits) {
                 int b = __ffs(bits) - 1;
@@ -492,9 +525,9 @@ __global__ void k_relabel(wide_t w, relabel_t r)
     }
 }
 
-// End of a mini-batch: take the nodes of frontier `layer` out of local_idx[]; with COUNT,
-// one access per node (the rows a gather for this mini-batch reads).  Access counting
-// passes the frontier before the last hop: k_bm_count has dealt with the rest.
+// End of a mini-batch: take the nodes of frontier `layer` (the last one that was listed) out
+// of local_idx[] and of the bitmaps; with COUNT, one access per node (the rows a gather for
+// this mini-batch reads) - k_bm_count has dealt with the nodes of the last hop.
 template <bool COUNT>
 __global__ void k_finish(wide_t w, int layer, uint32_t *__restrict__ counts)
 {
@@ -504,7 +537,11 @@ __global__ void k_finish(wide_t w, int layer, uint32_t *__restrict__ counts)
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t i = t; i < n; i += stride) {
         int32_t u = v.nodes[i];
-        v.local_idx[u] = -1;
+        if (w.index_nodes) v.local_idx[u] = -1;
+        if (w.clear_by_list) {                  // several nodes may share a word: all store the same zero
+            v.bitmap[(uint32_t)u >> 5] = 0u;
+            v.prev[(uint32_t)u >> 5] = 0u;
+        }
         if (COUNT) atomicAdd(&counts[u], 1u);
     }
     if (COUNT && t == 0 && n)
@@ -633,6 +670,7 @@ wide_t make_wide(tier_ctx *c, const int32_t *seeds, int64_t n_seeds_total, int32
     w.nodes_stride = nodes_stride;
     w.local_idx = c->local_idx;
     w.bitmap = c->bitmap;
+    w.prev = c->prev;
     w.summary = c->summary;
     w.n_sum = c->n_sum;
     w.meta = c->meta;
@@ -693,6 +731,9 @@ int tier_sample_minibatches(tier_ctx *ctx, const int32_t *seeds, int64_t n_seeds
                                  out->edge_stride[l]};
     }
     wide_t w = make_wide(ctx, seeds, n_seeds_total, batch_size, n_batches, out->nodes, out->nodes_stride);
+    w.frontier_bits = two_level(ctx) ? 0 : 1;
+    w.index_nodes = 1;
+    w.clear_by_list = w.frontier_bits;
     for (int s = 0; s < n_batches; ++s) {
         w.key0[s] = (uint32_t)batch_seeds[s];
         w.key1[s] = (uint32_t)(batch_seeds[s] >> 32);
@@ -756,6 +797,9 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
             const int slots = (int)(n_batches - b < ctx->n_slots ? n_batches - b : ctx->n_slots);
             const int64_t lo = b * batch_size;
             wide_t w = make_wide(ctx, train_ids + lo, n_train - lo, batch_size, slots, ctx->ps_nodes, stride);
+            w.frontier_bits = two_level(ctx) ? 0 : 1;
+            w.index_nodes = w.frontier_bits ? 0 : 1;       // small graphs: nothing is relabelled, local_idx[] stays untouched
+            w.clear_by_list = 0;                           // the flat last-hop kernel clears the bitmaps whole
             w.count_edges = total_edges != nullptr;
             for (int s = 0; s < slots; ++s) {
                 const uint64_t bs = tier_batch_seed(seed, (uint32_t)e, (uint32_t)(b + s));

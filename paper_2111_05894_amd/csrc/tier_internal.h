@@ -66,7 +66,8 @@ struct tier_ctx {
     // per-node scratch, one copy per slot (mini-batch sampled side by side)
     int n_slots;
     int32_t *local_idx;      // [n_slots][n_nodes]; -1 = not in the slot's current frontier
-    uint32_t *bitmap;        // [n_slots][n_words]; all zero between hops
+    uint32_t *bitmap;        // [n_slots][n_words]; frontier + nodes reached at the current hop; zero between mini-batches
+    uint32_t *prev;          // [n_slots][n_words]; the frontier before the current hop; zero between mini-batches
     int64_t n_words;         // ceil(n_nodes / 32)
     uint32_t *summary;       // [n_slots][n_sum]; bit j of word i set <=> bitmap word 32 i + j is non-zero
     int64_t n_sum;           // ceil(n_words / 32)
