@@ -286,6 +286,11 @@ def main():
                                  round(nrows * R / (ms * 1e-3) / 1e9 / LINK_PEAK_GBPS, 4),
                                  "avg_launch_ms": round(ms / nl, 4), "launches": nl}
         roofline["streams"] = streams
+        # the same blend with the rates the two streams reach on their own instead of the published peaks
+        t_row = h * alg_bytes_row / (streams["all_hit"]["hbm_GBps"] * 1e9) + (1 - h) * R / (streams["all_miss"]["host_link_GBps"] * 1e9)
+        roofline["frac_of_measured_streams"] = round(t_row * rows / (gather_ms * 1e-3), 4) if gather_ms else None
+        roofline["measured_streams_model"] = ("time per row = h (2R+8) / all-hit rate + (1-h) R / all-miss rate, over the "
+                                              "measured time per row: above 1 when the hits hide under the misses")
         untiered_ms = rows * R / (streams["all_miss"]["host_link_GBps"] * 1e9) * 1e3
         roofline["untiered_epoch_gather_ms"] = round(untiered_ms, 2)
         roofline["gather_speedup_vs_untiered"] = round(untiered_ms / gather_ms, 2) if gather_ms else None
