@@ -39,7 +39,7 @@ struct id_lists_t {
     const int64_t *n_dev;                // non-null: the length of list 0 is read from the device
 };
 
-// An id outside the graph is nobody's cold row: the hot launch writes its row of zeros.
+// An id outside the graph is nobody's cold row: the blocks that copy hot rows write its row of zeros.
 template <int MODE>
 __device__ inline int is_cold(int32_t id, const int32_t *__restrict__ slot, int64_t n_nodes, int64_t n_hot)
 {

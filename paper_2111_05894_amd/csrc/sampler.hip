@@ -45,12 +45,14 @@
 //
 // tier_presample runs the same chain without materialising blocks (no offsets,
 // no edge ids, no relabel; on the smaller graphs no local_idx[] either) and gives
-// every node of the final frontier one atomic increment: those reached at the last
-// hop straight from the bitmap (k_bm_count, never listed), the earlier ones from the
-// list (k_finish).  Within a mini-batch the frontier nodes are distinct, so only
-// mini-batches of different slots can meet on one counter; global atomics handle that
-// (the counters are spread over all nodes, there is no hot spot an LDS staging could
-// absorb).
+// every node of the final frontier one access.  On the smaller graphs the slots'
+// `seen` bitmaps hold exactly those frontiers when the chain ends, and one pass adds
+// them up column by column (k_count_columns: no atomics, the nodes of the last hop
+// are never listed).  On the larger graphs the nodes reached at the last hop take an
+// atomic increment straight from the bitmap (k_bm_count, never listed either) and the
+// earlier ones from the list (k_finish): within a mini-batch the frontier nodes are
+// distinct, so only mini-batches of different slots can meet on one counter, spread
+// over all nodes - no hot spot an LDS staging could absorb.
 #include "rng.h"
 #include "tier_internal.h"
 
@@ -76,7 +78,7 @@ struct wide_t {
     uint32_t *summary;           // [slot][n_sum]
     int32_t frontier_bits;       // != 0 (graphs of up to 32 M nodes): the bitmaps hold the frontier too, see k_hop_sample
     int32_t index_nodes;         // != 0: local_idx[] records every frontier node's index (blocks; membership on large graphs)
-    int32_t clear_by_list;       // != 0: k_finish clears the bitmaps node by node (k_bm_count_flat clears them whole)
+    int32_t clear_by_list;       // != 0: k_finish clears the bitmaps node by node (k_count_columns clears them whole)
     int64_t *meta;               // [slot][META_WORDS]; totals and the error flag live in slot 0
     int32_t *partial_hop;        // [slot][TIER_SCAN_BLOCKS]
     int32_t *partial_bm;         // [slot][TIER_SCAN_BLOCKS]
@@ -456,34 +458,9 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int layer)
     }
 }
 
-// Access counting, last hop: the nodes reached there are neither listed nor indexed (no
-// further hop, no relabelling), each takes its one access straight from the bitmap.
-__global__ __launch_bounds__(kBlock) void k_bm_count_flat(wide_t w, uint32_t *__restrict__ counts)
-{
-    __shared__ int s_wave[kBlock / 64];
-    const slot_view v = view_of(w);
-    int64_t lo, hi;
-    block_range(w.n_words, lo, hi);
-    int sum = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
-        const uint32_t cur = v.bitmap[i];
-        if (cur) {
-            uint32_t bits = cur ^ v.prev[i];
-            v.bitmap[i] = 0u;                   // the mini-batch ends here: both bitmaps back to zero
-            v.prev[i] = 0u;
-            sum += __popc(bits);
-            while (bits) {
-                int b = __ffs(bits) - 1;
-                bits &= bits - 1;
-                atomicAdd(&counts[i * 32 + b], 1u);
-            }
-        }
-    }
-    const int tot = block_sum(sum, s_wave);
-    if (threadIdx.x == 0 && tot)
-        atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)tot);
-}
-
+// Access counting on the larger graphs, last hop: the nodes reached there are neither listed
+// nor indexed (no further hop, no relabelling), each takes its one access straight from the
+// bitmap; k_finish counts the listed ones.
 __global__ __launch_bounds__(kBlock) void k_bm_count(wide_t w, uint32_t *__restrict__ counts)
 {
     __shared__ int s_wave[kBlock / 64];
@@ -509,6 +486,59 @@ __global__ __launch_bounds__(kBlock) void k_bm_count(wide_t w, uint32_t *__restr
         }
     }
     const int tot = block_sum(sum, s_wave);
+    if (threadIdx.x == 0 && tot)
+        atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)tot);
+}
+
+// Counting mode on graphs of up to 32 M nodes, end of a chain: `seen` of a slot now holds the
+// whole final frontier of its mini-batch, so counts[v] grows by the number of slots whose bit
+// v is set.  One thread owns one bitmap word position = 32 counters across all slots: it adds
+// the slots' words bit-sliced (five planes hold sums up to 31; a flush every 31 slots), updates
+// its counters without atomics (no other thread of this kernel touches them, and kernels on
+// the stream run one after the other) and clears both bitmaps.
+__global__ __launch_bounds__(kBlock) void k_count_columns(wide_t w, uint32_t *__restrict__ counts)
+{
+    __shared__ int s_wave[kBlock / 64];
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    int rows = 0;
+    if (i < w.n_words) {
+        uint32_t plane[5] = {0u, 0u, 0u, 0u, 0u};
+        int held = 0;
+        auto flush = [&]() {
+            if (plane[0] | plane[1] | plane[2] | plane[3] | plane[4]) {
+                uint32_t *c = counts + i * 32;
+                const int64_t left = w.n_nodes - i * 32;         // the last word may be ragged
+#pragma unroll
+                for (int b = 0; b < 32; ++b) {
+                    const uint32_t add = ((plane[0] >> b) & 1u) | (((plane[1] >> b) & 1u) << 1) |
+                                         (((plane[2] >> b) & 1u) << 2) | (((plane[3] >> b) & 1u) << 3) |
+                                         (((plane[4] >> b) & 1u) << 4);
+                    if (add && b < left) c[b] += add;
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < 5; ++p) plane[p] = 0u;
+            held = 0;
+        };
+        for (int s = 0; s < w.n_slots; ++s) {
+            uint32_t *seen = w.bitmap + (int64_t)s * w.n_words + i;
+            uint32_t carry = *seen;
+            if (carry) {
+                *seen = 0u;
+                w.prev[(int64_t)s * w.n_words + i] = 0u;
+                rows += __popc(carry);
+#pragma unroll
+                for (int p = 0; p < 5; ++p) {                     // ripple-carry add of one bit per column
+                    const uint32_t t = plane[p] & carry;
+                    plane[p] ^= carry;
+                    carry = t;
+                }
+                if (++held == 31) flush();
+            }
+        }
+        flush();
+    }
+    const int tot = block_sum(rows, s_wave);
     if (threadIdx.x == 0 && tot)
         atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)tot);
 }
@@ -627,8 +657,9 @@ int enqueue_wide(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_lay
         if (c->indptr_i64) launch_hop<int64_t>(c, w, cap_nodes[l], l, fanouts[l], o);
         else launch_hop<int32_t>(c, w, cap_nodes[l], l, fanouts[l], o);
         if (o.counts && l == n_layers - 1) {
+            // the last hop's nodes are never listed: counted from the bitmaps (see k_count_columns / k_bm_count)
             if (tl) k_bm_count<<<bm_grid, kBlock, 0, c->stream>>>(w, o.counts);
-            else k_bm_count_flat<<<bm_grid, kBlock, 0, c->stream>>>(w, o.counts);
+            else k_count_columns<<<clamp_grid(c->n_words, kBlock, 1 << 22), kBlock, 0, c->stream>>>(w, o.counts);
         } else if (tl) {
             k_bm_partial<<<bm_grid, kBlock, 0, c->stream>>>(w);
             k_bm_emit<<<bm_grid, kBlock, 0, c->stream>>>(w, l);
@@ -650,8 +681,8 @@ int enqueue_wide(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_lay
     }
     const int last = o.counts ? n_layers - 1 : n_layers;       // last frontier that was listed
     const dim3 fgrid(clamp_grid(cap_nodes[last], kBlock, 4096), slots);
-    if (o.counts) k_finish<true><<<fgrid, kBlock, 0, c->stream>>>(w, last, o.counts);
-    else k_finish<false><<<fgrid, kBlock, 0, c->stream>>>(w, last, nullptr);
+    if (o.counts && tl) k_finish<true><<<fgrid, kBlock, 0, c->stream>>>(w, last, o.counts);
+    else if (!o.counts) k_finish<false><<<fgrid, kBlock, 0, c->stream>>>(w, last, nullptr);
     TIER_HIP(c, hipGetLastError());
     return TIER_OK;
 }
@@ -799,7 +830,7 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
             wide_t w = make_wide(ctx, train_ids + lo, n_train - lo, batch_size, slots, ctx->ps_nodes, stride);
             w.frontier_bits = two_level(ctx) ? 0 : 1;
             w.index_nodes = w.frontier_bits ? 0 : 1;       // small graphs: nothing is relabelled, local_idx[] stays untouched
-            w.clear_by_list = 0;                           // the flat last-hop kernel clears the bitmaps whole
+            w.clear_by_list = 0;                           // k_count_columns clears the bitmaps whole
             w.count_edges = total_edges != nullptr;
             for (int s = 0; s < slots; ++s) {
                 const uint64_t bs = tier_batch_seed(seed, (uint32_t)e, (uint32_t)(b + s));
