@@ -50,6 +50,8 @@ def main():
                     help="also sweep the HBM budget and the sampling depth (analogues of the paper's Fig. 5 and 6)")
     ap.add_argument("--link-blocks", type=int, default=64,
                     help="blocks of the cold-row launch of the split gather (0: one uniform launch per call)")
+    ap.add_argument("--no-shared-misses", action="store_true",
+                    help="read every requested cold row over the host link, also those a call requests more than once")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink nodes, edges and budget alike")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for profiler byte counters)")
@@ -109,6 +111,8 @@ def main():
     gs = torch.cuda.Stream()
     tier.tier_set_gather_stream(ctx, gs)
     tier.tier_set_gather_split(ctx, args.link_blocks, SPLIT_MIN_ROWS)
+    shared_on = not args.no_shared_misses
+    tier.tier_set_gather_dedup(ctx, shared_on)
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
     def sample_group(g, into=None):
@@ -202,22 +206,25 @@ def main():
     # the same epoch with the uniform gather launch (every block copies hot and cold rows)
     uniform = None
     if args.link_blocks > 0:
+        tier.tier_set_gather_dedup(ctx, False)
         tier.tier_set_gather_split(ctx, 0, 0)
         urec = {"sample_ms": [], "gather_ms": [], "epoch_wall_ms": []}
         epoch(None)
         for _ in range(max(args.steps, 1)):
             epoch(urec)
         tier.tier_set_gather_split(ctx, args.link_blocks, SPLIT_MIN_ROWS)
+        tier.tier_set_gather_dedup(ctx, shared_on)
         uniform = {"epoch_wall_ms": round(sum(urec["epoch_wall_ms"]) / len(urec["epoch_wall_ms"]), 3),
                    "gather_ms": round(sum(urec["gather_ms"]) / len(urec["gather_ms"]), 3),
                    "sample_ms": round(sum(urec["sample_ms"]) / len(urec["sample_ms"]), 3)}
 
     # hit / miss rows of the measured epoch (outside the timed region: asking for them waits per batch)
-    hit_rows = 0
+    hit_rows = link_rows = 0
     for g in groups:
         blk = sample_group(g)
         _, _, h, m = tier.tier_gather_minibatches(ctx, blk, len(g), out_buf[0], want_stats=True)
         hit_rows += h
+        link_rows += ctx.last_link_rows          # the misses, or with shared misses the distinct ones per call
     # the sampler on its own (in the timed region it shares the GPU with the gathers)
     torch.cuda.synchronize()
     a, b_ = ev(), ev()
@@ -240,8 +247,11 @@ def main():
     avg_launch_ms = gather_ms / launches if launches else 0.0
     alg_per_launch = alg_bytes_row * rows / launches if launches else 0.0
     achieved = alg_per_launch / (avg_launch_ms * 1e-3) / 1e9 if avg_launch_ms else 0.0
-    hbm_b = (1 + h) * R + 8            # per row through HBM
-    link_b = (1 - h) * R               # per row over the host link
+    # d = share of the cold requests that have to cross the link: all of them, or with shared misses
+    # the distinct ones of each call (the repeats are copies inside HBM)
+    d = link_rows / (rows - hit_rows) if rows > hit_rows else 1.0
+    hbm_b = (1 + h + (1 - h) * (1 - d)) * R + 8     # per row through HBM
+    link_b = (1 - h) * d * R                        # per row over the host link
     peak_time_additive = alg_bytes_row / (hbm_b / HBM_PEAK_GBPS + link_b / LINK_PEAK_GBPS)
     peak_overlap = alg_bytes_row / max(hbm_b / HBM_PEAK_GBPS, link_b / LINK_PEAK_GBPS)   # both streams fully overlapped
     peak_arithmetic = h * HBM_PEAK_GBPS + (1 - h) * LINK_PEAK_GBPS
@@ -250,17 +260,19 @@ def main():
         "peak": round(peak_time_additive, 2), "unit": "GB/s",
         "frac": round(achieved / peak_time_additive, 4) if peak_time_additive else None,
         "traffic": measured_traffic(wl.name) if scale == 1.0 and args.budget is None else None,
-        "peak_model": "time-additive blend: (2R+8) / (((1+h)R+8)/HBM + (1-h)R/link), HBM 8000 GB/s, host link 64 GB/s",
+        "peak_model": "time-additive blend: (2R+8) / (hbm_bytes/HBM + link_bytes/link) per row, link_bytes = (1-h) d R, "
+                      "hbm_bytes = (1 + h + (1-h)(1-d)) R + 8, d = share of the cold requests that must cross the link "
+                      "(1, or with shared misses the distinct cold rows of each call); HBM 8000 GB/s, host link 64 GB/s",
         "overlap_bound_peak": round(peak_overlap, 2),
         "frac_vs_overlap_bound": round(achieved / peak_overlap, 4) if peak_overlap else None,
-        "overlap_bound_model": "(2R+8) / max(((1+h)R+8)/HBM, (1-h)R/link): the strict ceiling when HBM and link "
+        "overlap_bound_model": "(2R+8) / max(hbm_bytes/HBM, link_bytes/link): the strict ceiling when HBM and link "
                                "transfers overlap perfectly; the time-additive peak above adds the two times and "
                                "can be exceeded by a kernel that overlaps them",
-        "hit_fraction": round(h, 4),
+        "hit_fraction": round(h, 4), "cold_requests_crossing_the_link": round(d, 4),
         "avg_launch_ms": round(avg_launch_ms, 4), "launches_per_step": launches,
         "alg_bytes_per_launch": round(alg_per_launch),
         "feature_read_GBps": round(gathered_bytes / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
-        "host_link_GBps": round((rows - hit_rows) * R / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
+        "host_link_GBps": round(link_rows * R / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
         "arithmetic_blend_peak": round(peak_arithmetic, 1),
         "arithmetic_blend_frac": round(gathered_bytes / (gather_ms * 1e-3) / 1e9 / peak_arithmetic, 4) if gather_ms else None,
     }
@@ -269,6 +281,7 @@ def main():
     streams = None
     if not args.no_streams:
         streams = {}
+        tier.tier_set_gather_dedup(ctx, False)         # every requested row really crosses the link here
         for name, bud in (("all_hit", n * R), ("all_miss", 0)):
             tier.tier_place(ctx, counts, bud, want_slot_map=False)
             ms = 0.0; nrows = 0; nl = 0
@@ -285,11 +298,13 @@ def main():
                 streams[name] = {"host_link_GBps": round(nrows * R / (ms * 1e-3) / 1e9, 2), "frac_of_link_peak":
                                  round(nrows * R / (ms * 1e-3) / 1e9 / LINK_PEAK_GBPS, 4),
                                  "avg_launch_ms": round(ms / nl, 4), "launches": nl}
+        tier.tier_set_gather_dedup(ctx, shared_on)
         roofline["streams"] = streams
         # the same blend with the rates the two streams reach on their own instead of the published peaks
-        t_row = h * alg_bytes_row / (streams["all_hit"]["hbm_GBps"] * 1e9) + (1 - h) * R / (streams["all_miss"]["host_link_GBps"] * 1e9)
+        t_row = ((h + (1 - h) * (1 - d)) * alg_bytes_row / (streams["all_hit"]["hbm_GBps"] * 1e9)
+                 + (1 - h) * d * R / (streams["all_miss"]["host_link_GBps"] * 1e9))
         roofline["frac_of_measured_streams"] = round(t_row * rows / (gather_ms * 1e-3), 4) if gather_ms else None
-        roofline["measured_streams_model"] = ("time per row = h (2R+8) / all-hit rate + (1-h) R / all-miss rate, over the "
+        roofline["measured_streams_model"] = ("time per row = (h + (1-h)(1-d)) (2R+8) / all-hit rate + (1-h) d R / all-miss rate, over the "
                                               "measured time per row: above 1 when the hits hide under the misses")
         untiered_ms = rows * R / (streams["all_miss"]["host_link_GBps"] * 1e9) * 1e3
         roofline["untiered_epoch_gather_ms"] = round(untiered_ms, 2)
@@ -319,7 +334,7 @@ def main():
                     links = link_rows
             shared[name] = {"gather_ms": round(ms, 3), "host_link_bytes": links * R,
                             "gathered_GBps": round(rows * R / (ms * 1e-3) / 1e9, 2) if ms else None}
-        tier.tier_set_gather_dedup(ctx, False)
+        tier.tier_set_gather_dedup(ctx, shared_on)
         shared["note"] = ("one pass over the measured epoch, gathers only; shared_misses reads every distinct cold row "
                           "of a call (16 mini-batches) over the host link once")
 
@@ -333,7 +348,7 @@ def main():
 
     reorder = None
     if not args.no_reorder:
-        reorder = reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, args.link_blocks)
+        reorder = reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, args.link_blocks, shared_on)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -351,8 +366,8 @@ def main():
         "sample_alone_ms": round(sample_alone_ms, 3),
         "gather_GBps": round(gathered_bytes / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
         "rows_per_epoch": rows, "edges_per_epoch": edges, "hit_fraction": round(h, 4),
-        "host_link_bytes_tiered": (rows - hit_rows) * R, "host_link_bytes_untiered": rows * R,
-        "host_link_reduction": round(h, 4),
+        "host_link_bytes_tiered": link_rows * R, "host_link_bytes_untiered": rows * R,
+        "host_link_reduction": round(1 - link_rows / rows, 4) if rows else None,
         "phase_note": "presample + place + epoch_wall = the step.  place = ordering, slot map (place_sort) and the cache "
                       "fill, which runs on the gather stream while the main stream already samples; epoch_wall counts from "
                       "the end of that fill to the end of the last gather.  sample and gather are per-stream busy times "
@@ -362,7 +377,7 @@ def main():
                      "place_sort": round(mean(rec["place_sort_ms"]), 3),
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3),
                      "epoch_wall": round(mean(rec["epoch_wall_ms"]), 3)},
-        "gather_launch": {"link_blocks": args.link_blocks, "min_rows": SPLIT_MIN_ROWS,
+        "gather_launch": {"link_blocks": args.link_blocks, "min_rows": SPLIT_MIN_ROWS, "shared_misses": shared_on,
                           "note": "split launch: the first link_blocks blocks copy the cold rows (host link), all others the "
                                   "hot rows (HBM); uniform_launch_epoch is the same epoch with every block copying both",
                           "uniform_launch_epoch": uniform},
@@ -455,7 +470,7 @@ def run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_
     return {"budget": budget, "depth": depth}
 
 
-def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, link_blocks):
+def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, link_blocks, shared_on):
     """The paper's own layout (Sec. 3.2, Alg. 2): graph and table renamed by rank, hot part =
     ids below the boundary, gather without a map.  Times the reordering and one sampled and
     gathered epoch on the reordered data (its draws differ: they are keyed by node id)."""
@@ -480,6 +495,7 @@ def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget,
         train2 = tier.tier_relabel_ids(ctx, rank, train)
         ctx2 = tier.tier_create(ip2, ix2, table2)
         tier.tier_set_gather_split(ctx2, link_blocks, SPLIT_MIN_ROWS)
+        tier.tier_set_gather_dedup(ctx2, shared_on)
         n_hot, res["place_boundary_ms"] = timed(lambda: tier.tier_place_boundary(ctx2, budget))
         bs = wl.batch_size; L = len(wl.fanouts)
         n_train = train2.numel(); n_batches = -(-n_train // bs)

@@ -278,17 +278,20 @@ int tier_gather_minibatches(tier_ctx *ctx, const int32_t *nodes, int64_t nodes_s
  * results as the uniform launch (link_blocks = 0, the default), in which every block waits
  * on host reads and the kernels of other streams wait for the whole launch: use it when
  * something else (sampling, training) should run beside the gather.  0 <= link_blocks <=
- * 65536, min_rows >= 0.  Ignored while tier_set_gather_dedup is on.  Waits for the gather
- * stream. */
+ * 65536, min_rows >= 0.  Waits for the gather stream. */
 int tier_set_gather_split(tier_ctx *ctx, int32_t link_blocks, int64_t min_rows);
 
-/* Shared misses.  With on != 0 every gather call first finds the distinct cold ids among
- * all its requests, reads each of those rows over the host link once into an HBM staging
- * area owned by the context (up to min(requests, n_nodes) rows, grown on demand; n_nodes
- * bits and 4 n_nodes bytes of scratch besides), and serves all requests from HBM.  Results
+/* Shared misses.  With on != 0 every gather call reads each distinct cold row among all
+ * its requests over the host link once: the cold workers of the split launch (which this
+ * option implies for every call with cold rows; link_blocks as set by
+ * tier_set_gather_split, else 64) claim a cold id in a table over all nodes before they
+ * fetch it, the requests that find it claimed are served by a second, short kernel that
+ * copies the row inside HBM from the output row of the request that fetched it.  Results
  * are the same; it pays when the mini-batches of one tier_gather_minibatches call overlap
- * in their cold rows and costs three small kernels otherwise.  Off by default.  Waits for
- * the gather stream. */
+ * in their cold rows and costs one atomic per cold request and that second kernel
+ * otherwise.  Scratch owned by the context: 8 n_nodes bytes for the claims (allocated
+ * here) and 16 bytes per request of the largest call.  Off by default.  Waits for the
+ * gather stream. */
 int tier_set_gather_dedup(tier_ctx *ctx, int on);
 
 /* Put the gathers of this context on a stream of their own (NULL = back to the stream of

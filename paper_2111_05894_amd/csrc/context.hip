@@ -122,11 +122,8 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipFree(ctx->slot);
     (void)hipFree(ctx->cache);
     (void)hipStreamSynchronize(ctx->gather_stream);
-    (void)hipFree(ctx->gbitmap);
-    (void)hipFree(ctx->stage_slot);
-    (void)hipFree(ctx->gpartial);
-    (void)hipFree(ctx->uniq_ids);
-    (void)hipFree(ctx->stage);
+    (void)hipFree(ctx->claim);
+    (void)hipFree(ctx->deferred);
     for (int i = 0; i < 2; ++i) {
         (void)hipFree(ctx->sort.keys[i]);
         (void)hipFree(ctx->sort.vals[i]);

@@ -6,13 +6,6 @@
 // so a row is read and written with full-width coalesced accesses; several rows
 // per group are in flight to cover the host link's latency.
 //
-// Shared misses (tier_set_gather_dedup): the mini-batches gathered by one call overlap
-// (on a low-skew 10 M-node graph two thirds of a call's cold rows are requested more
-// than once), so the call can first mark its cold ids in a bitmap over all nodes, turn
-// the bitmap into an ascending list of distinct cold ids (k_gbm_*), fetch those rows
-// over the host link once into an HBM staging area, and then serve every request from
-// HBM: cache rows for hits, staged rows for misses.
-//
 // Split gather (tier_set_gather_split): the host link is saturated by the requests of a
 // few dozen blocks.  A full grid that queues megabytes of host reads gains nothing on the
 // link, holds every compute unit's slots until the link has served them, and makes
@@ -22,6 +15,15 @@
 // launch (row 0 of the grid, dispatched first): they look through the requests, copy the
 // cold ones and stay until the link has delivered them, while all other blocks copy hot
 // rows only and drain at HBM speed, leaving the chip to whoever else has work.
+//
+// Shared misses (tier_set_gather_dedup): the mini-batches gathered by one call overlap
+// (on a low-skew 10 M-node graph two thirds of a call's cold rows are requested more
+// than once).  The cold workers then claim every cold id in a table over all nodes
+// before they fetch it: the first request of an id in the call wins and reads the row
+// over the host link, every later one only notes "my row = that request's row", and a
+// short second kernel copies those rows inside HBM (k_copy_deferred).  A claim is the
+// call's stamp and the winner's output row in one 64-bit word, so the table needs no
+// clearing between calls.
 #include "tier_internal.h"
 
 namespace {
@@ -29,6 +31,8 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kRowsInFlight = 4;        // measured best of 2 / 4 / 8 on MI355X
 constexpr int kLinkBlocks = 64;         // blocks of a launch that reads host rows only (best of 32 .. 512, full grid)
+constexpr int kClaimRowBits = 40;       // claim = stamp << 40 | output row of the winning request
+constexpr int kDeferBlock = 64;         // deferred copies are reserved 64 entries at a time
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // The id lists one launch serves (blockIdx.y picks one): a mini-batch each.
@@ -36,7 +40,14 @@ struct id_lists_t {
     const int32_t *ids[TIER_MAX_BATCHES];
     int64_t n[TIER_MAX_BATCHES];
     int64_t out_row[TIER_MAX_BATCHES];   // first output row of the list
-    const int64_t *n_dev;                // non-null: the length of list 0 is read from the device
+};
+
+// What the cold workers of a split launch need beyond the lists.
+struct cold_t {
+    int workers;                         // blocks of grid row 0 that copy cold rows
+    unsigned long long stamp;            // shared misses: this call's stamp, already shifted; 0 = off
+    unsigned long long *claim;           // [n_nodes]
+    int64_t *deferred;                   // pairs (output row, output row to copy from); first < 0: unused
 };
 
 // An id outside the graph is nobody's cold row: the blocks that copy hot rows write its row of zeros.
@@ -53,49 +64,105 @@ __device__ inline int is_cold(int32_t id, const int32_t *__restrict__ slot, int6
 // their units, and appends the unit's cold requests (one ballot) to a small queue of its
 // own in LDS.  Whenever the queue holds a full pass - kRowsInFlight rows for each group of
 // LPR lanes - the wave copies one, so the bytes it keeps in flight on the host link do not
-// depend on how many of the requests are cold.  Three stages run ahead of that: the
-// counter is read three units ahead, the ids two, the slot lookups one, so the copies
-// never wait for a lookup.  The last wave to run dry leaves both counters at zero for the
-// next launch on the stream.
-template <int LPR, int MODE>
+// depend on how many of the requests are cold.  Four stages run ahead of that, a unit
+// each: the counter, the ids, the slot lookups and (shared misses) the claims, so the
+// copies never wait for any of them.  The last wave to run dry leaves both counters at
+// zero for the next launch on the stream.
+template <int LPR, int MODE, bool DEDUP>
 __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, const int32_t *__restrict__ slot,
-                                      int64_t n_nodes, int64_t n_hot, int workers,
+                                      int64_t n_nodes, int64_t n_hot, const cold_t &cold,
                                       const uint4 *__restrict__ host, uint4 *__restrict__ out_base, int cpr,
-                                      int64_t *__restrict__ meta)
+                                      int64_t *__restrict__ meta, int count_rows)
 {
     constexpr int kGroupsPerWave = 64 / LPR;
     constexpr int kPerPass = kGroupsPerWave * kRowsInFlight;
     constexpr int kQueue = 128;                       // ring: at most kPerPass - 1 + 64 entries wait
     __shared__ int32_t s_src[kBlock / 64][kQueue];    // host row of a waiting cold request
     __shared__ int64_t s_dst[kBlock / 64][kQueue];    // its output row
-    if ((int)blockIdx.x >= workers) return;
+    if ((int)blockIdx.x >= cold.workers) return;
     const int lane64 = threadIdx.x & 63;
     const int g = lane64 / LPR, lane = lane64 % LPR;
     int32_t *q_src = s_src[threadIdx.x >> 6];
     int64_t *q_dst = s_dst[threadIdx.x >> 6];
-    const unsigned long long n_waves = (unsigned long long)workers * (kBlock / 64);
+    const unsigned long long n_waves = (unsigned long long)cold.workers * (kBlock / 64);
     unsigned long long *next = (unsigned long long *)&meta[META_COLD_NEXT];
     unsigned long long *done = (unsigned long long *)&meta[META_COLD_DONE];
     int64_t total = 0;
     for (int b = 0; b < n_lists; ++b) total += (lists.n[b] + 63) / 64;
 
+    struct unit_t {
+        int64_t q;        // number of the unit (wave-uniform)
+        int64_t row0;     // output row of its first request (wave-uniform)
+        int32_t id;       // this lane's request, -1 beyond the list or the call
+        int fetch;        // this lane's request is cold (after the claim stage: and is the one that reads the row)
+    };
     // the counter's value arrives in lane 0; it is broadcast only where it is needed, an
     // iteration later, so that the atomic's latency hides behind the work in between
     auto grab = [&]() -> unsigned long long { return lane64 == 0 ? atomicAdd(next, 1ull) : 0ull; };
     auto bcast = [&](unsigned long long raw) -> int64_t { return (int64_t)__shfl(raw, 0); };
-    // this lane's request of unit u (-1 beyond the list or the call) and the unit's first output row
-    auto load_unit = [&](int64_t u, int64_t &row0) -> int32_t {
-        row0 = 0;
-        if (u >= total) return -1;
+    auto load_ids = [&](unit_t &u) {
+        u.row0 = 0;
+        u.id = -1;
+        u.fetch = 0;
+        int64_t c = u.q;
+        if (c >= total) return;
         int b = 0;
-        for (;; ++b) {                              // u < total: ends inside the lists
+        for (;; ++b) {                              // c < total: ends inside the lists
             const int64_t nu = (lists.n[b] + 63) / 64;
-            if (u < nu) break;
-            u -= nu;
+            if (c < nu) break;
+            c -= nu;
         }
-        row0 = lists.out_row[b] + u * 64;
-        const int64_t i = u * 64 + lane64;
-        return i < lists.n[b] ? lists.ids[b][i] : -1;
+        u.row0 = lists.out_row[b] + c * 64;
+        const int64_t i = c * 64 + lane64;
+        if (i < lists.n[b]) u.id = lists.ids[b][i];
+    };
+    auto classify = [&](unit_t &u) { u.fetch = u.id >= 0 ? is_cold<MODE>(u.id, slot, n_nodes, n_hot) : 0; };
+
+    // shared misses: the first request of an id in this call fetches the row, the others
+    // get a deferred copy from that request's output row
+    int64_t def_base = -1;                            // wave-uniform: current block of deferred entries
+    int def_used = kDeferBlock;
+    int fetched = 0;                                  // rows this lane sent over the link
+    auto pad_deferred = [&]() {                       // unused entries of the current block
+        if (def_base >= 0 && def_used + lane64 < kDeferBlock) cold.deferred[2 * (def_base + def_used + lane64)] = -1;
+    };
+    auto claim = [&](unit_t &u) {
+        if (!DEDUP) return;
+        int lose = 0;
+        int64_t from = 0;
+        if (u.fetch) {
+            const unsigned long long mine = cold.stamp | (unsigned long long)(u.row0 + lane64);
+            unsigned long long *c = &cold.claim[u.id];
+            unsigned long long cur = __hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (;;) {
+                if ((cur >> kClaimRowBits) == (cold.stamp >> kClaimRowBits)) {     // claimed in this call: final
+                    lose = 1;
+                    from = (int64_t)(cur & ((1ull << kClaimRowBits) - 1ull));
+                    break;
+                }
+                const unsigned long long seen = atomicCAS(c, cur, mine);
+                if (seen == cur) break;                                           // the claim is ours
+                cur = seen;
+            }
+        }
+        const unsigned long long losers = __ballot(lose);
+        if (losers) {
+            const int n = __popcll(losers);
+            if (def_used + n > kDeferBlock) {         // wave-uniform: a fresh block of entries
+                pad_deferred();
+                unsigned long long base = 0;
+                if (lane64 == 0) base = atomicAdd((unsigned long long *)&meta[META_DEFER_N], (unsigned long long)kDeferBlock);
+                def_base = (int64_t)__shfl(base, 0);
+                def_used = 0;
+            }
+            if (lose) {
+                const int64_t e = def_base + def_used + __popcll(losers & ((1ull << lane64) - 1ull));
+                cold.deferred[2 * e] = u.row0 + lane64;
+                cold.deferred[2 * e + 1] = from;
+                u.fetch = 0;
+            }
+            def_used += n;
+        }
     };
     // copy the n (<= kPerPass) requests at the head of the queue
     auto copy_pass = [&](unsigned head, int n) {
@@ -129,23 +196,31 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
     };
 
     unsigned head = 0, waiting = 0;                   // wave-uniform state of the queue
-    int64_t q0 = bcast(grab()), q1 = bcast(grab());
-    unsigned long long raw2 = grab();
-    int64_t row0, row1, row2;
-    int32_t id0 = load_unit(q0, row0), id1 = load_unit(q1, row1);
-    int cold0 = id0 >= 0 ? is_cold<MODE>(id0, slot, n_nodes, n_hot) : 0;
-    while (q0 < total) {
-        const unsigned long long raw3 = grab();
-        const int64_t q2 = bcast(raw2);
-        const int32_t id2 = load_unit(q2, row2);
-        const int cold1 = id1 >= 0 ? is_cold<MODE>(id1, slot, n_nodes, n_hot) : 0;
-        // the cold requests of unit 0 join the queue in request order
-        const unsigned long long mask = __ballot(cold0);
-        if (cold0) {
+    unit_t u0, u1, u2, u3;
+    u0.q = bcast(grab());
+    u1.q = bcast(grab());
+    u2.q = bcast(grab());
+    u3.q = bcast(grab());
+    unsigned long long raw = grab();
+    load_ids(u0);
+    load_ids(u1);
+    load_ids(u2);
+    classify(u0);
+    classify(u1);
+    claim(u0);
+    while (u0.q < total) {
+        const unsigned long long raw_next = grab();
+        load_ids(u3);
+        classify(u2);
+        claim(u1);
+        // the requests of unit 0 that read their row from the host join the queue in request order
+        const unsigned long long mask = __ballot(u0.fetch);
+        if (u0.fetch) {
             const unsigned before = __popcll(mask & ((1ull << lane64) - 1ull));
             const unsigned e = (head + waiting + before) % kQueue;
-            q_src[e] = id0;
-            q_dst[e] = row0 + lane64;
+            q_src[e] = u0.id;
+            q_dst[e] = u0.row0 + lane64;
+            ++fetched;
         }
         waiting += (unsigned)__popcll(mask);
         __builtin_amdgcn_wave_barrier();
@@ -155,16 +230,21 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
             waiting -= kPerPass;
         }
         __builtin_amdgcn_wave_barrier();
-        q0 = q1;
-        q1 = q2;
-        raw2 = raw3;
-        id0 = id1;
-        id1 = id2;
-        row0 = row1;
-        row1 = row2;
-        cold0 = cold1;
+        u0 = u1;
+        u1 = u2;
+        u2 = u3;
+        u3.q = bcast(raw);
+        raw = raw_next;
     }
     if (waiting) copy_pass(head, (int)waiting);       // fewer than a pass left
+    if (DEDUP) {
+        pad_deferred();
+        if (count_rows) {
+            for (int off = 32; off > 0; off >>= 1) fetched += __shfl_down(fetched, off);
+            if (lane64 == 0 && fetched)
+                atomicAdd((unsigned long long *)&meta[META_LINK_ROWS], (unsigned long long)fetched);
+        }
+    }
     if (lane64 == 0 && atomicAdd(done, 1ull) == n_waves - 1) {    // every other wave has made its last grab
         atomicExch(next, 0ull);
         atomicExch(done, 0ull);
@@ -176,28 +256,25 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
 //                       part (rows in rank order: the two-way branch of Listing 1)
 //       GATHER_HOST     every row from host memory: the untiered copy that fills the HBM
 //                       cache at placement time
-// STAGED: cold rows come from the staging area (row stage_slot[id]) instead of host memory.
-// SPLIT:  grid row 0 holds the cold workers (copy_cold_rows), list b is served by grid row b + 1
-//         and skips its cold rows.
-template <int LPR, int MODE, bool STAGED, bool SPLIT>
+// SPLIT:  grid row 0 holds the cold workers (scan_cold_rows), list b is served by grid row b + 1
+//         and skips its cold rows.  DEDUP: the workers fetch every distinct cold row once.
+template <int LPR, int MODE, bool SPLIT, bool DEDUP>
 __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32_t *__restrict__ slot,
                                                    const uint4 *__restrict__ cache,
                                                    const uint4 *__restrict__ host,
-                                                   const uint4 *__restrict__ stage,
-                                                   const int32_t *__restrict__ stage_slot,
                                                    uint4 *__restrict__ out_base, int cpr, int64_t n_nodes,
                                                    int64_t n_hot, int64_t *__restrict__ meta, int count_hits,
-                                                   int cold_workers)
+                                                   cold_t cold)
 {
     constexpr int kGroups = kBlock / LPR;
     if (SPLIT && blockIdx.y == 0) {
-        scan_cold_rows<LPR, MODE>(lists, (int)gridDim.y - 1, slot, n_nodes, n_hot, cold_workers, host, out_base, cpr,
-                                  meta);
+        scan_cold_rows<LPR, MODE, DEDUP>(lists, (int)gridDim.y - 1, slot, n_nodes, n_hot, cold, host, out_base, cpr,
+                                         meta, count_hits);
         return;
     }
     const int list = SPLIT ? blockIdx.y - 1 : blockIdx.y;
     const int32_t *__restrict__ ids = lists.ids[list];
-    const int64_t n = lists.n_dev ? *lists.n_dev : lists.n[list];
+    const int64_t n = lists.n[list];
     uint4 *__restrict__ out = out_base + lists.out_row[list] * cpr;
     const int lane = threadIdx.x % LPR;
     const int64_t group = (int64_t)blockIdx.x * kGroups + threadIdx.x / LPR;
@@ -226,11 +303,9 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
                         hits += (lane == 0);
                     } else if (SPLIT) {
                         put[j] = false;
-                    } else if (STAGED) {
-                        src[j] = stage + (int64_t)stage_slot[id] * cpr;
                     } else if (MODE == GATHER_BOUNDARY) {
-                        const uint4 *cold = host + n_hot * cpr;          // first row of the cold part
-                        src[j] = cold + ((int64_t)id - n_hot) * cpr;
+                        const uint4 *cold_part = host + n_hot * cpr;     // first row of the cold part
+                        src[j] = cold_part + ((int64_t)id - n_hot) * cpr;
                     } else {
                         src[j] = host + (int64_t)id * cpr;
                     }
@@ -269,129 +344,83 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
     }
 }
 
-// ---- shared misses: distinct cold ids of a call ---------------------------------------
-
-__device__ inline int gblock_sum(int x, int *s_wave)
+// Shared misses, second step: out[first] = out[second] for every deferred pair the cold
+// workers of the launch before left behind (rows that another request of the same call
+// has already brought over the host link).  A copy inside HBM.
+template <int LPR>
+__global__ __launch_bounds__(kBlock) void k_copy_deferred(const int64_t *__restrict__ deferred,
+                                                          const int64_t *__restrict__ meta,
+                                                          uint4 *__restrict__ out, int cpr)
 {
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) s_wave[threadIdx.x >> 6] = x;
-    __syncthreads();
-    int t = 0;
-    for (int i = 0; i < kBlock / 64; ++i) t += s_wave[i];
-    return t;
-}
-
-__device__ inline void gblock_range(int64_t n, int64_t &lo, int64_t &hi)
-{
-    int64_t chunk = (n + gridDim.x - 1) / gridDim.x;
-    chunk = (chunk + kBlock - 1) / kBlock * kBlock;
-    lo = (int64_t)blockIdx.x * chunk;
-    if (lo > n) lo = n;
-    hi = lo + chunk;
-    if (hi > n) hi = n;
-}
-
-template <int MODE>
-__global__ void k_mark_misses(id_lists_t lists, const int32_t *__restrict__ slot, int64_t n_nodes, int64_t n_hot,
-                              uint32_t *__restrict__ bitmap)
-{
-    const int32_t *__restrict__ ids = lists.ids[blockIdx.y];
-    const int64_t n = lists.n[blockIdx.y];
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n; r += stride) {
-        const int32_t id = ids[r];
-        if ((uint32_t)id >= (uint64_t)n_nodes) continue;            // reported by the gather itself
-        const bool hit = MODE == GATHER_SLOT ? slot[id] >= 0 : id < n_hot;
-        if (!hit) {
-            const uint32_t bit = 1u << (id & 31);
-            if (!(bitmap[id >> 5] & bit)) atomicOr(&bitmap[id >> 5], bit);   // most repeats stop at the read
-        }
-    }
-}
-
-__global__ __launch_bounds__(kBlock) void k_gbm_partial(const uint32_t *__restrict__ bitmap, int64_t n_words,
-                                                        int32_t *__restrict__ partial)
-{
-    __shared__ int s_wave[kBlock / 64];
-    int64_t lo, hi;
-    gblock_range(n_words, lo, hi);
-    int sum = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) sum += __popc(bitmap[i]);
-    int tot = gblock_sum(sum, s_wave);
-    if (threadIdx.x == 0) partial[blockIdx.x] = tot;
-}
-
-// bitmap -> ascending list of distinct cold ids; stage_slot[id] = its row in the staging area
-__global__ __launch_bounds__(kBlock) void k_gbm_emit(uint32_t *__restrict__ bitmap, int64_t n_words,
-                                                     const int32_t *__restrict__ partial,
-                                                     int32_t *__restrict__ uniq, int32_t *__restrict__ stage_slot,
-                                                     int64_t *__restrict__ meta)
-{
-    __shared__ int s_wave[kBlock / 64];
-    int64_t lo, hi;
-    gblock_range(n_words, lo, hi);
-    int b4 = 0, all = 0;
-    for (int i = threadIdx.x; i < (int)gridDim.x; i += kBlock) {
-        int p = partial[i];
-        all += p;
-        b4 += (i < (int)blockIdx.x) ? p : 0;
-    }
-    int carry = gblock_sum(b4, s_wave);
-    all = gblock_sum(all, s_wave);
-    if (blockIdx.x == 0 && threadIdx.x == 0) meta[META_NFRONT] = all;      // distinct cold rows of this call
-    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
-    for (int64_t tile = lo; tile < hi; tile += kBlock) {
-        const int64_t i = tile + threadIdx.x;
-        uint32_t bits = i < hi ? bitmap[i] : 0u;
-        int incl = __popc(bits);
-        const int mine = incl;
-        for (int d = 1; d < 64; d <<= 1) {
-            int y = __shfl_up(incl, d);
-            if (l >= d) incl += y;
-        }
-        __syncthreads();
-        if (l == 63) s_wave[w] = incl;
-        __syncthreads();
-        int base = 0, tot = 0;
-        for (int q = 0; q < kBlock / 64; ++q) {
-            int t = s_wave[q];
-            base += q < w ? t : 0;
-            tot += t;
-        }
-        int pos = carry + base + incl - mine;
-        carry += tot;
-        if (bits) {
-            bitmap[i] = 0u;
-            while (bits) {
-                int b = __ffs(bits) - 1;
-                bits &= bits - 1;
-                int32_t u = (int32_t)(i * 32 + b);
-                uniq[pos] = u;
-                stage_slot[u] = pos;
-                ++pos;
+    constexpr int kGroups = kBlock / LPR;
+    const int64_t n = meta[META_DEFER_N];             // entries reserved, unused ones marked
+    const int lane = threadIdx.x % LPR;
+    const int64_t group = (int64_t)blockIdx.x * kGroups + threadIdx.x / LPR;
+    const int64_t n_groups = (int64_t)gridDim.x * kGroups;
+    for (int64_t e0 = group * kRowsInFlight; e0 < n; e0 += n_groups * kRowsInFlight) {
+        const uint4 *src[kRowsInFlight];
+        uint4 *dst[kRowsInFlight];
+#pragma unroll
+        for (int j = 0; j < kRowsInFlight; ++j) {
+            src[j] = nullptr;
+            dst[j] = nullptr;
+            if (e0 + j < n) {
+                const int64_t to = deferred[2 * (e0 + j)];
+                if (to >= 0) {
+                    dst[j] = out + to * cpr;
+                    src[j] = out + deferred[2 * (e0 + j) + 1] * cpr;
+                }
             }
         }
+        for (int c = lane; c < cpr; c += LPR) {
+            uint4 v[kRowsInFlight];
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j) {
+                v[j] = make_uint4(0, 0, 0, 0);
+                if (src[j]) v[j] = src[j][c];
+            }
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j)
+                if (dst[j]) dst[j][c] = v[j];
+        }
     }
 }
 
-__global__ void k_clear_hits(int64_t *meta)
+// Before a launch that counts: hit counters, deferred entries and link rows back to zero.
+__global__ void k_gather_prepare(int64_t *meta)
 {
     if (threadIdx.x < META_HIT_STRIPES) meta[META_HIT_ROWS + threadIdx.x] = 0;
+    if (threadIdx.x == 0) {
+        meta[META_DEFER_N] = 0;
+        meta[META_LINK_ROWS] = 0;
+    }
 }
 __global__ void k_clear_gather_error(int64_t *meta) { meta[META_ERROR] = 0; }
 
-}  // namespace
-
-// One k_gather launch on stream st, bookkeeping words in meta.
-static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, bool staged,
-                        void *out, bool count_hits, hipStream_t st, int64_t *meta, bool split = false)
+__global__ void k_zero_claims(unsigned long long *claim, int64_t n)
 {
-    if (count_hits) k_clear_hits<<<1, META_HIT_STRIPES, 0, st>>>(meta);
-    if (n_max <= 0) return TIER_OK;
-    const int cpr = (int)(ctx->row_bytes / 16);
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) claim[i] = 0ull;
+}
+
+int lanes_per_row(int cpr)
+{
     int lpr = 8;
     while (lpr < cpr && lpr < 64) lpr *= 2;
+    return lpr;
+}
+
+}  // namespace
+
+// One k_gather launch on stream st, bookkeeping words in meta.  split: with cold workers;
+// dedup (with split only): they fetch every distinct cold row of the launch once.
+static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, void *out,
+                        bool count_hits, hipStream_t st, int64_t *meta, bool split = false, bool dedup = false)
+{
+    if (count_hits || dedup) k_gather_prepare<<<1, META_HIT_STRIPES, 0, st>>>(meta);
+    if (n_max <= 0) return TIER_OK;
+    const int cpr = (int)(ctx->row_bytes / 16);
+    const int lpr = lanes_per_row(cpr);
     const int groups = kBlock / lpr;
     int64_t blocks = (n_max + (int64_t)groups * kRowsInFlight - 1) / ((int64_t)groups * kRowsInFlight);
     const int64_t max_blocks = 1 << 18;     // beyond that groups loop; fewer blocks cost ~5 % of the all-hit rate
@@ -400,20 +429,28 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
         // every row over the host link: a few dozen blocks fill it, more only queue up
         if (blocks > kLinkBlocks) blocks = kLinkBlocks;
     }
-    const int cold_workers = split ? (int)(ctx->link_blocks < blocks ? ctx->link_blocks : blocks) : 0;
+    cold_t cold = {};
+    if (split) {
+        const int want = ctx->link_blocks > 0 ? ctx->link_blocks : kLinkBlocks;
+        cold.workers = (int)(want < blocks ? want : blocks);
+        if (dedup) {
+            cold.stamp = (unsigned long long)ctx->claim_stamp << kClaimRowBits;
+            cold.claim = ctx->claim;
+            cold.deferred = ctx->deferred;
+        }
+    }
     const dim3 grid((unsigned)blocks, (unsigned)(n_lists + (split ? 1 : 0)));
-#define GATHER_LAUNCH(L, M, S, P)                                                                    \
-    k_gather<L, M, S, P><<<grid, kBlock, 0, st>>>(lists, ctx->slot, (const uint4 *)ctx->cache,       \
-                                                  (const uint4 *)ctx->host_rows, (const uint4 *)ctx->stage, \
-                                                  ctx->stage_slot, (uint4 *)out, cpr, ctx->n_nodes,  \
-                                                  ctx->n_hot, meta, count_hits ? 1 : 0, cold_workers)
+#define GATHER_LAUNCH(L, M, P, D)                                                                    \
+    k_gather<L, M, P, D><<<grid, kBlock, 0, st>>>(lists, ctx->slot, (const uint4 *)ctx->cache,       \
+                                                  (const uint4 *)ctx->host_rows, (uint4 *)out, cpr,  \
+                                                  ctx->n_nodes, ctx->n_hot, meta, count_hits ? 1 : 0, cold)
 #define GATHER_CASE(L)                                                                               \
     case L:                                                                                          \
-        if (mode == GATHER_SLOT && split) GATHER_LAUNCH(L, GATHER_SLOT, false, true);                \
-        else if (mode == GATHER_BOUNDARY && split) GATHER_LAUNCH(L, GATHER_BOUNDARY, false, true);   \
-        else if (mode == GATHER_SLOT && staged) GATHER_LAUNCH(L, GATHER_SLOT, true, false);          \
+        if (mode == GATHER_SLOT && split && dedup) GATHER_LAUNCH(L, GATHER_SLOT, true, true);        \
+        else if (mode == GATHER_BOUNDARY && split && dedup) GATHER_LAUNCH(L, GATHER_BOUNDARY, true, true); \
+        else if (mode == GATHER_SLOT && split) GATHER_LAUNCH(L, GATHER_SLOT, true, false);           \
+        else if (mode == GATHER_BOUNDARY && split) GATHER_LAUNCH(L, GATHER_BOUNDARY, true, false);   \
         else if (mode == GATHER_SLOT) GATHER_LAUNCH(L, GATHER_SLOT, false, false);                   \
-        else if (mode == GATHER_BOUNDARY && staged) GATHER_LAUNCH(L, GATHER_BOUNDARY, true, false);  \
         else if (mode == GATHER_BOUNDARY) GATHER_LAUNCH(L, GATHER_BOUNDARY, false, false);           \
         else GATHER_LAUNCH(L, GATHER_HOST, false, false);                                            \
         break;
@@ -426,6 +463,16 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
 #undef GATHER_CASE
 #undef GATHER_LAUNCH
     TIER_HIP(ctx, hipGetLastError());
+    if (split && dedup) {
+        const dim3 dgrid(1024);
+        switch (lpr) {
+        case 8: k_copy_deferred<8><<<dgrid, kBlock, 0, st>>>(ctx->deferred, meta, (uint4 *)out, cpr); break;
+        case 16: k_copy_deferred<16><<<dgrid, kBlock, 0, st>>>(ctx->deferred, meta, (uint4 *)out, cpr); break;
+        case 32: k_copy_deferred<32><<<dgrid, kBlock, 0, st>>>(ctx->deferred, meta, (uint4 *)out, cpr); break;
+        default: k_copy_deferred<64><<<dgrid, kBlock, 0, st>>>(ctx->deferred, meta, (uint4 *)out, cpr); break;
+        }
+        TIER_HIP(ctx, hipGetLastError());
+    }
     return TIER_OK;
 }
 
@@ -434,63 +481,44 @@ int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, v
     id_lists_t lists = {};
     lists.ids[0] = ids;
     lists.n[0] = n;
-    return launch_lists(ctx, lists, 1, n, mode, false, out, count_hits, ctx->gather_stream, ctx->gmeta);
+    return launch_lists(ctx, lists, 1, n, mode, out, count_hits, ctx->gather_stream, ctx->gmeta);
 }
 
-static int grow(tier_ctx *ctx, void **buf, int64_t *cap, int64_t want, size_t elem)
+// Claims hold an output row in kClaimRowBits bits.
+static bool dedup_applies(const tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_total)
 {
-    if (want <= *cap) return TIER_OK;
-    TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
-    if (*buf) TIER_HIP(ctx, hipFree(*buf));
-    *buf = nullptr;
-    *cap = 0;
-    TIER_HIP(ctx, hipMalloc(buf, (size_t)want * elem));
-    *cap = want;
-    return TIER_OK;
+    if (!ctx->dedup || n_total <= 0 || ctx->n_hot >= ctx->n_nodes) return false;
+    for (int b = 0; b < n_lists; ++b)
+        if (lists.out_row[b] + lists.n[b] >= (1LL << kClaimRowBits)) return false;
+    return true;
 }
 
-// The tiered gather of one call: one uniform launch, one launch with cold workers apart, or
-// every distinct cold row fetched once.
+// The tiered gather of one call: one uniform launch, or one launch with cold workers
+// apart, which with shared misses fetch every distinct cold row once.
 static int gather_call(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int64_t n_total, void *out,
                        bool count_hits)
 {
     const int mode = ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT;
     hipStream_t st = ctx->gather_stream;
-    // nothing to split off when every row is in the cache
-    if (!ctx->dedup && ctx->link_blocks > 0 && n_total > 0 && n_total >= ctx->split_min_rows &&
-        ctx->n_hot < ctx->n_nodes)
-        return launch_lists(ctx, lists, n_lists, n_max, mode, false, out, count_hits, st, ctx->gmeta, true);
-    if (!ctx->dedup || n_total == 0)
-        return launch_lists(ctx, lists, n_lists, n_max, mode, false, out, count_hits, st, ctx->gmeta);
-
-    // at most min(requests, nodes) distinct cold rows
-    const int64_t cap = n_total < ctx->n_nodes ? n_total : ctx->n_nodes;
-    int rc = grow(ctx, (void **)&ctx->stage, &ctx->stage_cap, cap, (size_t)ctx->row_bytes);
-    if (rc == TIER_OK) rc = grow(ctx, (void **)&ctx->uniq_ids, &ctx->uniq_cap, cap, sizeof(int32_t));
-    if (rc != TIER_OK) return rc;
-    const dim3 mgrid((unsigned)((n_max + kBlock - 1) / kBlock < 4096 ? (n_max + kBlock - 1) / kBlock : 4096),
-                     (unsigned)n_lists);
-    if (mode == GATHER_SLOT)
-        k_mark_misses<GATHER_SLOT><<<mgrid, kBlock, 0, st>>>(lists, ctx->slot, ctx->n_nodes, ctx->n_hot, ctx->gbitmap);
-    else
-        k_mark_misses<GATHER_BOUNDARY><<<mgrid, kBlock, 0, st>>>(lists, ctx->slot, ctx->n_nodes, ctx->n_hot,
-                                                                 ctx->gbitmap);
-    int64_t g = (ctx->n_words + 4 * kBlock - 1) / (4 * kBlock);
-    const int bgrid = (int)(g < 1 ? 1 : (g > TIER_SCAN_BLOCKS ? TIER_SCAN_BLOCKS : g));
-    k_gbm_partial<<<bgrid, kBlock, 0, st>>>(ctx->gbitmap, ctx->n_words, ctx->gpartial);
-    k_gbm_emit<<<bgrid, kBlock, 0, st>>>(ctx->gbitmap, ctx->n_words, ctx->gpartial, ctx->uniq_ids, ctx->stage_slot,
-                                         ctx->gmeta);
-    TIER_HIP(ctx, hipGetLastError());
-    id_lists_t fetch = {};
-    fetch.ids[0] = ctx->uniq_ids;
-    fetch.n[0] = cap;
-    fetch.n_dev = &ctx->gmeta[META_NFRONT];
-    rc = launch_lists(ctx, fetch, 1, cap, GATHER_HOST, false, ctx->stage, false, st, ctx->gmeta);
-    if (rc != TIER_OK) return rc;
-    return launch_lists(ctx, lists, n_lists, n_max, mode, true, out, count_hits, st, ctx->gmeta);
+    const bool any_cold = n_total > 0 && ctx->n_hot < ctx->n_nodes;     // nothing to split off otherwise
+    ctx->last_deduped = dedup_applies(ctx, lists, n_lists, n_total);
+    if (ctx->last_deduped) {
+        // deferred entries: at most one block of kDeferBlock per unit of 64 requests, plus one per worker wave
+        const int64_t workers = ctx->link_blocks > 0 ? ctx->link_blocks : kLinkBlocks;
+        const int64_t entries = n_total + (int64_t)kDeferBlock * (n_lists + workers * (kBlock / 64) + 1);
+        int rc = tier_ensure(ctx, (void **)&ctx->deferred, &ctx->deferred_cap, (size_t)entries * 2 * sizeof(int64_t));
+        if (rc != TIER_OK) return rc;
+        if (++ctx->claim_stamp >= (1u << (64 - kClaimRowBits))) {     // stamps used up: start over on a clean table
+            k_zero_claims<<<4096, kBlock, 0, st>>>(ctx->claim, ctx->n_nodes);
+            ctx->claim_stamp = 1;
+        }
+        return launch_lists(ctx, lists, n_lists, n_max, mode, out, count_hits, st, ctx->gmeta, true, true);
+    }
+    const bool split = ctx->link_blocks > 0 && any_cold && n_total >= ctx->split_min_rows;
+    return launch_lists(ctx, lists, n_lists, n_max, mode, out, count_hits, st, ctx->gmeta, split);
 }
 
-// hit / miss rows of the launch(es) since the last k_clear_hits on the gather stream
+// hit / miss rows of the launch since the last k_gather_prepare on the gather stream
 static int read_stats(tier_ctx *ctx, int64_t n_total, tier_gather_stats *stats)
 {
     TIER_HIP(ctx, hipMemcpyAsync(ctx->gmeta_host, ctx->gmeta, GMETA_WORDS * sizeof(int64_t), hipMemcpyDeviceToHost,
@@ -503,7 +531,7 @@ static int read_stats(tier_ctx *ctx, int64_t n_total, tier_gather_stats *stats)
     stats->hit_rows = 0;
     for (int i = 0; i < META_HIT_STRIPES; ++i) stats->hit_rows += ctx->gmeta_host[META_HIT_ROWS + i];
     stats->miss_rows = n_total - stats->hit_rows;
-    stats->link_rows = ctx->dedup && n_total > 0 ? ctx->gmeta_host[META_NFRONT] : stats->miss_rows;
+    stats->link_rows = ctx->last_deduped ? ctx->gmeta_host[META_LINK_ROWS] : stats->miss_rows;
     return TIER_OK;
 }
 
@@ -560,13 +588,13 @@ extern "C" int tier_set_gather_dedup(tier_ctx *ctx, int on)
 {
     if (!ctx) return TIER_EINVAL;
     TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
-    if (on && !ctx->gbitmap) {
-        const size_t words = (size_t)(ctx->n_words > 0 ? ctx->n_words : 1);
-        TIER_HIP(ctx, hipMalloc(&ctx->gbitmap, words * sizeof(uint32_t)));
-        TIER_HIP(ctx, hipMemsetAsync(ctx->gbitmap, 0, words * sizeof(uint32_t), ctx->gather_stream));
-        TIER_HIP(ctx, hipMalloc(&ctx->stage_slot, (size_t)(ctx->n_nodes > 0 ? ctx->n_nodes : 1) * sizeof(int32_t)));
-        TIER_HIP(ctx, hipMalloc(&ctx->gpartial, TIER_SCAN_BLOCKS * sizeof(int32_t)));
+    if (on && !ctx->claim) {
+        const int64_t n = ctx->n_nodes > 0 ? ctx->n_nodes : 1;
+        TIER_HIP(ctx, hipMalloc(&ctx->claim, (size_t)n * sizeof(unsigned long long)));
+        k_zero_claims<<<4096, kBlock, 0, ctx->gather_stream>>>(ctx->claim, n);
+        TIER_HIP(ctx, hipGetLastError());
         TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+        ctx->claim_stamp = 0;
     }
     ctx->dedup = on != 0;
     return TIER_OK;

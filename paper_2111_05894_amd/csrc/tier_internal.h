@@ -15,6 +15,8 @@ enum {
     META_ERROR,                               // != 0: a kernel saw an id outside [0, n_nodes)
     META_COLD_NEXT,                           // split gather: next chunk of requests for the cold workers,
     META_COLD_DONE,                           //   workers' waves that ran dry; both zero between launches
+    META_DEFER_N,                             // shared misses: deferred entries reserved by the cold workers
+    META_LINK_ROWS,                           //   rows they read over the host link (counted on request)
     META_HIT_ROWS,                            // first of META_HIT_STRIPES counters (gather bookkeeping only)
     META_WORDS
 };
@@ -41,15 +43,13 @@ struct tier_ctx {
     hipStream_t gather_stream;   // stream of tier_gather_features (= stream unless set apart)
     int64_t *gmeta;              // device: error flag and hit counter of the gather stream
     int64_t *gmeta_host;         // pinned mirror
-    // shared misses (tier_set_gather_dedup): scratch of the gather stream
+    // shared misses (tier_set_gather_dedup): state of the gather stream
     bool dedup;
-    uint32_t *gbitmap;           // n_words; cold ids requested by the current call, zero between calls
-    int32_t *stage_slot;         // n_nodes; row of a cold id in the staging area (valid for the current call's ids)
-    int32_t *gpartial;           // TIER_SCAN_BLOCKS
-    int32_t *uniq_ids;           // distinct cold ids of the current call, ascending
-    int64_t uniq_cap;
-    uint8_t *stage;              // their rows, fetched once
-    int64_t stage_cap;           // in rows
+    bool last_deduped;           // the last gather call ran with claims (its link rows are in META_LINK_ROWS)
+    unsigned long long *claim;   // n_nodes; stamp << 40 | output row of the request that fetches the id in that call
+    uint32_t claim_stamp;        // stamp of the last call that claimed (24 bits, then the table is cleared)
+    int64_t *deferred;           // pairs (output row, output row to copy from) left by the cold workers
+    size_t deferred_cap;         // bytes
     // split gather (tier_set_gather_split): the cold rows of a call go to a few blocks of the launch
     int link_blocks;             // how many; 0 = every block copies hot and cold rows alike
     int64_t split_min_rows;      // calls with fewer rows keep the uniform launch
