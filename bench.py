@@ -320,7 +320,7 @@ def main():
         for name, on in (("plain", False), ("shared_misses", True)):
             tier.tier_set_gather_dedup(ctx, on)
             for timed in (False, True):                 # first pass grows the staging area and counts, second times
-                ms = 0.0; link_rows = 0
+                ms = 0.0; call_links = 0
                 for g in groups:
                     blk = sample_group(g)
                     if timed:
@@ -329,9 +329,9 @@ def main():
                         ms += a.elapsed_time(b_)
                     else:
                         tier.tier_gather_minibatches(ctx, blk, len(g), out_buf[0], want_stats=True)
-                        link_rows += ctx.last_link_rows
+                        call_links += ctx.last_link_rows
                 if not timed:
-                    links = link_rows
+                    links = call_links
             shared[name] = {"gather_ms": round(ms, 3), "host_link_bytes": links * R,
                             "gathered_GBps": round(rows * R / (ms * 1e-3) / 1e9, 2) if ms else None}
         tier.tier_set_gather_dedup(ctx, shared_on)
@@ -504,7 +504,7 @@ def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget,
         B = tier.tier_max_batches(ctx2)
         blocks = tier.BlocksBatch(n, bs, wl.fanouts, B, dev)
         out = None
-        rows = hits = 0; ms = 0.0; launches = 0
+        rows = hits = links = 0; ms = 0.0; launches = 0
         for g0 in range(0, n_batches, B):
             g = list(range(g0, min(g0 + B, n_batches)))
             blk = tier.tier_sample_minibatches(ctx2, ep[g[0] * bs: min(n_train, (g[-1] + 1) * bs)], bs,
@@ -518,12 +518,18 @@ def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget,
             torch.cuda.synchronize()
             ms += a.elapsed_time(b_); launches += 1; rows += r
             hits += sum(int((blk.frontier(i) < n_hot).sum()) for i in range(len(g)))
+            if shared_on:                           # cold rows that have to cross the link: the distinct ones of the call
+                ids = torch.cat([blk.frontier(i) for i in range(len(g))])
+                links += int(torch.unique(ids[ids >= n_hot]).numel())
+        if not shared_on:
+            links = rows - hits
         R = ctx2.row_bytes
         h = hits / rows if rows else 0.0
+        d = links / (rows - hits) if rows > hits else 1.0
         res.update({"n_hot": n_hot, "rows_per_epoch": rows, "hit_fraction": round(h, 4),
                     "gather_ms": round(ms, 3), "gather_GBps": round(rows * R / (ms * 1e-3) / 1e9, 2) if ms else None,
                     "avg_launch_ms": round(ms / launches, 4) if launches else None})
-        peak = (2 * R + 4) / (((1 + h) * R + 4) / HBM_PEAK_GBPS + (1 - h) * R / LINK_PEAK_GBPS)
+        peak = (2 * R + 4) / (((1 + h + (1 - h) * (1 - d)) * R + 4) / HBM_PEAK_GBPS + (1 - h) * d * R / LINK_PEAK_GBPS)
         res["roofline_frac"] = round((2 * R + 4) * rows / (ms * 1e-3) / 1e9 / peak, 4) if ms else None
         ctx2.close()
     finally:
