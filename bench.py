@@ -50,6 +50,9 @@ def main():
                     help="also sweep the HBM budget and the sampling depth (analogues of the paper's Fig. 5 and 6)")
     ap.add_argument("--link-blocks", type=int, default=64,
                     help="blocks of the cold-row launch of the split gather (0: one uniform launch per call)")
+    ap.add_argument("--group", type=int, default=16,
+                    help="mini-batches per sampling / gather call (at most what the context takes, up to 64); a larger "
+                         "group shares more cold rows per call and holds that many mini-batches' rows in HBM at once")
     ap.add_argument("--no-shared-misses", action="store_true",
                     help="read every requested cold row over the host link, also those a call requests more than once")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink nodes, edges and budget alike")
@@ -99,6 +102,8 @@ def main():
     order = synth.random_order(n_train, synth.EPOCH_SEED, 1, dev)
     epoch_ids = train[order].contiguous()
     B = tier.tier_max_batches(ctx)                 # mini-batches sampled side by side per call
+    if args.group > 0:
+        B = min(B, args.group)
     groups = [list(range(g, min(g + B, n_batches))) for g in range(0, n_batches, B)]
     bseed = [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in range(n_batches)]
     # three sets of block buffers: while up to two groups of mini-batches wait for or run their
@@ -348,7 +353,7 @@ def main():
 
     reorder = None
     if not args.no_reorder:
-        reorder = reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, args.link_blocks, shared_on)
+        reorder = reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, args.link_blocks, shared_on, B)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -378,6 +383,7 @@ def main():
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3),
                      "epoch_wall": round(mean(rec["epoch_wall_ms"]), 3)},
         "gather_launch": {"link_blocks": args.link_blocks, "min_rows": SPLIT_MIN_ROWS, "shared_misses": shared_on,
+                          "mini_batches_per_call": B, "output_rows_held": int(out_buf[0].shape[0]),
                           "note": "split launch: the first link_blocks blocks copy the cold rows (host link), all others the "
                                   "hot rows (HBM); uniform_launch_epoch is the same epoch with every block copying both",
                           "uniform_launch_epoch": uniform},
@@ -470,7 +476,7 @@ def run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_
     return {"budget": budget, "depth": depth}
 
 
-def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, link_blocks, shared_on):
+def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget, n, dtype, dev, log, link_blocks, shared_on, group):
     """The paper's own layout (Sec. 3.2, Alg. 2): graph and table renamed by rank, hot part =
     ids below the boundary, gather without a map.  Times the reordering and one sampled and
     gathered epoch on the reordered data (its draws differ: they are keyed by node id)."""
@@ -501,7 +507,7 @@ def reordered_variant(tier, synth, torch, ctx, wl, table, counts, train, budget,
         n_train = train2.numel(); n_batches = -(-n_train // bs)
         order_e = synth.random_order(n_train, synth.EPOCH_SEED, 1, dev)
         ep = train2[order_e].contiguous()
-        B = tier.tier_max_batches(ctx2)
+        B = min(group, tier.tier_max_batches(ctx2))
         blocks = tier.BlocksBatch(n, bs, wl.fanouts, B, dev)
         out = None
         rows = hits = links = 0; ms = 0.0; launches = 0

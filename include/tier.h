@@ -44,7 +44,7 @@ extern "C" {
 
 #define TIER_MAX_LAYERS 8    /* hops per mini-batch                              */
 #define TIER_MAX_FANOUT 64   /* neighbours drawn per node per hop (one wavefront) */
-#define TIER_MAX_BATCHES 16  /* mini-batches one tier_sample_minibatches call can take  */
+#define TIER_MAX_BATCHES 64  /* mini-batches one tier_sample_minibatches call can take  */
 
 typedef enum {
     TIER_OK = 0,

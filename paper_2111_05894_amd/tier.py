@@ -13,7 +13,7 @@ import torch
 
 MAX_LAYERS = 8
 MAX_FANOUT = 64
-MAX_BATCHES = 16
+MAX_BATCHES = 64
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtier.so")
 _lib = None
