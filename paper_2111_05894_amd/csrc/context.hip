@@ -165,7 +165,7 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     const int64_t n = c->n_nodes;
     c->n_words = (n + 31) / 32;
     c->n_sum = (c->n_words + 31) / 32;
-    // as many mini-batch slots as fit in 8 GiB of per-node scratch (16 slots up to 121 M nodes)
+    // as many mini-batch slots as fit in 8 GiB of per-node scratch (64 slots up to 32 M nodes, 18 at 111 M)
     const int64_t per_slot = (n + c->n_words + c->n_sum + 1) * 4;     // + n_words for `prev` on graphs of up to 32 M nodes
     int64_t slots = (8LL << 30) / per_slot;
     c->n_slots = (int)(slots < 1 ? 1 : (slots > TIER_MAX_BATCHES ? TIER_MAX_BATCHES : slots));
