@@ -349,7 +349,7 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
 // has already brought over the host link).  A copy inside HBM.
 template <int LPR>
 __global__ __launch_bounds__(kBlock) void k_copy_deferred(const int64_t *__restrict__ deferred,
-                                                          const int64_t *__restrict__ meta,
+                                                          int64_t *__restrict__ meta,
                                                           uint4 *__restrict__ out, int cpr)
 {
     constexpr int kGroups = kBlock / LPR;
@@ -384,16 +384,20 @@ __global__ __launch_bounds__(kBlock) void k_copy_deferred(const int64_t *__restr
                 if (dst[j]) dst[j][c] = v[j];
         }
     }
+    // the last block to finish leaves the list empty for the next call (every block has read n by then)
+    __syncthreads();
+    if (threadIdx.x == 0 &&
+        atomicAdd((unsigned long long *)&meta[META_DEFER_DONE], 1ull) == (unsigned long long)gridDim.x - 1) {
+        meta[META_DEFER_N] = 0;
+        meta[META_DEFER_DONE] = 0;
+    }
 }
 
-// Before a launch that counts: hit counters, deferred entries and link rows back to zero.
+// Before a launch that counts: hit counters and link rows back to zero.
 __global__ void k_gather_prepare(int64_t *meta)
 {
     if (threadIdx.x < META_HIT_STRIPES) meta[META_HIT_ROWS + threadIdx.x] = 0;
-    if (threadIdx.x == 0) {
-        meta[META_DEFER_N] = 0;
-        meta[META_LINK_ROWS] = 0;
-    }
+    if (threadIdx.x == 0) meta[META_LINK_ROWS] = 0;
 }
 __global__ void k_clear_gather_error(int64_t *meta) { meta[META_ERROR] = 0; }
 
@@ -417,7 +421,7 @@ int lanes_per_row(int cpr)
 static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, void *out,
                         bool count_hits, hipStream_t st, int64_t *meta, bool split = false, bool dedup = false)
 {
-    if (count_hits || dedup) k_gather_prepare<<<1, META_HIT_STRIPES, 0, st>>>(meta);
+    if (count_hits) k_gather_prepare<<<1, META_HIT_STRIPES, 0, st>>>(meta);
     if (n_max <= 0) return TIER_OK;
     const int cpr = (int)(ctx->row_bytes / 16);
     const int lpr = lanes_per_row(cpr);

@@ -15,7 +15,8 @@ enum {
     META_ERROR,                               // != 0: a kernel saw an id outside [0, n_nodes)
     META_COLD_NEXT,                           // split gather: next chunk of requests for the cold workers,
     META_COLD_DONE,                           //   workers' waves that ran dry; both zero between launches
-    META_DEFER_N,                             // shared misses: deferred entries reserved by the cold workers
+    META_DEFER_N,                             // shared misses: deferred entries reserved by the cold workers,
+    META_DEFER_DONE,                          //   blocks of the copy kernel that are through; both zero between calls
     META_LINK_ROWS,                           //   rows they read over the host link (counted on request)
     META_HIT_ROWS,                            // first of META_HIT_STRIPES counters (gather bookkeeping only)
     META_WORDS
