@@ -178,7 +178,8 @@ def test_blocks_large_frontier_spans_many_tiles():
 # ------------------------------------------------------------------------------
 # access counts
 # ------------------------------------------------------------------------------
-@pytest.mark.parametrize("fanouts,batch,epochs", [((10, 5), 100, 1), ((4, 3, 2), 64, 2), ((15,), 333, 1)])
+@pytest.mark.parametrize("fanouts,batch,epochs", [((10, 5), 100, 1), ((4, 3, 2), 64, 2), ((15,), 333, 1),
+                                                  ((5, 3), 16, 2)])       # 63 mini-batches side by side
 def test_counts_match_oracle(small, fanouts, batch, epochs):
     train = synth.train_set(small.n, 0.2, 11).numpy()
     want, wrows, wedges = orc.presample(small.indptr, small.indices, train, batch, fanouts, epochs, 5894, threads=4)
@@ -347,9 +348,10 @@ def test_split_gather_gives_the_same_rows(dim, boundary, link_blocks):
         rng = np.random.default_rng(dim + link_blocks)
         counts = rng.integers(0, 20, w.n).astype(np.uint32)
         B = tier.tier_max_batches(w.ctx)
-        seeds = rng.choice(w.n, 64 * B - 11, replace=False).astype(np.int32)
+        seeds = rng.choice(w.n, 64 * (B - 2) - 11, replace=False).astype(np.int32)   # ragged, then two empty mini-batches
         blk = tier.tier_sample_minibatches(w.ctx, torch.from_numpy(seeds).to(DEV), 64, list(range(B)), (10, 6))
         ids = torch.cat([blk.frontier(b) for b in range(B)]).cpu().numpy()
+        assert blk.n_nodes[B - 1][-1] == 0
         gs = torch.cuda.Stream()
         for hot_rows in (0, 1, 500, w.n):
             if boundary:
@@ -366,10 +368,14 @@ def test_split_gather_gives_the_same_rows(dim, boundary, link_blocks):
             tier.tier_set_gather_split(w.ctx, link_blocks, 0)
             for stream in (None, gs, None):
                 tier.tier_set_gather_stream(w.ctx, stream)
-                for rep in range(2):                                     # the cold list is rebuilt per call
+                for rep in range(4):                                     # plain, plain, shared misses twice
+                    tier.tier_set_gather_dedup(w.ctx, rep >= 2)
                     got, offs2, hit, miss = tier.tier_gather_minibatches(w.ctx, blk, B, want_stats=True)
                     assert offs2 == offs and (hit, miss) == (whit, wmiss) and torch.equal(got, plain)
                     assert np.array_equal(got.view(torch.uint8).cpu().numpy().reshape(-1, w.row_bytes), want)
+                    cold = ids[oslot[ids] < 0]
+                    assert w.ctx.last_link_rows == (len(np.unique(cold)) if rep >= 2 else len(cold))
+                tier.tier_set_gather_dedup(w.ctx, False)
                 m = 4999                                                 # a smaller call right after a larger one
                 one, h1, m1 = tier.tier_gather_features(w.ctx, torch.from_numpy(ids[:m]).to(DEV), want_stats=True)
                 w1, wh1, wm1 = orc.gather(w.feat_bytes, cache, oslot, ids[:m])
