@@ -78,7 +78,7 @@ struct wide_t {
     uint32_t *summary;           // [slot][n_sum]
     int32_t frontier_bits;       // != 0 (graphs of up to 32 M nodes): the bitmaps hold the frontier too, see k_hop_sample
     int32_t index_nodes;         // != 0: local_idx[] records every frontier node's index (blocks; membership on large graphs)
-    int32_t clear_by_list;       // != 0: k_finish clears the bitmaps node by node (k_count_columns clears them whole)
+    int32_t clear_bitmaps;       // != 0: k_finish zeroes the slot's two bitmaps (k_count_columns does it in counting mode)
     int64_t *meta;               // [slot][META_WORDS]; totals and the error flag live in slot 0
     int32_t *partial_hop;        // [slot][TIER_SCAN_BLOCKS]
     int32_t *partial_bm;         // [slot][TIER_SCAN_BLOCKS]
@@ -568,12 +568,13 @@ __global__ void k_finish(wide_t w, int layer, uint32_t *__restrict__ counts)
     for (int64_t i = t; i < n; i += stride) {
         int32_t u = v.nodes[i];
         if (w.index_nodes) v.local_idx[u] = -1;
-        if (w.clear_by_list) {                  // several nodes may share a word: all store the same zero
-            v.bitmap[(uint32_t)u >> 5] = 0u;
-            v.prev[(uint32_t)u >> 5] = 0u;
-        }
         if (COUNT) atomicAdd(&counts[u], 1u);
     }
+    if (w.clear_bitmaps)                        // small enough to stream through whole: cheaper than two
+        for (int64_t i = t; i < w.n_words; i += stride) {     // scattered stores per frontier node
+            v.bitmap[i] = 0u;
+            v.prev[i] = 0u;
+        }
     if (COUNT && t == 0 && n)
         atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)n);
 }
@@ -764,7 +765,7 @@ int tier_sample_minibatches(tier_ctx *ctx, const int32_t *seeds, int64_t n_seeds
     wide_t w = make_wide(ctx, seeds, n_seeds_total, batch_size, n_batches, out->nodes, out->nodes_stride);
     w.frontier_bits = two_level(ctx) ? 0 : 1;
     w.index_nodes = 1;
-    w.clear_by_list = w.frontier_bits;
+    w.clear_bitmaps = w.frontier_bits;
     for (int s = 0; s < n_batches; ++s) {
         w.key0[s] = (uint32_t)batch_seeds[s];
         w.key1[s] = (uint32_t)(batch_seeds[s] >> 32);
@@ -830,7 +831,7 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
             wide_t w = make_wide(ctx, train_ids + lo, n_train - lo, batch_size, slots, ctx->ps_nodes, stride);
             w.frontier_bits = two_level(ctx) ? 0 : 1;
             w.index_nodes = w.frontier_bits ? 0 : 1;       // small graphs: nothing is relabelled, local_idx[] stays untouched
-            w.clear_by_list = 0;                           // k_count_columns clears the bitmaps whole
+            w.clear_bitmaps = 0;                           // k_count_columns clears the bitmaps
             w.count_edges = total_edges != nullptr;
             for (int s = 0; s < slots; ++s) {
                 const uint64_t bs = tier_batch_seed(seed, (uint32_t)e, (uint32_t)(b + s));
