@@ -349,7 +349,7 @@ def main():
 
     sweeps = None
     if args.sweeps:
-        sweeps = run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_group, L, log)
+        sweeps = run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_group, L, log, timed_gather, gs)
 
     reorder = None
     if not args.no_reorder:
@@ -430,10 +430,12 @@ def score_comparison(tier, synth, torch, ctx, wl, counts, train, budget, groups,
     return res
 
 
-def run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_group, L, log):
+def run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_group, L, log, timed_gather, gs):
     """Harness-only analysis on the library's outputs.
     budget: hit fraction of the measured epoch against the share of rows kept in HBM, for placement by
-    presampled counts and by weighted reverse PageRank (the paper's Fig. 6 sweeps the loaded share).
+    presampled counts and by weighted reverse PageRank, and for the placement by counts the measured
+    time of the placement (cache fill included) and of the epoch's gathers (the paper's Fig. 6 sweeps
+    the loaded share and plots PCIe traffic and time).
     depth: share of all measured accesses that falls on the top 10 % of nodes by score, for fanouts
     (10,10) .. (10,10,10,10,10) (the paper's Fig. 5), accesses measured by tier_presample with the
     measured epoch's seed over at most 64 mini-batches."""
@@ -458,7 +460,24 @@ def run_sweeps(tier, synth, torch, ctx, wl, counts, train, n, R, groups, sample_
             h = float((rk[allf] < n_hot).sum()) / rows
             row[f"hit_{name}"] = round(h, 4)
         row["host_link_bytes_counts"] = int(round((1 - row["hit_counts"]) * rows)) * R
+        # measured: placement by counts at this share, then the epoch's gathers (alone on the GPU)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        tier.tier_place(ctx, counts, n_hot * R, want_slot_map=False)
+        with torch.cuda.stream(gs):
+            e1.record()
+        torch.cuda.synchronize()
+        row["place_ms"] = round(e0.elapsed_time(e1), 3)
+        ms = 0.0
+        for g in groups:
+            blk = sample_group(g)
+            a, b_, _ = timed_gather(blk, len(g))
+            torch.cuda.synchronize()
+            ms += a.elapsed_time(b_)
+        row["epoch_gather_ms"] = round(ms, 3)
         budget.append(row)
+        log(f"[bench] budget sweep {p}: {row}")
     depth = []
     sub = train[: min(train.numel(), 64 * wl.batch_size)].contiguous()
     acc = torch.empty_like(counts)
