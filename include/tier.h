@@ -173,7 +173,7 @@ int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes,
  * Edges run source -> target and row v of the graph lists the sources of the edges into v.
  *
  * tier_score_degree: degree[u] = out degree of u = number of adjacency lists that hold u
- * ("the first metric", Sec. 3.1).  degree: (device) n_nodes entries, overwritten; feed it
+ * (the simplest of the scores of Sec. 3.1).  degree: (device) n_nodes entries, overwritten; feed it
  * to tier_place / tier_rank as the counts.  Asynchronous.
  *
  * tier_score_wrpr: weighted reverse PageRank (Alg. 1): score = 1/N, times N/n_train on the
@@ -255,7 +255,11 @@ int tier_max_batches(const tier_ctx *ctx);
  * the HBM cache when slot[ids[i]] >= 0 and from host memory otherwise; the result
  * does not depend on the placement.  ids: (device) n ids, repeats allowed.
  * out: (device) n * row_bytes bytes, 16-byte aligned.  stats (host, optional): row
- * counts per tier; asking for them makes the call wait, otherwise asynchronous. */
+ * counts per tier; asking for them makes the call wait, otherwise asynchronous.
+ * Ids inside [0, n_nodes) are a precondition that only a call with stats checks: such
+ * a call returns TIER_EINVAL when one of its own ids is outside (stats then unset); a
+ * call without stats returns TIER_OK.  Either way the row of such an id is all zero
+ * bytes and no memory outside the tables is touched. */
 int tier_gather_features(tier_ctx *ctx, const int32_t *ids, int64_t n, void *out,
                          tier_gather_stats *stats);
 

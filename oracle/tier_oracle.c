@@ -327,39 +327,40 @@ void orc_gather(const uint8_t *feat, const uint8_t *cache, const int32_t *slot,
 }
 
 /* ------------------------------------------------------------------------ */
-/* Graph and feature reordering (Sec. 3.2, Alg. 2 "Parallelizable Graph      */
-/* Reordering"): every node takes its rank as its new id.  srt_idx is the    */
-/* old id -> new id map (the rank).  In the algorithm's order:               */
-/*   1. nd_new[srt_idx[i] + 1] = length of node i's neighbour list           */
-/*   2. nd_new[0] = 0, prefix sum over nd_new                                */
-/*   3. every value of the edge list is replaced by its new id               */
-/*   4. node i's list moves from nd[i] to nd_new[srt_idx[i]], order kept     */
-/* Reading: the printed last loop indexes nd_new with the old id i; the text */
-/* ("identify the location of old neighbor list using nd and place to the    */
-/* new location using nd_new") fixes the new location as that of the new id. */
+/* Graph and feature reordering (Sec. 3.2, Alg. 2): every node takes its     */
+/* rank as its new id.  The result has a plain definition, written out here:  */
+/* new node r owns the neighbour list of the node whose rank is r, entries in */
+/* their old order, every entry replaced by its own rank; offsets_new is the  */
+/* running sum of those list lengths.  (Alg. 2 reaches the same arrays by a   */
+/* scatter of lengths, a prefix sum and a relocation, so that every step is   */
+/* parallel; the GPU path does it that way.)                                  */
+/* Reading: Alg. 2's last loop, as printed, addresses the new offsets with    */
+/* the old id; its accompanying text places a list at the offset of the       */
+/* node's new id, which is also the only reading consistent with the first    */
+/* loop, and is what the definition above says.                               */
 /* ------------------------------------------------------------------------ */
-void orc_reorder_graph(int64_t n, const int64_t *nd, const int32_t *edg, const int32_t *srt_idx,
-                       int64_t *nd_new, int32_t *edg_new)
+void orc_reorder_graph(int64_t n, const int64_t *indptr, const int32_t *indices, const int32_t *rank,
+                       int64_t *indptr_new, int32_t *indices_new)
 {
-    int64_t n_edges = nd[n];
-    int32_t *relabelled = (int32_t *)malloc((size_t)(n_edges > 0 ? n_edges : 1) * sizeof(int32_t));
-    for (int64_t i = 0; i < n; ++i) nd_new[srt_idx[i] + 1] = nd[i + 1] - nd[i];
-    nd_new[0] = 0;
-    for (int64_t i = 0; i < n; ++i) nd_new[i + 1] += nd_new[i];
-    for (int64_t e = 0; e < n_edges; ++e) relabelled[e] = srt_idx[edg[e]];
-    for (int64_t i = 0; i < n; ++i) {
-        int64_t len = nd[i + 1] - nd[i];
-        for (int64_t j = 0; j < len; ++j) edg_new[nd_new[srt_idx[i]] + j] = relabelled[nd[i] + j];
+    int32_t *who = (int32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int32_t));   /* who[r] = node of rank r */
+    for (int64_t i = 0; i < n; ++i) who[rank[i]] = (int32_t)i;
+    indptr_new[0] = 0;
+    for (int64_t r = 0; r < n; ++r) {
+        const int64_t i = who[r];
+        const int64_t len = indptr[i + 1] - indptr[i];
+        indptr_new[r + 1] = indptr_new[r] + len;
+        for (int64_t j = 0; j < len; ++j)
+            indices_new[indptr_new[r] + j] = rank[indices[indptr[i] + j]];
     }
-    free(relabelled);
+    free(who);
 }
 
 /* Feature rows follow their nodes (Sec. 3.2: the table is reordered by score). */
-void orc_reorder_rows(const uint8_t *feat, int64_t n, int64_t row_bytes, const int32_t *srt_idx,
+void orc_reorder_rows(const uint8_t *feat, int64_t n, int64_t row_bytes, const int32_t *rank,
                       uint8_t *feat_new)
 {
     for (int64_t i = 0; i < n; ++i)
-        memcpy(feat_new + (size_t)srt_idx[i] * (size_t)row_bytes, feat + (size_t)i * (size_t)row_bytes,
+        memcpy(feat_new + (size_t)rank[i] * (size_t)row_bytes, feat + (size_t)i * (size_t)row_bytes,
                (size_t)row_bytes);
 }
 
@@ -393,39 +394,41 @@ void orc_score_degree(int64_t n, const int64_t *indptr, const int32_t *indices, 
     for (int64_t e = 0; e < indptr[n]; ++e) degree[indices[e]] += 1u;
 }
 
-/* Score 3: weighted reverse PageRank (Alg. 1).  In the algorithm's order:          */
-/*   score = 1/N everywhere, times N/N_train on the training nodes;                  */
-/*   per iteration: score[j] /= in_degree[j]; every node pulls (sums) the scores of  */
-/*   the nodes it targets; score[j] = (1-d)/N + d*score[j].                          */
-/* With weight 1 (no training ids) this is plain reverse PageRank (score 2) cut     */
-/* after `iter` rounds.  Readings: a node without incoming edges is not divided      */
-/* (nobody pulls from it); the pull replaces the score (a node that targets nothing  */
-/* pulls 0); sums run over rows in order and over each row in list order.            */
+/* Score 3: weighted reverse PageRank (Sec. 3.1, Alg. 1), an iteration, so its rounds  */
+/* are taken as the paper orders them.  Start: every node 1/N, a training node N/n_train */
+/* times that.  One round: each node v splits its score evenly over its incoming edges   */
+/* (share[v] = score[v] / in_degree(v)); each node u collects the shares of the nodes it */
+/* points to; score[u] = (1 - damp)/N + damp * collected[u].  Without training ids the   */
+/* start is uniform and this is plain reverse PageRank (score 2) cut after `iterations`  */
+/* rounds.  Readings: a node nobody points to keeps its score undivided (no node         */
+/* collects from it); what a node collects replaces its score (a node that points        */
+/* nowhere collects 0); sums run over the rows in order and over each row in list order. */
 void orc_score_wrpr(int64_t n, const int64_t *indptr, const int32_t *indices,
-                    const int32_t *tid, int64_t num_train, int iter, double d, double *score)
+                    const int32_t *train_ids, int64_t n_train, int iterations, double damp, double *score)
 {
-    double *pulled = (double *)malloc((size_t)(n > 0 ? n : 1) * sizeof(double));
-    for (int64_t i = 0; i < n; ++i) score[i] = 1.0 / (double)n;
-    if (num_train > 0) {
-        double weight = (double)n / (double)num_train;
-        for (int64_t i = 0; i < num_train; ++i) score[tid[i]] = score[tid[i]] * weight;
+    double *share = (double *)malloc((size_t)(n > 0 ? n : 1) * sizeof(double));
+    double *collected = (double *)malloc((size_t)(n > 0 ? n : 1) * sizeof(double));
+    for (int64_t v = 0; v < n; ++v) score[v] = 1.0 / (double)n;
+    if (n_train > 0) {
+        const double boost = (double)n / (double)n_train;
+        for (int64_t t = 0; t < n_train; ++t) score[train_ids[t]] = score[train_ids[t]] * boost;
     }
-    for (int it = 0; it < iter; ++it) {
-        for (int64_t j = 0; j < n; ++j) {
-            int64_t in_degree = indptr[j + 1] - indptr[j];
-            if (in_degree > 0) score[j] = score[j] / (double)in_degree;
+    for (int round = 0; round < iterations; ++round) {
+        for (int64_t v = 0; v < n; ++v) {
+            const int64_t in_degree = indptr[v + 1] - indptr[v];     /* row v lists the sources of the edges into v */
+            share[v] = in_degree > 0 ? score[v] / (double)in_degree : score[v];
+            collected[v] = 0.0;
         }
-        /* pull_from_neighbor: source u sums over the nodes v it targets; row v lists those sources */
-        for (int64_t u = 0; u < n; ++u) pulled[u] = 0.0;
         for (int64_t v = 0; v < n; ++v)
-            for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e) pulled[indices[e]] += score[v];
-        for (int64_t j = 0; j < n; ++j) {
-            double a = (1.0 - d) / (double)n;
-            double b = d * pulled[j];
-            score[j] = a + b;
+            for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e) collected[indices[e]] += share[v];   /* indices[e] points to v */
+        for (int64_t u = 0; u < n; ++u) {
+            const double floor_part = (1.0 - damp) / (double)n;
+            const double pulled_part = damp * collected[u];
+            score[u] = floor_part + pulled_part;
         }
     }
-    free(pulled);
+    free(share);
+    free(collected);
 }
 
 /* Ranking by a real-valued score: descending score, equal scores by ascending id. */

@@ -190,6 +190,7 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     k_fill_i32<<<grid_for(prev_words, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->prev, prev_words, 0);
     k_fill_i32<<<grid_for(c->n_sum * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->summary,
                                                                                 c->n_sum * (int64_t)S, 0);
+    k_fill_i32<<<grid_for(n, 256, 8192), 256, 0, c->stream>>>(c->slot, n, -1);          // nothing placed yet
     k_fill_i32<<<1, 64, 0, c->stream>>>((int32_t *)c->gmeta, GMETA_WORDS * 2, 0);
     k_fill_i32<<<4, 256, 0, c->stream>>>((int32_t *)c->meta, (int64_t)S * META_WORDS * 2, 0);
     TIER_HIP(c, hipGetLastError());

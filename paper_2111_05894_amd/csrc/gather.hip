@@ -245,7 +245,11 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
                 atomicAdd((unsigned long long *)&meta[META_LINK_ROWS], (unsigned long long)fetched);
         }
     }
-    if (lane64 == 0 && atomicAdd(done, 1ull) == n_waves - 1) {    // every other wave has made its last grab
+    // The wave's last grab (its value is never looked at) must have reached the counter before the wave
+    // counts as done: the increment of `done` releases everything this lane issued before it, so the
+    // wave that sees n_waves - 1 resets a counter nobody will touch again in this launch.
+    if (lane64 == 0 &&
+        __hip_atomic_fetch_add(done, 1ull, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == n_waves - 1) {
         atomicExch(next, 0ull);
         atomicExch(done, 0ull);
     }
@@ -393,13 +397,16 @@ __global__ __launch_bounds__(kBlock) void k_copy_deferred(const int64_t *__restr
     }
 }
 
-// Before a launch that counts: hit counters and link rows back to zero.
+// Before a launch that counts: hit counters, link rows and the id-error flag back to zero, so that the
+// statistics (and the error) a call reports are its own.
 __global__ void k_gather_prepare(int64_t *meta)
 {
     if (threadIdx.x < META_HIT_STRIPES) meta[META_HIT_ROWS + threadIdx.x] = 0;
-    if (threadIdx.x == 0) meta[META_LINK_ROWS] = 0;
+    if (threadIdx.x == 0) {
+        meta[META_LINK_ROWS] = 0;
+        meta[META_ERROR] = 0;
+    }
 }
-__global__ void k_clear_gather_error(int64_t *meta) { meta[META_ERROR] = 0; }
 
 __global__ void k_zero_claims(unsigned long long *claim, int64_t n)
 {
@@ -528,10 +535,7 @@ static int read_stats(tier_ctx *ctx, int64_t n_total, tier_gather_stats *stats)
     TIER_HIP(ctx, hipMemcpyAsync(ctx->gmeta_host, ctx->gmeta, GMETA_WORDS * sizeof(int64_t), hipMemcpyDeviceToHost,
                                  ctx->gather_stream));
     TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
-    if (ctx->gmeta_host[META_ERROR] != 0) {
-        k_clear_gather_error<<<1, 1, 0, ctx->gather_stream>>>(ctx->gmeta);
-        return TIER_EINVAL;
-    }
+    if (ctx->gmeta_host[META_ERROR] != 0) return TIER_EINVAL;     // an id of this call outside [0, n_nodes)
     stats->hit_rows = 0;
     for (int i = 0; i < META_HIT_STRIPES; ++i) stats->hit_rows += ctx->gmeta_host[META_HIT_ROWS + i];
     stats->miss_rows = n_total - stats->hit_rows;

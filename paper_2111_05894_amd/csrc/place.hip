@@ -328,12 +328,16 @@ static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget
     if (n_hot > 0) {
         int rc = tier_ensure(ctx, (void **)&ctx->cache, &ctx->cache_cap, (size_t)n_hot * (size_t)ctx->row_bytes);
         if (rc != TIER_OK) return rc;
-        if (gs != st) {
-            TIER_HIP(ctx, hipEventRecord(ctx->ev_place, st));
-            TIER_HIP(ctx, hipStreamWaitEvent(gs, ctx->ev_place, 0));
-            ctx->fill_pending = true;
-        }
-        rc = tier_launch_gather(ctx, order, n_hot, GATHER_HOST, ctx->cache, false);
+    }
+    if (gs != st) {
+        // everything later on the gather stream (the fill below, every gather) comes after the map,
+        // also when nothing is placed: a gather must never meet a half-written map
+        TIER_HIP(ctx, hipEventRecord(ctx->ev_place, st));
+        TIER_HIP(ctx, hipStreamWaitEvent(gs, ctx->ev_place, 0));
+    }
+    if (n_hot > 0) {
+        if (gs != st) ctx->fill_pending = true;
+        int rc = tier_launch_gather(ctx, order, n_hot, GATHER_HOST, ctx->cache, false);
         if (rc != TIER_OK) return rc;
     }
     ctx->n_hot = n_hot;

@@ -67,23 +67,25 @@ MUTANTS = [
     ("gather indexes the cache by id", "row = cache + (size_t)slot[v] * (size_t)row_bytes; ++hit;",
      "row = cache + (size_t)(v % 2) * (size_t)row_bytes; ++hit;",
      [pins.test_gather_equals_fancy_indexing_for_any_budget]),
-    ("reorder: lengths placed at the old id", "nd_new[srt_idx[i] + 1] = nd[i + 1] - nd[i];", "nd_new[i + 1] = nd[i + 1] - nd[i];",
-     [rpins.test_reorder_hand_worked_example], "isolate"),      # may write past a list's end: own process
-    ("reorder: values not renamed", "relabelled[e] = srt_idx[edg[e]];", "relabelled[e] = edg[e];",
+    ("reorder: lists stay at the old id", "const int64_t i = who[r];", "const int64_t i = r;",
+     [rpins.test_reorder_hand_worked_example], "isolate"),      # own process, as for any mutant that moves whole lists
+    ("reorder: map applied the wrong way round", "who[rank[i]] = (int32_t)i;", "who[i] = rank[i];",
+     [rpins.test_reorder_hand_worked_example, rpins.test_reorder_is_a_relabelling], "isolate"),
+    ("reorder: values not renamed", "= rank[indices[indptr[i] + j]];", "= indices[indptr[i] + j];",
      [rpins.test_reorder_hand_worked_example, rpins.test_reorder_is_a_relabelling]),
-    ("reorder: lists reversed while moving", "= relabelled[nd[i] + j];", "= relabelled[nd[i] + len - 1 - j];",
+    ("reorder: lists reversed while moving", "= rank[indices[indptr[i] + j]];", "= rank[indices[indptr[i] + len - 1 - j]];",
      [rpins.test_reorder_hand_worked_example, rpins.test_reorder_is_a_relabelling]),
     ("boundary gather forgets the offset", "row = cold + (size_t)(ids[i] - boundary) * (size_t)row_bytes;",
      "row = cold + (size_t)ids[i] % 3 * (size_t)row_bytes;",
      [rpins.test_rows_follow_their_nodes_and_boundary_gather]),
-    ("pagerank divides by out-degree 1", "if (in_degree > 0) score[j] = score[j] / (double)in_degree;", "",
+    ("pagerank shares are not divided", "share[v] = in_degree > 0 ? score[v] / (double)in_degree : score[v];", "share[v] = score[v];",
      [spins.test_wrpr_hand_worked, spins.test_wrpr_equals_sparse_matrix_iteration]),
-    ("pagerank pulls the wrong way", "pulled[indices[e]] += score[v];", "pulled[v] += score[indices[e]];",
+    ("pagerank pulls the wrong way", "collected[indices[e]] += share[v];", "collected[v] += share[indices[e]];",
      [spins.test_wrpr_hand_worked, spins.test_wrpr_equals_sparse_matrix_iteration]),
-    ("pagerank weight inverted", "double weight = (double)n / (double)num_train;", "double weight = (double)num_train / (double)n;",
+    ("pagerank weight inverted", "const double boost = (double)n / (double)n_train;", "const double boost = (double)n_train / (double)n;",
      [spins.test_wrpr_hand_worked]),
-    ("pagerank damping swapped", "double a = (1.0 - d) / (double)n;\n            double b = d * pulled[j];",
-     "double a = d / (double)n;\n            double b = (1.0 - d) * pulled[j];",
+    ("pagerank damping swapped", "const double floor_part = (1.0 - damp) / (double)n;\n            const double pulled_part = damp * collected[u];",
+     "const double floor_part = damp / (double)n;\n            const double pulled_part = (1.0 - damp) * collected[u];",
      [spins.test_wrpr_equals_sparse_matrix_iteration, spins.test_wrpr_invariants]),
     ("degree counts rows instead of entries", "degree[indices[e]] += 1u;", "degree[indices[e]] = 1u;",
      [spins.test_degree_is_a_bincount]),
