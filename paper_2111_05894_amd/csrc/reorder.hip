@@ -209,8 +209,9 @@ int reorder_graph(tier_ctx *c, const int32_t *rank, const int32_t *order, OffT *
     TIER_HIP(c, hipGetLastError());
     int rc = tier_sync_meta(c);
     if (rc != TIER_OK) return rc;
-    OffT *partial = nullptr;
-    TIER_HIP(c, hipMalloc(&partial, 1024 * sizeof(OffT)));
+    rc = tier_ensure(c, (void **)&c->scan_partial, &c->scan_partial_cap, TIER_SCAN_BLOCKS * sizeof(int64_t));
+    if (rc != TIER_OK) return rc;
+    OffT *partial = (OffT *)c->scan_partial;      // kept by the context: no allocation after the first call
     k_scatter_len<OffT><<<grid_for(n, kBlock, 4096), kBlock, 0, st>>>((const OffT *)c->indptr, rank, n, nd_new);
     const int sg = grid_for(n + 1, 4 * kBlock, 1024);
     k_scan_partial<OffT><<<sg, kBlock, 0, st>>>(nd_new, n + 1, partial);
@@ -218,11 +219,8 @@ int reorder_graph(tier_ctx *c, const int32_t *rank, const int32_t *order, OffT *
     if (ne > 0 && n > 0)
         k_relocate<OffT><<<grid_for(ne, kSpan, 65536), kBlock, 0, st>>>((const OffT *)c->indptr, c->indices, rank,
                                                                         order, nd_new, n, ne, edg_new);
-    hipError_t e = hipGetLastError();
-    hipError_t e2 = hipStreamSynchronize(st);
-    (void)hipFree(partial);
-    TIER_HIP(c, e);
-    TIER_HIP(c, e2);
+    TIER_HIP(c, hipGetLastError());
+    TIER_HIP(c, hipStreamSynchronize(st));
     return TIER_OK;
 }
 

@@ -131,8 +131,9 @@ int tier_score_wrpr(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, in
     const int64_t n = ctx->n_nodes, ne = ctx->n_edges;
     if (n == 0) return TIER_OK;
     hipStream_t st = ctx->stream;
-    double *pulled = nullptr;
-    TIER_HIP(ctx, hipMalloc(&pulled, (size_t)n * sizeof(double)));
+    int rc = tier_ensure(ctx, (void **)&ctx->pulled, &ctx->pulled_cap, (size_t)n * sizeof(double));
+    if (rc != TIER_OK) return rc;
+    double *pulled = ctx->pulled;        // kept by the context: no allocation after the first call
     const int g = grid_for(n, kBlock, 4096);
     k_fill_f64<<<g, kBlock, 0, st>>>(score, n, 1.0 / (double)n);
     if (n_train > 0)
@@ -153,11 +154,8 @@ int tier_score_wrpr(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, in
         }
         k_damp<<<g, kBlock, 0, st>>>(pulled, n, base, damp, score);
     }
-    hipError_t e = hipGetLastError();
-    int rc = tier_sync_meta(ctx);       // also waits, so that `pulled` can be freed
-    (void)hipFree(pulled);
-    TIER_HIP(ctx, e);
-    return rc;
+    TIER_HIP(ctx, hipGetLastError());
+    return tier_sync_meta(ctx);          // waits: reports a training id outside the graph
 }
 
 }  // extern "C"

@@ -89,6 +89,11 @@ struct tier_ctx {
     int32_t *partial_bm;     // [n_slots][TIER_SCAN_BLOCKS]
     int32_t *ps_nodes;       // frontier buffers used by tier_presample
     int64_t cap_ps_nodes;
+    // scratch of the score functions and of the graph reordering, kept between calls
+    double *pulled;          // n_nodes sums of one round of tier_score_wrpr
+    size_t pulled_cap;       // bytes
+    int64_t *scan_partial;   // TIER_SCAN_BLOCKS block sums of the offsets' prefix sum (tier_reorder_graph)
+    size_t scan_partial_cap;
 };
 
 #define TIER_HIP(ctx, call)                                              \
