@@ -115,10 +115,13 @@ void tier_destroy(tier_ctx *ctx)
 {
     if (!ctx) return;
     (void)hipStreamSynchronize(ctx->stream);
-    (void)hipFree(ctx->local_idx);
-    (void)hipFree(ctx->bitmap);
-    (void)hipFree(ctx->prev);
-    (void)hipFree(ctx->summary);
+    (void)hipFree(ctx->fresh);
+    (void)hipFree(ctx->aux);
+    (void)hipFree(ctx->flag);
+    (void)hipFree(ctx->segbase);
+    (void)hipFree(ctx->table);
+    (void)hipFree(ctx->f_beg);
+    (void)hipFree(ctx->f_deg);
     (void)hipFree(ctx->slot);
     (void)hipFree(ctx->cache);
     (void)hipStreamSynchronize(ctx->gather_stream);
@@ -166,18 +169,24 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
 
     const int64_t n = c->n_nodes;
     c->n_words = (n + 31) / 32;
-    c->n_sum = (c->n_words + 31) / 32;
-    // as many mini-batch slots as fit in 8 GiB of per-node scratch (64 slots up to 32 M nodes, 18 at 111 M)
-    const int64_t per_slot = (n + c->n_words + c->n_sum + 1) * 4;     // + n_words for `prev` on graphs of up to 32 M nodes
+    c->bm_stride = (c->n_words + 31) / 32 * 32;
+    if (c->bm_stride == 0) c->bm_stride = 32;
+    c->seg_log2 = c->n_words > (1 << 20) ? 5 : 0;      // as sampler.hip's large_graph()
+    c->n_seg = (c->n_words + (1ll << c->seg_log2) - 1) >> c->seg_log2;
+    c->flag_stride = (c->n_seg + 15) / 16 * 16;
+    // as many mini-batch slots as fit in 8 GiB of per-node scratch (two bitmaps, a flag byte and a
+    // start position per segment: 0.26 - 0.41 bytes per node and slot)
+    const int64_t per_slot = c->bm_stride * 8 + c->flag_stride + c->n_seg * 4 + 64;
     int64_t slots = (8LL << 30) / per_slot;
     c->n_slots = (int)(slots < 1 ? 1 : (slots > TIER_MAX_BATCHES ? TIER_MAX_BATCHES : slots));
     const size_t S = (size_t)c->n_slots;
-    TIER_HIP(c, hipMalloc(&c->local_idx, S * (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
-    TIER_HIP(c, hipMalloc(&c->bitmap, S * (size_t)(c->n_words > 0 ? c->n_words : 1) * sizeof(uint32_t)));
-    const bool frontier_bits = c->n_words <= (1 << 20);      // as sampler.hip's two_level(): `prev` serves the smaller graphs
-    const int64_t prev_words = frontier_bits && c->n_words > 0 ? c->n_words * (int64_t)S : 1;
-    TIER_HIP(c, hipMalloc(&c->prev, (size_t)prev_words * sizeof(uint32_t)));
-    TIER_HIP(c, hipMalloc(&c->summary, S * (size_t)(c->n_sum > 0 ? c->n_sum : 1) * sizeof(uint32_t)));
+    const int64_t words = c->bm_stride * (int64_t)S;
+    const int64_t flags4 = (c->flag_stride > 0 ? c->flag_stride : 16) * (int64_t)S / 4;
+    const int64_t segs = (c->n_seg > 0 ? c->n_seg : 1) * (int64_t)S;
+    TIER_HIP(c, hipMalloc(&c->fresh, (size_t)words * sizeof(uint32_t)));
+    TIER_HIP(c, hipMalloc(&c->aux, (size_t)words * sizeof(uint32_t)));
+    TIER_HIP(c, hipMalloc(&c->flag, (size_t)flags4 * 4));
+    TIER_HIP(c, hipMalloc(&c->segbase, (size_t)segs * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->slot, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->meta, S * META_WORDS * sizeof(int64_t)));
     TIER_HIP(c, hipHostMalloc((void **)&c->meta_host, S * META_WORDS * sizeof(int64_t), hipHostMallocDefault));
@@ -186,12 +195,9 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     TIER_HIP(c, hipEventCreateWithFlags(&c->ev_place, hipEventDisableTiming));
     TIER_HIP(c, hipMalloc(&c->partial_hop, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->partial_bm, S * TIER_SCAN_BLOCKS * sizeof(int32_t)));
-    k_fill_i32<<<grid_for(n * (int64_t)S, 256, 8192), 256, 0, c->stream>>>(c->local_idx, n * (int64_t)S, -1);
-    k_fill_i32<<<grid_for(c->n_words * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->bitmap,
-                                                                                  c->n_words * (int64_t)S, 0);
-    k_fill_i32<<<grid_for(prev_words, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->prev, prev_words, 0);
-    k_fill_i32<<<grid_for(c->n_sum * (int64_t)S, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->summary,
-                                                                                c->n_sum * (int64_t)S, 0);
+    k_fill_i32<<<grid_for(words, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->fresh, words, 0);
+    k_fill_i32<<<grid_for(words, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->aux, words, 0);
+    k_fill_i32<<<grid_for(flags4, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->flag, flags4, 0);
     k_fill_i32<<<grid_for(n, 256, 8192), 256, 0, c->stream>>>(c->slot, n, -1);          // nothing placed yet
     k_fill_i32<<<1, 64, 0, c->stream>>>((int32_t *)c->gmeta, GMETA_WORDS * 2, 0);
     k_fill_i32<<<4, 256, 0, c->stream>>>((int32_t *)c->meta, (int64_t)S * META_WORDS * 2, 0);
@@ -270,6 +276,36 @@ const char *tier_strerror(int status)
 }
 
 int tier_last_hip_error(const tier_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+int tier_set_segment_words(tier_ctx *ctx, int32_t words)
+{
+    if (!ctx || (words != 1 && words != 32)) return TIER_EINVAL;
+    TIER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const int seg_log2 = words == 32 ? 5 : 0;
+    if (seg_log2 == ctx->seg_log2) return TIER_OK;
+    const int64_t n_seg = (ctx->n_words + words - 1) / words;
+    const int64_t flag_stride = (n_seg + 15) / 16 * 16;
+    const int64_t flags4 = (flag_stride > 0 ? flag_stride : 16) * (int64_t)ctx->n_slots / 4;
+    const int64_t segs = (n_seg > 0 ? n_seg : 1) * (int64_t)ctx->n_slots;
+    uint8_t *flag = nullptr;
+    int32_t *segbase = nullptr;
+    TIER_HIP(ctx, hipMalloc(&flag, (size_t)flags4 * 4));
+    hipError_t e = hipMalloc(&segbase, (size_t)segs * sizeof(int32_t));
+    if (e != hipSuccess) {
+        (void)hipFree(flag);
+        TIER_HIP(ctx, e);
+    }
+    (void)hipFree(ctx->flag);
+    (void)hipFree(ctx->segbase);
+    ctx->flag = flag;
+    ctx->segbase = segbase;
+    ctx->seg_log2 = seg_log2;
+    ctx->n_seg = n_seg;
+    ctx->flag_stride = flag_stride;
+    k_fill_i32<<<grid_for(flags4, 256, 8192), 256, 0, ctx->stream>>>((int32_t *)ctx->flag, flags4, 0);
+    TIER_HIP(ctx, hipGetLastError());
+    return TIER_OK;
+}
 
 int tier_set_gather_stream(tier_ctx *ctx, void *stream)
 {

@@ -242,8 +242,8 @@ int tier_reorder_rows(tier_ctx *ctx, const int32_t *rank, void *rows_new)
     const int64_t n = ctx->n_nodes;
     if (n == 0) return TIER_OK;
     // the first slot's bitmap (all zero between sampling calls) marks the ranks seen
-    k_check_rank_marks<<<grid_for(n, kBlock, 4096), kBlock, 0, ctx->stream>>>(rank, n, ctx->bitmap, ctx->meta);
-    k_clear_words<<<grid_for(ctx->n_words, kBlock, 4096), kBlock, 0, ctx->stream>>>(ctx->bitmap, ctx->n_words);
+    k_check_rank_marks<<<grid_for(n, kBlock, 4096), kBlock, 0, ctx->stream>>>(rank, n, ctx->fresh, ctx->meta);
+    k_clear_words<<<grid_for(ctx->n_words, kBlock, 4096), kBlock, 0, ctx->stream>>>(ctx->fresh, ctx->n_words);
     TIER_HIP(ctx, hipGetLastError());
     int rc = tier_sync_meta(ctx);
     if (rc != TIER_OK) return rc;

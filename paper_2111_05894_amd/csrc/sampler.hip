@@ -2,63 +2,76 @@
 // it (Sec. 3.1, Sec. 5.2).
 //
 // A mini-batch of ~1000 seeds is far too small to fill 256 compute units, so the
-// sampler works on up to TIER_MAX_BATCHES mini-batches side by side: every
-// kernel below is launched on a (blocks, slots) grid, blockIdx.y naming the slot
-// (one mini-batch with its own frontier, its own `local_idx` and bitmap scratch
-// and its own size bookkeeping).  One hop over the current frontiers is a short
-// chain of kernels on the context's stream; all sizes stay on the device
-// (tier_internal.h, META_*):
+// sampler works on up to TIER_MAX_BATCHES mini-batches side by side, each in a slot
+// of its own (its own frontier, its own scratch, its own size bookkeeping).  One hop
+// over the current frontiers is a short chain of kernels on the context's stream;
+// all sizes stay on the device (tier_internal.h, META_*):
 //
 //   k_hop_partial   per-block sums of min(fanout, degree) over the frontier
 //   k_hop_rowptr    offsets of every dst's edges (scan of the sums above)
 //   k_hop_sample    a group of G lanes per dst draws its neighbours: lane i owns
 //                   draw i, the Floyd collision rule is resolved with in-group
-//                   shuffles; every neighbour not yet in the frontier sets its
-//                   bit in a bitmap over all nodes
-//   k_bm_partial    popcounts of the nodes reached at this hop
-//   k_bm_emit       bitmap -> ascending list of new nodes appended to the
-//                   frontier (dedup and sort in one pass), their frontier index
-//                   recorded in local_idx[] where it is needed
-//   k_relabel       once per mini-batch, all hops: col[e] = frontier index of
-//                   the sampled neighbour (col[] held its node id until then)
-//   k_finish        takes the mini-batch's nodes out of local_idx[] and the bitmaps
+//                   shuffles; a neighbour already in the frontier gets its frontier
+//                   index at once, any other sets its bit in `fresh`, a bitmap over
+//                   all nodes, and the byte flag of the bit's segment
+//   k_bm_partial    popcounts of the flagged segments
+//   k_bm_emit       flagged segments -> ascending list of new nodes appended to the
+//                   frontier (dedup and sort in one pass)
+//   k_settle        the new nodes' adjacency offsets and degrees, listed beside the
+//                   frontier (every later hop reads them in order instead of chasing
+//                   indptr[] again), and the second half of entering them into the
+//                   frontier index
+//   k_relabel       once per mini-batch: col[e] of the neighbours that were new at
+//                   their hop
+//   k_finish        leaves the slot's scratch clean for the next mini-batch
 //
-// Two layouts of that bookkeeping, by graph size:
+// What the design is built around, measured on MI355X: an atomic of any kind and
+// scope runs at ~27 G/s for the whole chip, a random 4-byte read from HBM at ~50 G/s,
+// and a random read or plain store that stays in one XCD's 4 MB L2 at ~240 G/s.  So
+//   - every kernel maps workgroups to slots by XCD (workgroup i runs on XCD i % 8; a
+//     slot is served by one XCD only and the slots of an XCD one after the other), so
+//     that a slot's small structures live in that XCD's L2; nothing depends on this
+//     mapping for correctness;
+//   - the frontier index is an open-addressing table (node -> position in nodes[], 4
+//     bytes per cell, key checked against nodes[]) sized for the largest frontier that
+//     ever draws (a few MB at most for the usual fanouts), not an array over all nodes:
+//     membership test and index are one lookup in L2;
+//   - nodes enter the table without atomics: k_bm_emit stores into an empty home cell
+//     with a plain store, k_settle (next kernel) checks who won a contested cell and
+//     moves only the losers on, by compare-and-swap;
+//   - a dst node's work is a chain of dependent reads (offsets, neighbour id, index cell,
+//     key), and with every wave slot taken the chain's latency, not any throughput, set
+//     the pace: k_hop_sample therefore works on four dst nodes per lane group at a time,
+//     issuing each stage's reads for all four before it uses any;
+//   - the nodes reached at the last hop never enter the table (nothing is drawn from
+//     them): their frontier index is the segment's start position (written by
+//     k_bm_emit) plus the rank of their bit inside the segment;
+//   - the only atomic per sampled edge left is the bit in `fresh`, which dedups and
+//     sorts the new nodes; the flag of the segment is a plain byte store.
 //
-// Up to 32 M nodes (bitmap of up to 4 MB per slot: walking it whole is cheap and it
-// stays in the L2 caches): two bitmaps per slot, `seen` = frontier + nodes reached at
-// this hop and `prev` = the frontier before the hop.  The hop kernel asks `prev`
-// whether a neighbour is in the frontier - one bit per node instead of a 4-byte
-// local_idx[] entry, whose 128-byte line came from HBM or the last-level cache for
-// most sampled edges - and sets the bit in `seen` otherwise; `prev` does not change
-// during the hop, so the words of the hubs, which most edges lead to, stay in each
-// compute unit's own cache.  New nodes = seen ^ prev, then prev = seen.  (Asking
-// `seen` itself, to skip the atomic for neighbours already marked at this hop, was
-// slower either way: cached reads see stale zeros and the hubs' words drown in
-// atomics, device-scope reads pile up on the L2 channels of those same words.)
+// A segment is one bitmap word on graphs of up to 32 M nodes and 32 words above, so
+// the kernels that read the bitmap walk one byte per 32 or 1024 nodes and touch only
+// the words of flagged segments: their cost follows the mini-batch, not the graph.
 //
-// Above 32 M nodes: membership from local_idx[] (a bitmap of that size is no more
-// cache-friendly), the bitmap holds this hop's new nodes only and a summary bitmap
-// holds one bit per bitmap word (set by whoever sets the first bit of that word), so
-// that the kernels reading the bitmap visit only its non-zero words and their cost
-// follows the mini-batch, not the graph.
-//
-// tier_presample runs the same chain without materialising blocks (no offsets,
-// no edge ids, no relabel; on the smaller graphs no local_idx[] either) and gives
-// every node of the final frontier one access.  On the smaller graphs the slots'
-// `seen` bitmaps hold exactly those frontiers when the chain ends, and one pass adds
-// them up column by column (k_count_columns: no atomics, the nodes of the last hop
-// are never listed).  On the larger graphs the nodes reached at the last hop take an
-// atomic increment straight from the bitmap (k_bm_count, never listed either) and the
-// earlier ones from the list (k_finish): within a mini-batch the frontier nodes are
-// distinct, so only mini-batches of different slots can meet on one counter, spread
-// over all nodes - no hot spot an LDS staging could absorb.
+// tier_presample runs the same chains without materialising blocks (no offsets, no
+// edge ids, no relabel).  Up to 32 M nodes it keeps the frontier itself in two bitmaps
+// per slot (`seen` = frontier + reached at this hop, `prev` = frontier before the
+// hop; membership is one bit of `prev`, which stays in cache) and needs no index at
+// all; above, it uses the table for membership and a second bitmap `all` that
+// collects the whole frontier (the last hop marks it directly).  Either way a slot
+// ends with the bitmap of its mini-batch's final frontier, and one pass adds the
+// slots' bitmaps column by column (k_count_columns: no atomics; the nodes of the last
+// hop are never listed).  Within a mini-batch the frontier nodes are distinct, so no
+// counter is a hot spot that LDS staging could absorb.
 #include "rng.h"
 #include "tier_internal.h"
 
 namespace {
 
 constexpr int kBlock = 256;
+constexpr int kXcds = 8;             // XCDs of an MI355X; workgroup i of a launch runs on XCD i % 8
+
+enum { MODE_BLOCKS = 0, MODE_COUNT_SMALL = 1, MODE_COUNT_LARGE = 2 };
 
 // What every sampler kernel needs to find its slot's data (passed by value).
 struct wide_t {
@@ -67,18 +80,24 @@ struct wide_t {
     int32_t batch_size;
     int32_t n_slots;
     int32_t count_edges;         // != 0: add the sampled edges to META_TOTAL_EDGES (costs an atomic per block)
+    int32_t seg_log2;            // log2 of the bitmap words per segment (0 or 5)
     int64_t n_nodes;             // graph nodes
-    int64_t n_words;             // bitmap words per slot
-    int64_t n_sum;               // summary words per slot (one bit per bitmap word)
+    int64_t n_words;             // bitmap words that cover the graph
+    int64_t bm_stride;           // bitmap words per slot (n_words rounded up to whole 128-byte lines; the rest stays zero)
+    int64_t n_seg;               // segments per slot
+    int64_t flag_stride;         // bytes of flags per slot (n_seg rounded up)
     int32_t *nodes;              // slot s: nodes + s * nodes_stride
     int64_t nodes_stride;
-    int32_t *local_idx;          // [slot][n_nodes]
-    uint32_t *bitmap;            // [slot][n_words]  "seen": frontier + reached at this hop
-    uint32_t *prev;              // [slot][n_words]  the frontier before this hop
-    uint32_t *summary;           // [slot][n_sum]
-    int32_t frontier_bits;       // != 0 (graphs of up to 32 M nodes): the bitmaps hold the frontier too, see k_hop_sample
-    int32_t index_nodes;         // != 0: local_idx[] records every frontier node's index (blocks; membership on large graphs)
-    int32_t clear_bitmaps;       // != 0: k_finish zeroes the slot's two bitmaps (k_count_columns does it in counting mode)
+    uint32_t *fresh;             // [slot][bm_stride]  nodes first reached at this hop (MODE_COUNT_SMALL: `seen`)
+    uint32_t *aux;               // [slot][bm_stride]  MODE_COUNT_SMALL: `prev`; MODE_COUNT_LARGE: `all`
+    uint8_t *flag;               // [slot][flag_stride]  != 0: the segment holds a bit of `fresh`
+    int32_t *segbase;            // [slot][n_seg]    last hop of a block call: new nodes listed before the segment's first
+    uint32_t *table;             // [slot][1 << table_log2]  frontier index: position in nodes[] + 1, 0 = empty
+    int32_t table_log2;
+    int32_t pad_;
+    int64_t *beg;                // [slot][deg_stride]  indptr[node] of the frontier nodes that draw
+    int32_t *deg;                // [slot][deg_stride]  their degrees
+    int64_t deg_stride;
     int64_t *meta;               // [slot][META_WORDS]; totals and the error flag live in slot 0
     int32_t *partial_hop;        // [slot][TIER_SCAN_BLOCKS]
     int32_t *partial_bm;         // [slot][TIER_SCAN_BLOCKS]
@@ -101,28 +120,80 @@ struct relabel_t {
 
 struct slot_view {
     int32_t *nodes;
-    int32_t *local_idx;
-    uint32_t *bitmap;
-    uint32_t *prev;
-    uint32_t *summary;
+    uint32_t *fresh;
+    uint32_t *aux;
+    uint8_t *flag;
+    int32_t *segbase;
+    uint32_t *table;
+    int64_t *beg;
+    int32_t *deg;
     int64_t *meta;
     int32_t *partial_hop;
     int32_t *partial_bm;
 };
 
-__device__ inline slot_view view_of(const wide_t &w)
+// Which slot and which of the slot's gx blocks this workgroup is.  The launch has
+// 8 * gx * ceil(n_slots / 8) workgroups; workgroup f runs on XCD f % 8 and serves slot
+// (f % 8) + 8 * ((f / 8) / gx): every slot is served by one XCD, and an XCD takes its
+// slots one after the other, so the structures of one or two slots are what its L2 holds
+// at any time.  Workgroups that fall on a slot beyond n_slots have nothing to do.
+struct spot_t {
+    int slot;
+    int bx;      // block index within the slot, 0 .. gx - 1
+    int gx;
+};
+
+__device__ inline bool my_spot(const wide_t &w, int gx, spot_t &p)
 {
-    const int64_t s = blockIdx.y;
+    const unsigned f = blockIdx.x;
+    const unsigned k = f / kXcds;
+    p.slot = (int)(f % kXcds) + kXcds * (int)(k / (unsigned)gx);
+    p.bx = (int)(k % (unsigned)gx);
+    p.gx = gx;
+    return p.slot < w.n_slots;
+}
+
+__device__ inline slot_view view_of(const wide_t &w, int slot)
+{
+    const int64_t s = slot;
     slot_view v;
     v.nodes = w.nodes + s * w.nodes_stride;
-    v.local_idx = w.local_idx + s * w.n_nodes;
-    v.bitmap = w.bitmap + s * w.n_words;
-    v.prev = w.prev + s * w.n_words;
-    v.summary = w.summary + s * w.n_sum;
+    v.fresh = w.fresh + s * w.bm_stride;
+    v.aux = w.aux + s * w.bm_stride;
+    v.flag = w.flag + s * w.flag_stride;
+    v.segbase = w.segbase + s * w.n_seg;
+    v.table = w.table + (s << w.table_log2);
+    v.beg = w.beg + s * w.deg_stride;
+    v.deg = w.deg + s * w.deg_stride;
     v.meta = w.meta + s * META_WORDS;
     v.partial_hop = w.partial_hop + s * TIER_SCAN_BLOCKS;
     v.partial_bm = w.partial_bm + s * TIER_SCAN_BLOCKS;
     return v;
+}
+
+// ---- frontier index: open addressing, linear probing, key = nodes[cell - 1] --------------------
+
+__device__ inline uint32_t home_of(uint32_t node, int table_log2) { return (node * 0x9E3779B1u) >> (32 - table_log2); }
+
+// Position of `node` in nodes[], or -1.  The table holds at most half as many nodes as cells.
+__device__ inline int32_t index_of(const uint32_t *__restrict__ table, int table_log2,
+                                   const int32_t *__restrict__ nodes, int32_t node)
+{
+    const uint32_t mask = (1u << table_log2) - 1u;
+    uint32_t h = home_of((uint32_t)node, table_log2);
+    for (;;) {
+        const uint32_t cell = table[h];
+        if (cell == 0u) return -1;
+        if (nodes[cell - 1u] == node) return (int32_t)(cell - 1u);
+        h = (h + 1u) & mask;
+    }
+}
+
+// Enter nodes[pos] with compare-and-swap (the few seeds; the losers of k_settle).
+__device__ inline void index_insert_cas(uint32_t *__restrict__ table, int table_log2, uint32_t h, uint32_t pos)
+{
+    const uint32_t mask = (1u << table_log2) - 1u;
+    while (atomicCAS(&table[h], 0u, pos + 1u) != 0u) h = (h + 1u) & mask;
 }
 
 __device__ inline int wave_incl_scan(int x)
@@ -169,37 +240,40 @@ __device__ inline int block_excl_scan(int x, int &total, int *s_wave)
     return base + incl - x;
 }
 
-// Contiguous share of [0, n) for this block: a multiple of kBlock items.
-__device__ inline void block_range(int64_t n, int64_t &lo, int64_t &hi)
+// Contiguous share of [0, n) for block p.bx of p.gx: a multiple of kBlock items.
+__device__ inline void block_range(const spot_t &p, int64_t n, int64_t &lo, int64_t &hi)
 {
-    int64_t chunk = (n + gridDim.x - 1) / gridDim.x;
+    int64_t chunk = (n + p.gx - 1) / p.gx;
     chunk = (chunk + kBlock - 1) / kBlock * kBlock;
-    lo = (int64_t)blockIdx.x * chunk;
+    lo = (int64_t)p.bx * chunk;
     if (lo > n) lo = n;
     hi = lo + chunk;
     if (hi > n) hi = n;
 }
 
-// Sum of partial[0 .. blockIdx.x) and of all partials (gridDim.x <= TIER_SCAN_BLOCKS).
-__device__ inline void partial_prefix(const int32_t *partial, int &before, int &all, int *s_wave)
+// Sum of partial[0 .. p.bx) and of all p.gx partials (p.gx <= TIER_SCAN_BLOCKS).
+__device__ inline void partial_prefix(const spot_t &p, const int32_t *partial, int &before, int &all, int *s_wave)
 {
     int b = 0, a = 0;
-    for (int i = threadIdx.x; i < (int)gridDim.x; i += kBlock) {
-        int p = partial[i];
-        a += p;
-        b += (i < (int)blockIdx.x) ? p : 0;
+    for (int i = threadIdx.x; i < p.gx; i += kBlock) {
+        int q = partial[i];
+        a += q;
+        b += (i < p.bx) ? q : 0;
     }
     before = block_sum(b, s_wave);
     all = block_sum(a, s_wave);
 }
 
-__global__ void k_init_seeds(wide_t w)
+template <int MODE, typename OffT>
+__global__ __launch_bounds__(kBlock) void k_init_seeds(wide_t w, int gx, const OffT *__restrict__ indptr)
 {
-    const slot_view v = view_of(w);
-    const int64_t first = (int64_t)blockIdx.y * w.batch_size;
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int64_t first = (int64_t)p.slot * w.batch_size;
     int64_t n = w.n_seeds_total - first;
     n = n < 0 ? 0 : (n > w.batch_size ? w.batch_size : n);
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = (int64_t)p.bx * kBlock + threadIdx.x;
     if (i == 0) v.meta[META_NFRONT] = n;
     if (i < n) {
         int32_t u = w.seeds[first + i];
@@ -208,46 +282,52 @@ __global__ void k_init_seeds(wide_t w)
             u = 0;                                   // keep every later index in range
         }
         v.nodes[i] = u;
-        if (w.index_nodes) v.local_idx[u] = (int32_t)i;
-        if (w.frontier_bits) {
-            atomicOr(&v.bitmap[(uint32_t)u >> 5], 1u << (u & 31));
-            atomicOr(&v.prev[(uint32_t)u >> 5], 1u << (u & 31));
+        const OffT first_edge = indptr[u];
+        v.beg[i] = (int64_t)first_edge;
+        v.deg[i] = (int32_t)(indptr[u + 1] - first_edge);
+        const uint32_t word = (uint32_t)u >> 5, bit = 1u << (u & 31);
+        if (MODE == MODE_COUNT_SMALL) {
+            atomicOr(&v.fresh[word], bit);
+            atomicOr(&v.aux[word], bit);
+        } else {
+            index_insert_cas(v.table, w.table_log2, home_of((uint32_t)u, w.table_log2), (uint32_t)i);
+            if (MODE == MODE_COUNT_LARGE) atomicOr(&v.aux[word], bit);
         }
     }
 }
 
-template <typename OffT>
-__global__ __launch_bounds__(kBlock) void k_hop_partial(wide_t w, const OffT *__restrict__ indptr, int layer, int k)
+__global__ __launch_bounds__(kBlock) void k_hop_partial(wide_t w, int gx, int layer, int k)
 {
     __shared__ int s_wave[kBlock / 64];
-    const slot_view v = view_of(w);
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
     int64_t lo, hi;
-    block_range(v.meta[META_NFRONT + layer], lo, hi);
+    block_range(p, v.meta[META_NFRONT + layer], lo, hi);
     int sum = 0;
     for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
-        int32_t u = v.nodes[i];
-        int64_t d = (int64_t)(indptr[u + 1] - indptr[u]);
-        sum += d < k ? (int)d : k;
+        const int d = v.deg[i];
+        sum += d < k ? d : k;
     }
     int tot = block_sum(sum, s_wave);
-    if (threadIdx.x == 0) v.partial_hop[blockIdx.x] = tot;
+    if (threadIdx.x == 0) v.partial_hop[p.bx] = tot;
 }
 
 // Offsets of every dst's edges: row_ptr[i] = sum of min(k, degree) over dst 0..i-1.
-// Same grid as k_hop_partial; block b owns the same contiguous share of the frontier.
-template <typename OffT>
-__global__ __launch_bounds__(kBlock) void k_hop_rowptr(wide_t w, const OffT *__restrict__ indptr, int layer, int k,
-                                                       layer_out_t o)
+// Same grid as k_hop_partial; a block owns the same contiguous share of the frontier.
+__global__ __launch_bounds__(kBlock) void k_hop_rowptr(wide_t w, int gx, int layer, int k, layer_out_t o)
 {
     __shared__ int s_wave[kBlock / 64];
-    const slot_view v = view_of(w);
-    int32_t *row_ptr = o.row_ptr + (int64_t)blockIdx.y * o.row_ptr_stride;
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    int32_t *row_ptr = o.row_ptr + (int64_t)p.slot * o.row_ptr_stride;
     const int64_t n = v.meta[META_NFRONT + layer];
     int64_t lo, hi;
-    block_range(n, lo, hi);
+    block_range(p, n, lo, hi);
     int carry, all;
-    partial_prefix(v.partial_hop, carry, all, s_wave);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    partial_prefix(p, v.partial_hop, carry, all, s_wave);
+    if (p.bx == 0 && threadIdx.x == 0) {
         v.meta[META_NEDGES + layer] = all;
         row_ptr[n] = all;
     }
@@ -255,9 +335,8 @@ __global__ __launch_bounds__(kBlock) void k_hop_rowptr(wide_t w, const OffT *__r
         const int64_t i = tile + threadIdx.x;
         int cnt = 0;
         if (i < hi) {
-            int32_t u = v.nodes[i];
-            int64_t d = (int64_t)(indptr[u + 1] - indptr[u]);
-            cnt = d < k ? (int)d : k;
+            const int d = v.deg[i];
+            cnt = d < k ? d : k;
         }
         int tot;
         int rp = carry + block_excl_scan(cnt, tot, s_wave);
@@ -266,237 +345,399 @@ __global__ __launch_bounds__(kBlock) void k_hop_rowptr(wide_t w, const OffT *__r
     }
 }
 
-// One dst node, handled by a group of G consecutive lanes (G a power of two, k <= G).
-// d <= k: all neighbours in adjacency order.  d > k: Floyd's subset algorithm, draw i
-// on lane i: t_i uniform in [0, d-k+i]; position = t_i unless an earlier draw already
-// took t_i, then d-k+i.
-template <int G, bool BLOCKS, bool TWO_LEVEL, typename OffT>
-__device__ inline void sample_one(int lane, int32_t v, OffT beg, int32_t d, int k, int layer, uint32_t key0,
-                                  uint32_t key1, const int32_t *__restrict__ indices,
-                                  const int32_t *__restrict__ local_idx, uint32_t *__restrict__ seen,
-                                  const uint32_t *__restrict__ prev, uint32_t *__restrict__ summary, int64_t *__restrict__ eid,
-                                  int32_t *__restrict__ col, int32_t rp)
-{
-    const bool draw = d > k;
-    const int cnt = draw ? k : d;
-    int32_t pos = lane;
-    const int32_t j = d - k + lane;
-    int32_t t = -1;
-    if (draw && lane < k) {
-        uint64_t r = tier::philox_r64(key0, key1, (uint32_t)v, (uint32_t)lane, (uint32_t)layer, tier::kTagNeighbour);
-        t = (int32_t)__umul64hi(r, (uint64_t)(uint32_t)(j + 1));
-        pos = t;
-    }
-    if (draw) {
-        bool taken = false;
-        for (int i = 0; i + 1 < k; ++i) {
-            int32_t p = __shfl(pos, i, G);          // final position of draw i
-            taken = taken || (lane > i && t == p);
-            if (lane == i + 1) pos = taken ? j : t;
-        }
-    }
-    if (lane < cnt) {
-        OffT e = beg + (OffT)pos;
-        int32_t u = indices[e];
-        if (BLOCKS) {
-            eid[rp + lane] = (int64_t)e;
-            col[rp + lane] = u;                     // node id for now; k_relabel turns it into an index
-        }
-        const uint32_t word = (uint32_t)u >> 5, bit = 1u << (u & 31);
-        if (TWO_LEVEL) {
-            // large graph: membership from local_idx[], `seen` holds this hop's new nodes only
-            if (local_idx[u] < 0 && atomicOr(&seen[word], bit) == 0u)       // first bit of this word
-                atomicOr(&summary[word >> 5], 1u << (word & 31));
-        } else {
-            // one bit per node: in the frontier already?  `prev` does not change during the hop, so
-            // the words of the hubs, which most edges lead to, stay in the compute unit's own cache
-            if (!(prev[word] & bit)) atomicOr(&seen[word], bit);
-        }
-    }
-}
+constexpr int kAtOnce = 4;       // dst nodes a lane group works on at a time
 
-// One group of G lanes per dst node, all dst nodes of the frontier side by side.
-template <typename OffT, int G, bool BLOCKS, bool TWO_LEVEL>
-__global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, const OffT *__restrict__ indptr,
-                                                       const int32_t *__restrict__ indices, int layer, int k,
-                                                       layer_out_t o)
+// One group of G consecutive lanes per dst node (G a power of two, k <= G), all dst nodes of
+// the frontier side by side.  d <= k: all neighbours in adjacency order.  d > k: Floyd's subset
+// algorithm, draw i on lane i: t_i uniform in [0, d-k+i]; position = t_i unless an earlier draw
+// already took t_i, then d-k+i.  A group takes kAtOnce dst nodes at a time and goes through them
+// stage by stage, so that the reads of one stage are in flight together.
+template <int G, int MODE>
+__global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const int32_t *__restrict__ indices, int layer,
+                                                       int k, int last, layer_out_t o)
 {
     __shared__ int s_wave[kBlock / 64];
     constexpr int kGroups = kBlock / G;
-    const slot_view v = view_of(w);
-    const int s = blockIdx.y;
-    const int32_t *row_ptr = BLOCKS ? o.row_ptr + (int64_t)s * o.row_ptr_stride : nullptr;
-    int32_t *col = BLOCKS ? o.col + (int64_t)s * o.edge_stride : nullptr;
-    int64_t *eid = BLOCKS ? o.eid + (int64_t)s * o.edge_stride : nullptr;
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int s = p.slot;
+    const int32_t *row_ptr = MODE == MODE_BLOCKS ? o.row_ptr + (int64_t)s * o.row_ptr_stride : nullptr;
+    int32_t *col = MODE == MODE_BLOCKS ? o.col + (int64_t)s * o.edge_stride : nullptr;
+    int64_t *eid = MODE == MODE_BLOCKS ? o.eid + (int64_t)s * o.edge_stride : nullptr;
     const uint32_t key0 = w.key0[s], key1 = w.key1[s];
     const int lane = threadIdx.x % G;
     const int64_t n = v.meta[META_NFRONT + layer];
-    const int64_t stride = (int64_t)gridDim.x * kGroups;
+    const int64_t sweep = (int64_t)gx * kGroups;                  // dst nodes all the slot's groups cover side by side
+    const uint32_t mask = (1u << w.table_log2) - 1u;
     int edges = 0;
-    for (int64_t i = (int64_t)blockIdx.x * kGroups + threadIdx.x / G; i < n; i += stride) {
-        const int32_t u = v.nodes[i];
-        const OffT beg = indptr[u];
-        const int32_t d = (int32_t)(indptr[u + 1] - beg);
-        int32_t rp = 0;
-        if (BLOCKS) rp = row_ptr[i];
-        else if (w.count_edges && lane == 0) edges += d < k ? d : k;
-        sample_one<G, BLOCKS, TWO_LEVEL, OffT>(lane, u, beg, d, k, layer, key0, key1, indices, v.local_idx, v.bitmap, v.prev, v.summary,
-                                    eid, col, rp);
+    for (int64_t i0 = (int64_t)p.bx * kGroups + threadIdx.x / G; i0 < n; i0 += sweep * kAtOnce) {
+        // stage 1: the dst nodes, their offsets and degrees (listed by k_init_seeds / k_settle)
+        int32_t node[kAtOnce], d[kAtOnce], rp[kAtOnce];
+        int64_t beg[kAtOnce];
+#pragma unroll
+        for (int j = 0; j < kAtOnce; ++j) {
+            const int64_t i = i0 + j * sweep;
+            const bool there = i < n;
+            node[j] = there ? v.nodes[i] : 0;
+            beg[j] = there ? v.beg[i] : 0;
+            d[j] = there ? v.deg[i] : 0;
+            rp[j] = (MODE == MODE_BLOCKS && there) ? row_ptr[i] : 0;
+        }
+        // stage 2: positions in the adjacency lists
+        int32_t pos[kAtOnce];
+#pragma unroll
+        for (int j = 0; j < kAtOnce; ++j) {
+            const bool draw = d[j] > k;
+            pos[j] = lane;
+            const int32_t top = d[j] - k + lane;
+            int32_t t = -1;
+            if (draw && lane < k) {
+                uint64_t r = tier::philox_r64(key0, key1, (uint32_t)node[j], (uint32_t)lane, (uint32_t)layer, tier::kTagNeighbour);
+                t = (int32_t)__umul64hi(r, (uint64_t)(uint32_t)(top + 1));
+                pos[j] = t;
+            }
+            if (draw) {
+                bool taken = false;
+                for (int q = 0; q + 1 < k; ++q) {
+                    int32_t f = __shfl(pos[j], q, G);          // final position of draw q
+                    taken = taken || (lane > q && t == f);
+                    if (lane == q + 1) pos[j] = taken ? top : t;
+                }
+            }
+            if (MODE != MODE_BLOCKS && w.count_edges && lane == 0) edges += d[j] < k ? d[j] : k;
+        }
+        // stage 3: the neighbours
+        bool take[kAtOnce];
+        int32_t u[kAtOnce];
+#pragma unroll
+        for (int j = 0; j < kAtOnce; ++j) {
+            take[j] = lane < (d[j] < k ? d[j] : k);
+            u[j] = take[j] ? indices[beg[j] + pos[j]] : 0;
+        }
+        if (MODE == MODE_COUNT_SMALL) {
+            // one bit per node: in the frontier already?  `prev` does not change during the hop, so
+            // the words of the hubs, which most edges lead to, stay in the compute unit's own cache
+            uint32_t old[kAtOnce];
+#pragma unroll
+            for (int j = 0; j < kAtOnce; ++j) old[j] = take[j] ? v.aux[(uint32_t)u[j] >> 5] : 0xffffffffu;
+#pragma unroll
+            for (int j = 0; j < kAtOnce; ++j) {
+                const uint32_t bit = 1u << (u[j] & 31);
+                if (!(old[j] & bit)) atomicOr(&v.fresh[(uint32_t)u[j] >> 5], bit);
+            }
+            continue;
+        }
+        // stage 4: in the frontier already?  home cell of the index, then the key it points to
+        uint32_t h[kAtOnce], cell[kAtOnce];
+#pragma unroll
+        for (int j = 0; j < kAtOnce; ++j) {
+            h[j] = home_of((uint32_t)u[j], w.table_log2);
+            cell[j] = take[j] ? v.table[h[j]] : 0u;
+        }
+        int32_t key[kAtOnce];
+#pragma unroll
+        for (int j = 0; j < kAtOnce; ++j) key[j] = cell[j] ? v.nodes[cell[j] - 1u] : -1;
+        // stage 5: results
+#pragma unroll
+        for (int j = 0; j < kAtOnce; ++j) {
+            if (!take[j]) continue;
+            int32_t at = -1;
+            if (cell[j]) {
+                at = (int32_t)(cell[j] - 1u);
+                if (key[j] != u[j]) {                            // another node's cell: walk on (rare)
+                    uint32_t hh = h[j];
+                    for (;;) {
+                        hh = (hh + 1u) & mask;
+                        const uint32_t c2 = v.table[hh];
+                        if (c2 == 0u) { at = -1; break; }
+                        if (v.nodes[c2 - 1u] == u[j]) { at = (int32_t)(c2 - 1u); break; }
+                    }
+                }
+            }
+            if (MODE == MODE_BLOCKS) {
+                eid[rp[j] + lane] = beg[j] + pos[j];
+                col[rp[j] + lane] = at >= 0 ? at : ~u[j];        // negative: new at this hop, k_relabel finds its place
+            }
+            if (at < 0) {
+                const uint32_t word = (uint32_t)u[j] >> 5, bit = 1u << (u[j] & 31);
+                if (MODE == MODE_COUNT_LARGE && last) {
+                    atomicOr(&v.aux[word], bit);                 // nobody lists the last hop's nodes: straight into `all`
+                } else {
+                    atomicOr(&v.fresh[word], bit);
+                    v.flag[word >> w.seg_log2] = 1;
+                }
+            }
+        }
     }
-    if (!BLOCKS && w.count_edges) {
+    if (MODE != MODE_BLOCKS && w.count_edges) {
         int tot = block_sum(edges, s_wave);
         if (threadIdx.x == 0 && tot)
             atomicAdd((unsigned long long *)&w.meta[META_TOTAL_EDGES], (unsigned long long)tot);
     }
 }
 
-// Each thread owns one summary word = 32 bitmap words = 1024 node ids.
-__global__ __launch_bounds__(kBlock) void k_bm_partial(wide_t w)
+// ---- walking the flagged segments ---------------------------------------------------------------
+// A block takes its share of the segments 256 at a time: thread t reads the flag of segment
+// tile + t (consecutive bytes), the flagged ones are compacted, in order, into a list in LDS.
+// With one word per segment the thread then simply handles its own word.  With 32 words per
+// segment (one 128-byte line) a thread per segment would have every lane of a load on a
+// different line and a quarter of the bytes in flight that HBM needs; instead a group of 8
+// lanes takes one listed segment at a time, each lane 16 bytes of the line.
+constexpr int kSegTile = kBlock;
+constexpr int kSegGroups = kBlock / 8;
+
+__device__ inline int popc4(const uint4 &x) { return __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w); }
+
+// Sum of x over the 8 lanes of a group, returned to every lane.
+__device__ inline int group8_sum(int x)
 {
-    __shared__ int s_wave[kBlock / 64];
-    const slot_view v = view_of(w);
-    int64_t lo, hi;
-    block_range(w.n_sum, lo, hi);
-    int sum = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
-        uint32_t live = v.summary[i];
-        while (live) {
-            int j = __ffs(live) - 1;
-            live &= live - 1;
-            sum += __popc(v.bitmap[i * 32 + j]);
-        }
-    }
-    int tot = block_sum(sum, s_wave);
-    if (threadIdx.x == 0) v.partial_bm[blockIdx.x] = tot;
+    x += __shfl_xor(x, 4, 8);
+    x += __shfl_xor(x, 2, 8);
+    x += __shfl_xor(x, 1, 8);
+    return x;
 }
 
-__global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int layer)
+// Exclusive prefix of x over the 8 lanes of a group.
+__device__ inline int group8_excl_scan(int x)
+{
+    const int l = threadIdx.x & 7;
+    int incl = x;
+#pragma unroll
+    for (int d = 1; d < 8; d <<= 1) {
+        int y = __shfl_up(incl, d, 8);
+        if (l >= d) incl += y;
+    }
+    return incl - x;
+}
+
+// Popcounts of the flagged segments: their sum per block (for the scan over blocks) and, with 32
+// words per segment, each segment's own count in segbase[] (k_bm_emit reads it back, so that it
+// fetches every line only once).
+__global__ __launch_bounds__(kBlock) void k_bm_partial(wide_t w, int gx)
 {
     __shared__ int s_wave[kBlock / 64];
-    const slot_view v = view_of(w);
+    __shared__ int s_list[kSegTile];
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
     int64_t lo, hi;
-    block_range(w.n_sum, lo, hi);
-    int carry, all;
-    partial_prefix(v.partial_bm, carry, all, s_wave);
-    const int64_t base = v.meta[META_NFRONT + layer];
-    if (blockIdx.x == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all;
-    for (int64_t tile = lo; tile < hi; tile += kBlock) {
-        const int64_t i = tile + threadIdx.x;
-        const uint32_t live0 = i < hi ? v.summary[i] : 0u;
-        int cnt = 0;
-        for (uint32_t live = live0; live;) {
-            int j = __ffs(live) - 1;
-            live &= live - 1;
-            cnt += __popc(v.bitmap[i * 32 + j]);
-        }
-        int tot;
-        int64_t pos = base + carry + block_excl_scan(cnt, tot, s_wave);
-        carry += tot;
-        if (live0) {
-            v.summary[i] = 0u;
-            for (uint32_t live = live0; live;) {
-                int j = __ffs(live) - 1;
-                live &= live - 1;
-                const int64_t word = i * 32 + j;
-                uint32_t bits = v.bitmap[word];
-                v.bitmap[word] = 0u;
-                while (bits) {
-                    int b = __ffs(bits) - 1;
-                    bits &= bits - 1;
-                    int32_t u = (int32_t)(word * 32 + b);
-                    v.nodes[pos] = u;
-                    v.local_idx[u] = (int32_t)pos;
-                    ++pos;
+    block_range(p, w.n_seg, lo, hi);
+    int sum = 0;
+    if (w.seg_log2 == 0) {
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock)
+            if (v.flag[i]) sum += __popc(v.fresh[i]);
+    } else {
+        const int g = threadIdx.x >> 3, lane8 = threadIdx.x & 7;
+        const uint4 *lines = (const uint4 *)v.fresh;             // a slot's bitmap is whole lines
+        for (int64_t tile = lo; tile < hi; tile += kSegTile) {
+            const int64_t i = tile + threadIdx.x;
+            const int f = (i < hi && v.flag[i] != 0) ? 1 : 0;
+            int n_f;
+            const int at = block_excl_scan(f, n_f, s_wave);
+            if (f) s_list[at] = threadIdx.x;
+            __syncthreads();
+            for (int q = g; q < n_f; q += kSegGroups) {
+                const int64_t seg = tile + s_list[q];
+                const int c = group8_sum(popc4(lines[seg * 8 + lane8]));
+                if (lane8 == 0) {
+                    v.segbase[seg] = c;
+                    sum += c;
                 }
             }
+            __syncthreads();
+        }
+    }
+    int tot = block_sum(sum, s_wave);
+    if (threadIdx.x == 0) v.partial_bm[p.bx] = tot;
+}
+
+// The new nodes of one bitmap word, ascending, to nodes[pos ..); keep == 0: each also enters the
+// frontier index (first half: a plain store into an empty home cell).
+__device__ inline int64_t emit_word(const slot_view &v, int table_log2, int64_t word, uint32_t bits, int64_t pos, int keep)
+{
+    while (bits) {
+        const int b = __ffs(bits) - 1;
+        bits &= bits - 1;
+        const int32_t u = (int32_t)(word * 32 + b);
+        v.nodes[pos] = u;
+        if (!keep) {
+            const uint32_t h = home_of((uint32_t)u, table_log2);
+            if (v.table[h] == 0u) v.table[h] = (uint32_t)pos + 1u;      // may lose to another store: k_settle
+        }
+        ++pos;
+    }
+    return pos;
+}
+
+// The nodes reached at hop `layer`, ascending, appended to the frontier.  keep == 0: they will
+// draw at the next hop, so they enter the frontier index (k_settle settles contested cells)
+// and the segment's bits and flag are cleared for the next hop (MODE_COUNT_LARGE: the bits move
+// on into `all`).  keep != 0 (last hop of a block call): nothing draws from them; the segment's
+// start position is recorded for k_relabel and the bits stay until k_finish.
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer, int keep)
+{
+    __shared__ int s_wave[kBlock / 64];
+    __shared__ int s_list[kSegTile];
+    __shared__ int s_before[kSegTile];
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    int64_t lo, hi;
+    block_range(p, w.n_seg, lo, hi);
+    int carry, all;
+    partial_prefix(p, v.partial_bm, carry, all, s_wave);
+    const int64_t base = v.meta[META_NFRONT + layer];
+    if (p.bx == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all;
+    if (w.seg_log2 == 0) {
+        for (int64_t tile = lo; tile < hi; tile += kBlock) {
+            const int64_t i = tile + threadIdx.x;
+            const bool live = i < hi && v.flag[i] != 0;
+            const uint32_t bits = live ? v.fresh[i] : 0u;
+            int tot;
+            const int before = carry + block_excl_scan(__popc(bits), tot, s_wave);
+            carry += tot;
+            if (live) {
+                if (keep) {
+                    v.segbase[i] = before;
+                } else {
+                    v.flag[i] = 0;
+                    v.fresh[i] = 0u;
+                    if (MODE == MODE_COUNT_LARGE) v.aux[i] |= bits;      // this thread alone owns the word here
+                }
+                emit_word(v, w.table_log2, i, bits, base + before, keep);
+            }
+        }
+        return;
+    }
+    const int g = threadIdx.x >> 3, lane8 = threadIdx.x & 7;
+    uint4 *lines = (uint4 *)v.fresh;                             // a slot's bitmap is whole lines
+    uint4 *lines_all = (uint4 *)v.aux;
+    for (int64_t tile = lo; tile < hi; tile += kSegTile) {
+        // one scan gives both the place of a flagged segment in the list (high bits) and the number of
+        // new nodes before it (low bits: a tile holds at most 2^18 nodes)
+        const int64_t i = tile + threadIdx.x;
+        const bool live = i < hi && v.flag[i] != 0;
+        const int x = live ? ((1 << 20) | v.segbase[i]) : 0;      // k_bm_partial left the segment's count there
+        int tot;
+        const int ex = block_excl_scan(x, tot, s_wave);
+        if (live) {
+            s_list[ex >> 20] = threadIdx.x;
+            s_before[ex >> 20] = carry + (ex & 0xfffff);
+        }
+        __syncthreads();
+        const int n_f = tot >> 20;
+        for (int q = g; q < n_f; q += kSegGroups) {
+            const int64_t seg = tile + s_list[q];
+            const uint4 piece = lines[seg * 8 + lane8];
+            const int before = s_before[q];
+            const int ahead = group8_excl_scan(popc4(piece));
+            if (lane8 == 0) {
+                if (keep) v.segbase[seg] = before;
+                else v.flag[seg] = 0;
+            }
+            if (piece.x | piece.y | piece.z | piece.w) {
+                if (!keep) {
+                    lines[seg * 8 + lane8] = make_uint4(0u, 0u, 0u, 0u);
+                    if (MODE == MODE_COUNT_LARGE) {                      // this lane alone owns the piece here
+                        uint4 a = lines_all[seg * 8 + lane8];
+                        a.x |= piece.x; a.y |= piece.y; a.z |= piece.z; a.w |= piece.w;
+                        lines_all[seg * 8 + lane8] = a;
+                    }
+                }
+                const int64_t word = (seg << 5) + lane8 * 4;
+                int64_t pos = base + before + ahead;
+                pos = emit_word(v, w.table_log2, word, piece.x, pos, keep);
+                pos = emit_word(v, w.table_log2, word + 1, piece.y, pos, keep);
+                pos = emit_word(v, w.table_log2, word + 2, piece.z, pos, keep);
+                emit_word(v, w.table_log2, word + 3, piece.w, pos, keep);
+            }
+        }
+        carry += tot & 0xfffff;
+        __syncthreads();
+    }
+}
+
+// The frontier positions [n_layer, n_layer+1) that k_bm_emit (or k_bm_emit_flat) has just listed:
+// their adjacency offsets and degrees go beside them, and (MODE with an index) a node whose home
+// cell holds another node's position - an older entry, or the winner of this hop's plain stores -
+// takes the next empty cell by compare-and-swap.  Cells never empty again within a mini-batch, so
+// every node stays reachable from its home cell without a gap.
+template <int MODE, typename OffT>
+__global__ __launch_bounds__(kBlock) void k_settle(wide_t w, int gx, const OffT *__restrict__ indptr, int layer)
+{
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int64_t lo = v.meta[META_NFRONT + layer], hi = v.meta[META_NFRONT + layer + 1];
+    const uint32_t mask = (1u << w.table_log2) - 1u;
+    for (int64_t pos = lo + (int64_t)p.bx * kBlock + threadIdx.x; pos < hi; pos += (int64_t)gx * kBlock) {
+        const int32_t u = v.nodes[pos];
+        const OffT first_edge = indptr[u];
+        v.beg[pos] = (int64_t)first_edge;
+        v.deg[pos] = (int32_t)(indptr[u + 1] - first_edge);
+        if (MODE != MODE_COUNT_SMALL) {
+            const uint32_t h = home_of((uint32_t)u, w.table_log2);
+            if (v.table[h] != (uint32_t)pos + 1u) index_insert_cas(v.table, w.table_log2, (h + 1u) & mask, (uint32_t)pos);
         }
     }
 }
 
-// Flat variant for graphs whose whole bitmap is cheap to walk: every thread owns one
-// bitmap word, no summary is kept.
-__global__ __launch_bounds__(kBlock) void k_bm_partial_flat(wide_t w)
+// Flat variant for access counting on graphs whose whole bitmap is cheap to walk: every thread
+// owns one bitmap word; new = seen ^ prev, then prev = seen.
+__global__ __launch_bounds__(kBlock) void k_bm_partial_flat(wide_t w, int gx)
 {
     __shared__ int s_wave[kBlock / 64];
-    const slot_view v = view_of(w);
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
     int64_t lo, hi;
-    block_range(w.n_words, lo, hi);
+    block_range(p, w.n_words, lo, hi);
     int sum = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) sum += __popc(v.bitmap[i] ^ v.prev[i]);
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) sum += __popc(v.fresh[i] ^ v.aux[i]);
     int tot = block_sum(sum, s_wave);
-    if (threadIdx.x == 0) v.partial_bm[blockIdx.x] = tot;
+    if (threadIdx.x == 0) v.partial_bm[p.bx] = tot;
 }
 
-__global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int layer)
+__global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int gx, int layer)
 {
     __shared__ int s_wave[kBlock / 64];
-    const slot_view v = view_of(w);
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
     int64_t lo, hi;
-    block_range(w.n_words, lo, hi);
+    block_range(p, w.n_words, lo, hi);
     int carry, all;
-    partial_prefix(v.partial_bm, carry, all, s_wave);
+    partial_prefix(p, v.partial_bm, carry, all, s_wave);
     const int64_t base = v.meta[META_NFRONT + layer];
-    if (blockIdx.x == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all;
+    if (p.bx == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all;
     for (int64_t tile = lo; tile < hi; tile += kBlock) {
         const int64_t i = tile + threadIdx.x;
-        const uint32_t cur = i < hi ? v.bitmap[i] : 0u;
-        uint32_t bits = i < hi ? cur ^ v.prev[i] : 0u;
+        const uint32_t cur = i < hi ? v.fresh[i] : 0u;
+        uint32_t bits = i < hi ? cur ^ v.aux[i] : 0u;
         int tot;
         int64_t pos = base + carry + block_excl_scan(__popc(bits), tot, s_wave);
         carry += tot;
         if (bits) {
-            v.prev[i] = cur;
+            v.aux[i] = cur;
             while (bits) {
                 int b = __ffs(bits) - 1;
                 bits &= bits - 1;
-                int32_t u = (int32_t)(i * 32 + b);
-                v.nodes[pos] = u;
-                if (w.index_nodes) v.local_idx[u] = (int32_t)pos;
+                v.nodes[pos] = (int32_t)(i * 32 + b);
                 ++pos;
             }
         }
     }
 }
 
-// Access counting on the larger graphs, last hop: the nodes reached there are neither listed
-// nor indexed (no further hop, no relabelling), each takes its one access straight from the
-// bitmap; k_finish counts the listed ones.
-__global__ __launch_bounds__(kBlock) void k_bm_count(wide_t w, uint32_t *__restrict__ counts)
-{
-    __shared__ int s_wave[kBlock / 64];
-    const slot_view v = view_of(w);
-    int64_t lo, hi;
-    block_range(w.n_sum, lo, hi);
-    int sum = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) {
-        uint32_t live = v.summary[i];
-        if (live) v.summary[i] = 0u;
-        while (live) {
-            int j = __ffs(live) - 1;
-            live &= live - 1;
-            const int64_t word = i * 32 + j;
-            uint32_t bits = v.bitmap[word];
-            v.bitmap[word] = 0u;
-            sum += __popc(bits);
-            while (bits) {
-                int b = __ffs(bits) - 1;
-                bits &= bits - 1;
-                atomicAdd(&counts[word * 32 + b], 1u);
-            }
-        }
-    }
-    const int tot = block_sum(sum, s_wave);
-    if (threadIdx.x == 0 && tot)
-        atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)tot);
-}
-
-// Counting mode on graphs of up to 32 M nodes, end of a chain: `seen` of a slot now holds the
-// whole final frontier of its mini-batch, so counts[v] grows by the number of slots whose bit
-// v is set.  One thread owns one bitmap word position = 32 counters across all slots: it adds
-// the slots' words bit-sliced (five planes hold sums up to 31; a flush every 31 slots), updates
-// its counters without atomics (no other thread of this kernel touches them, and kernels on
-// the stream run one after the other) and clears both bitmaps.
-__global__ __launch_bounds__(kBlock) void k_count_columns(wide_t w, uint32_t *__restrict__ counts)
+// Access counting, end of a chain: one bitmap of every slot now holds the whole final frontier
+// of its mini-batch (`seen` on the smaller graphs, `all` above), so counts[v] grows by the
+// number of slots whose bit v is set.  One thread owns one bitmap word position = 32 counters
+// across all slots: it adds the slots' words bit-sliced (five planes hold sums up to 31; a flush
+// every 31 slots), updates its counters without atomics (no other thread of this kernel touches
+// them, and kernels on the stream run one after the other) and clears the bitmaps.
+__global__ __launch_bounds__(kBlock) void k_count_columns(wide_t w, int large, uint32_t *__restrict__ counts)
 {
     __shared__ int s_wave[kBlock / 64];
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -517,23 +758,29 @@ __global__ __launch_bounds__(kBlock) void k_count_columns(wide_t w, uint32_t *__
                 }
             }
 #pragma unroll
-            for (int p = 0; p < 5; ++p) plane[p] = 0u;
+            for (int q = 0; q < 5; ++q) plane[q] = 0u;
             held = 0;
         };
-        for (int s = 0; s < w.n_slots; ++s) {
-            uint32_t *seen = w.bitmap + (int64_t)s * w.n_words + i;
-            uint32_t carry = *seen;
-            if (carry) {
-                *seen = 0u;
-                w.prev[(int64_t)s * w.n_words + i] = 0u;
-                rows += __popc(carry);
+        uint32_t *column = (large ? w.aux : w.fresh) + i;
+        for (int s0 = 0; s0 < w.n_slots; s0 += 8) {                // eight slots' words in flight at a time
+            uint32_t x[8];
 #pragma unroll
-                for (int p = 0; p < 5; ++p) {                     // ripple-carry add of one bit per column
-                    const uint32_t t = plane[p] & carry;
-                    plane[p] ^= carry;
-                    carry = t;
+            for (int j = 0; j < 8; ++j) x[j] = s0 + j < w.n_slots ? column[(int64_t)(s0 + j) * w.bm_stride] : 0u;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                uint32_t carry = x[j];
+                if (carry) {
+                    column[(int64_t)(s0 + j) * w.bm_stride] = 0u;
+                    if (!large) w.aux[(int64_t)(s0 + j) * w.bm_stride + i] = 0u;
+                    rows += __popc(carry);
+#pragma unroll
+                    for (int q = 0; q < 5; ++q) {                 // ripple-carry add of one bit per column
+                        const uint32_t t = plane[q] & carry;
+                        plane[q] ^= carry;
+                        carry = t;
+                    }
+                    if (++held == 31) flush();
                 }
-                if (++held == 31) flush();
             }
         }
         flush();
@@ -543,40 +790,114 @@ __global__ __launch_bounds__(kBlock) void k_count_columns(wide_t w, uint32_t *__
         atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)tot);
 }
 
-__global__ void k_relabel(wide_t w, relabel_t r)
+// col[e] of the sampled neighbours that were not in the frontier when they were drawn (k_hop_sample
+// left ~node there).  New at a hop that is not the last: the node has entered the index since.  New
+// at the last hop: its position is the frontier size before the hop + the new nodes listed before
+// its segment + the bits below its own in the segment (the bitmap still holds the hop's bits).
+// With 32 words per segment those bits are one 128-byte line: the 8 lanes of a group take the
+// group's edges one at a time, each lane 16 bytes of the line.
+__global__ __launch_bounds__(kBlock) void k_relabel(wide_t w, int gx, relabel_t r)
 {
-    const slot_view v = view_of(w);
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int64_t stride = (int64_t)gx * kBlock;
+    const int64_t t = (int64_t)p.bx * kBlock + threadIdx.x;
     for (int l = 0; l < r.n_layers; ++l) {
-        int32_t *col = r.col[l] + (int64_t)blockIdx.y * r.stride[l];
+        int32_t *col = r.col[l] + (int64_t)p.slot * r.stride[l];
         const int64_t n = v.meta[META_NEDGES + l];
-        for (int64_t e = t; e < n; e += stride) col[e] = v.local_idx[col[e]];
+        const bool last = l == r.n_layers - 1;
+        const int32_t before_hop = (int32_t)v.meta[META_NFRONT + l];
+        if (!last) {
+            for (int64_t e = t; e < n; e += stride) {
+                const int32_t c = col[e];
+                if (c < 0) col[e] = index_of(v.table, w.table_log2, v.nodes, ~c);
+            }
+        } else if (w.seg_log2 == 0) {
+            for (int64_t e = t; e < n; e += stride) {
+                const int32_t c = col[e];
+                if (c >= 0) continue;
+                const int32_t u = ~c;
+                const int64_t word = (uint32_t)u >> 5;
+                col[e] = before_hop + v.segbase[word] + __popc(v.fresh[word] & ((1u << (u & 31)) - 1u));
+            }
+        } else {
+            const int lane8 = threadIdx.x & 7;
+            const uint4 *lines = (const uint4 *)v.fresh;                 // a segment = 8 pieces of 16 bytes
+            for (int64_t e0 = t - threadIdx.x; e0 < n; e0 += stride) {   // the whole block takes every step
+                const int64_t e = e0 + threadIdx.x;
+                const int32_t c = e < n ? col[e] : 0;
+                const int32_t start = c < 0 ? before_hop + v.segbase[(uint32_t)~c >> 10] : 0;
+                int32_t ci[8];
+                uint4 piece[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {                             // the eight lines of the group's edges, all in flight
+                    ci[i] = __shfl(c, i, 8);
+                    piece[i] = make_uint4(0u, 0u, 0u, 0u);
+                    if (ci[i] < 0) piece[i] = lines[(int64_t)((uint32_t)~ci[i] >> 10) * 8 + lane8];
+                }
+                int32_t mine = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t u = (uint32_t)~ci[i];
+                    const int word_in_seg = (u >> 5) & 31;
+                    const uint32_t words[4] = {piece[i].x, piece[i].y, piece[i].z, piece[i].w};
+                    int rank = 0;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int wi = lane8 * 4 + j;
+                        const uint32_t below = wi < word_in_seg ? 0xffffffffu : (wi == word_in_seg ? (1u << (u & 31)) - 1u : 0u);
+                        rank += __popc(words[j] & below);
+                    }
+                    rank = group8_sum(rank);
+                    if (lane8 == i) mine = rank;
+                }
+                if (c < 0) col[e] = start + mine;
+            }
+        }
     }
 }
 
-// End of a mini-batch: take the nodes of frontier `layer` (the last one that was listed) out
-// of local_idx[] and of the bitmaps; with COUNT, one access per node (the rows a gather for
-// this mini-batch reads) - k_bm_count has dealt with the nodes of the last hop.
-template <bool COUNT>
-__global__ void k_finish(wide_t w, int layer, uint32_t *__restrict__ counts)
+// End of a mini-batch: the frontier index back to all empty, and (block calls) the bits and flags
+// that the last hop left in place for k_relabel.
+__global__ __launch_bounds__(kBlock) void k_finish(wide_t w, int gx, int clear_fresh)
 {
-    const slot_view v = view_of(w);
-    const int64_t n = v.meta[META_NFRONT + layer];
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (int64_t i = t; i < n; i += stride) {
-        int32_t u = v.nodes[i];
-        if (w.index_nodes) v.local_idx[u] = -1;
-        if (COUNT) atomicAdd(&counts[u], 1u);
+    __shared__ int s_wave[kBlock / 64];
+    __shared__ int s_list[kSegTile];
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int64_t stride = (int64_t)gx * kBlock;
+    const int64_t t = (int64_t)p.bx * kBlock + threadIdx.x;
+    uint4 *cells = (uint4 *)v.table;                              // a slot's table is a multiple of 1024 cells
+    const int64_t n_cells4 = (1ll << w.table_log2) / 4;
+    for (int64_t i = t; i < n_cells4; i += stride) cells[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (!clear_fresh) return;
+    if (w.seg_log2 == 0) {
+        for (int64_t i = t; i < w.n_seg; i += stride)
+            if (v.flag[i]) {
+                v.flag[i] = 0;
+                v.fresh[i] = 0u;
+            }
+        return;
     }
-    if (w.clear_bitmaps)                        // small enough to stream through whole: cheaper than two
-        for (int64_t i = t; i < w.n_words; i += stride) {     // scattered stores per frontier node
-            v.bitmap[i] = 0u;
-            v.prev[i] = 0u;
+    int64_t lo, hi;
+    block_range(p, w.n_seg, lo, hi);
+    const int g = threadIdx.x >> 3, lane8 = threadIdx.x & 7;
+    uint4 *lines = (uint4 *)v.fresh;
+    for (int64_t tile = lo; tile < hi; tile += kSegTile) {
+        const int64_t i = tile + threadIdx.x;
+        const int f = (i < hi && v.flag[i] != 0) ? 1 : 0;
+        int n_f;
+        const int at = block_excl_scan(f, n_f, s_wave);
+        if (f) {
+            s_list[at] = threadIdx.x;
+            v.flag[i] = 0;
         }
-    if (COUNT && t == 0 && n)
-        atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)n);
+        __syncthreads();
+        for (int q = g; q < n_f; q += kSegGroups) lines[(tile + s_list[q]) * 8 + lane8] = make_uint4(0u, 0u, 0u, 0u);
+        __syncthreads();
+    }
 }
 
 __global__ void k_fill_u32(uint32_t *__restrict__ p, int64_t n, uint32_t value)
@@ -599,77 +920,73 @@ int clamp_grid(int64_t items, int per_block, int cap)
     return (int)g;
 }
 
+// Workgroups of a launch that gives every slot gx blocks (see my_spot).
+unsigned grid_of(int gx, int n_slots) { return (unsigned)(kXcds * gx * ((n_slots + kXcds - 1) / kXcds)); }
+
 struct wide_out {             // where the mini-batches' results go
     layer_out_t layer[TIER_MAX_LAYERS];
-    bool blocks;              // false: frontiers only (access counting)
-    uint32_t *counts;         // non-null: count the final frontiers
+    uint32_t *counts;         // access counting: where the final frontiers are counted
 };
 
-// The summary bitmap pays off once walking the whole bitmap costs more than the
-// returning atomics it needs: above 2^20 bitmap words (32 M nodes).
-bool two_level(const tier_ctx *c) { return c->n_words > (1 << 20); }
+// With 32 words per segment (the layout of graphs above 32 M nodes) access counting uses the index.
+bool large_graph(const tier_ctx *c) { return c->seg_log2 != 0; }
 
-template <typename OffT, int G, bool TWO_LEVEL>
-void launch_hop_sample2(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, const wide_out &o)
+template <int G, int MODE>
+void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, bool last, const wide_out &o)
 {
-    const OffT *ip = (const OffT *)c->indptr;
-    const dim3 grid(clamp_grid(cap_dst, kBlock / G, 16384), w.n_slots);
-    if (o.blocks)
-        k_hop_sample<OffT, G, true, TWO_LEVEL><<<grid, kBlock, 0, c->stream>>>(w, ip, c->indices, layer, k,
-                                                                               o.layer[layer]);
-    else
-        k_hop_sample<OffT, G, false, TWO_LEVEL><<<grid, kBlock, 0, c->stream>>>(w, ip, c->indices, layer, k,
-                                                                                layer_out_t{});
+    const int gx = clamp_grid(cap_dst, (kBlock / G) * kAtOnce, 16384);
+    k_hop_sample<G, MODE><<<grid_of(gx, w.n_slots), kBlock, 0, c->stream>>>(
+        w, gx, c->indices, layer, k, last ? 1 : 0, MODE == MODE_BLOCKS ? o.layer[layer] : layer_out_t{});
 }
 
-template <typename OffT, int G>
-void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, const wide_out &o)
+template <int MODE>
+void launch_hop(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, bool last, const wide_out &o)
 {
-    if (two_level(c)) launch_hop_sample2<OffT, G, true>(c, w, cap_dst, layer, k, o);
-    else launch_hop_sample2<OffT, G, false>(c, w, cap_dst, layer, k, o);
-}
-
-template <typename OffT>
-void launch_hop(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, const wide_out &o)
-{
-    if (o.blocks) {
-        const dim3 grid(clamp_grid(cap_dst, kBlock, TIER_SCAN_BLOCKS), w.n_slots);
-        k_hop_partial<OffT><<<grid, kBlock, 0, c->stream>>>(w, (const OffT *)c->indptr, layer, k);
-        k_hop_rowptr<OffT><<<grid, kBlock, 0, c->stream>>>(w, (const OffT *)c->indptr, layer, k, o.layer[layer]);
+    if (MODE == MODE_BLOCKS) {
+        const int gx = clamp_grid(cap_dst, kBlock, TIER_SCAN_BLOCKS);
+        const unsigned grid = grid_of(gx, w.n_slots);
+        k_hop_partial<<<grid, kBlock, 0, c->stream>>>(w, gx, layer, k);
+        k_hop_rowptr<<<grid, kBlock, 0, c->stream>>>(w, gx, layer, k, o.layer[layer]);
     }
-    if (k <= 4) launch_hop_sample<OffT, 4>(c, w, cap_dst, layer, k, o);
-    else if (k <= 8) launch_hop_sample<OffT, 8>(c, w, cap_dst, layer, k, o);
-    else if (k <= 16) launch_hop_sample<OffT, 16>(c, w, cap_dst, layer, k, o);
-    else if (k <= 32) launch_hop_sample<OffT, 32>(c, w, cap_dst, layer, k, o);
-    else launch_hop_sample<OffT, 64>(c, w, cap_dst, layer, k, o);
+    if (k <= 4) launch_hop_sample<4, MODE>(c, w, cap_dst, layer, k, last, o);
+    else if (k <= 8) launch_hop_sample<8, MODE>(c, w, cap_dst, layer, k, last, o);
+    else if (k <= 16) launch_hop_sample<16, MODE>(c, w, cap_dst, layer, k, last, o);
+    else if (k <= 32) launch_hop_sample<32, MODE>(c, w, cap_dst, layer, k, last, o);
+    else launch_hop_sample<64, MODE>(c, w, cap_dst, layer, k, last, o);
 }
 
 // Enqueue w.n_slots mini-batches.  cap_nodes / cap_edges: the bounds of tier_blocks_bounds
 // for one mini-batch of w.batch_size seeds.
-int enqueue_wide(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_layers, const int64_t *cap_nodes,
-                 const int64_t *cap_edges, const wide_out &o)
+template <int MODE, typename OffT>
+int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_layers, const int64_t *cap_nodes,
+                   const int64_t *cap_edges, const wide_out &o)
 {
-    const unsigned slots = (unsigned)w.n_slots;
-    k_init_seeds<<<dim3(clamp_grid(w.batch_size, kBlock, 1 << 20), slots), kBlock, 0, c->stream>>>(w);
-    const bool tl = two_level(c);
-    const dim3 bm_grid(tl ? clamp_grid(c->n_sum, kBlock, TIER_SCAN_BLOCKS)
-                          : clamp_grid(c->n_words, 4 * kBlock, TIER_SCAN_BLOCKS), slots);
+    const int slots = w.n_slots;
+    hipStream_t st = c->stream;
+    const OffT *indptr = (const OffT *)c->indptr;
+    {
+        const int gx = clamp_grid(w.batch_size, kBlock, 1 << 16);
+        k_init_seeds<MODE, OffT><<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, indptr);
+    }
+    const int seg_gx = clamp_grid(w.n_seg, kBlock, TIER_SCAN_BLOCKS);
+    const int flat_gx = clamp_grid(w.n_words, 4 * kBlock, TIER_SCAN_BLOCKS);
     for (int l = 0; l < n_layers; ++l) {
-        if (c->indptr_i64) launch_hop<int64_t>(c, w, cap_nodes[l], l, fanouts[l], o);
-        else launch_hop<int32_t>(c, w, cap_nodes[l], l, fanouts[l], o);
-        if (o.counts && l == n_layers - 1) {
-            // the last hop's nodes are never listed: counted from the bitmaps (see k_count_columns / k_bm_count)
-            if (tl) k_bm_count<<<bm_grid, kBlock, 0, c->stream>>>(w, o.counts);
-            else k_count_columns<<<clamp_grid(c->n_words, kBlock, 1 << 22), kBlock, 0, c->stream>>>(w, o.counts);
-        } else if (tl) {
-            k_bm_partial<<<bm_grid, kBlock, 0, c->stream>>>(w);
-            k_bm_emit<<<bm_grid, kBlock, 0, c->stream>>>(w, l);
+        const bool last = l == n_layers - 1;
+        launch_hop<MODE>(c, w, cap_nodes[l], l, fanouts[l], last, o);
+        if (MODE != MODE_BLOCKS && last) break;               // counted from the bitmaps, never listed
+        if (MODE == MODE_COUNT_SMALL) {
+            k_bm_partial_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx);
+            k_bm_emit_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx, l);
         } else {
-            k_bm_partial_flat<<<bm_grid, kBlock, 0, c->stream>>>(w);
-            k_bm_emit_flat<<<bm_grid, kBlock, 0, c->stream>>>(w, l);
+            k_bm_partial<<<grid_of(seg_gx, slots), kBlock, 0, st>>>(w, seg_gx);
+            k_bm_emit<MODE><<<grid_of(seg_gx, slots), kBlock, 0, st>>>(w, seg_gx, l, last ? 1 : 0);
+        }
+        if (!last) {
+            const int gx = clamp_grid(cap_nodes[l + 1], kBlock, 4096);
+            k_settle<MODE, OffT><<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, indptr, l);
         }
     }
-    if (o.blocks) {
+    if (MODE == MODE_BLOCKS) {
         relabel_t r = {};
         r.n_layers = n_layers;
         int64_t most = 1;
@@ -678,18 +995,58 @@ int enqueue_wide(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_lay
             r.stride[l] = o.layer[l].edge_stride;
             if (cap_edges[l] > most) most = cap_edges[l];
         }
-        k_relabel<<<dim3(clamp_grid(most, kBlock, 4096), slots), kBlock, 0, c->stream>>>(w, r);
+        const int gx = clamp_grid(most, kBlock, 4096);
+        k_relabel<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, r);
+    } else {
+        k_count_columns<<<clamp_grid(c->n_words, kBlock, 1 << 22), kBlock, 0, st>>>(w, MODE == MODE_COUNT_LARGE ? 1 : 0,
+                                                                                 o.counts);
     }
-    const int last = o.counts ? n_layers - 1 : n_layers;       // last frontier that was listed
-    const dim3 fgrid(clamp_grid(cap_nodes[last], kBlock, 4096), slots);
-    if (o.counts && tl) k_finish<true><<<fgrid, kBlock, 0, c->stream>>>(w, last, o.counts);
-    else if (!o.counts) k_finish<false><<<fgrid, kBlock, 0, c->stream>>>(w, last, nullptr);
+    if (MODE != MODE_COUNT_SMALL) {
+        const int64_t cells4 = (1ll << w.table_log2) / 4;
+        const int gx = clamp_grid(cells4 > w.n_seg ? cells4 : w.n_seg, 4 * kBlock, 2048);
+        k_finish<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, MODE == MODE_BLOCKS ? 1 : 0);
+    }
     TIER_HIP(c, hipGetLastError());
     return TIER_OK;
 }
 
+template <int MODE>
+int enqueue_wide(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_layers, const int64_t *cap_nodes,
+                 const int64_t *cap_edges, const wide_out &o)
+{
+    return c->indptr_i64 ? enqueue_wide_t<MODE, int64_t>(c, w, fanouts, n_layers, cap_nodes, cap_edges, o)
+                         : enqueue_wide_t<MODE, int32_t>(c, w, fanouts, n_layers, cap_nodes, cap_edges, o);
+}
+
+// Offsets and degrees of the frontier nodes that draw: `per_slot` entries for every slot.
+int ensure_degrees(tier_ctx *c, int64_t per_slot)
+{
+    const size_t n = (size_t)per_slot * (size_t)c->n_slots;
+    int rc = tier_ensure(c, (void **)&c->f_beg, &c->f_beg_cap, n * sizeof(int64_t));
+    if (rc == TIER_OK) rc = tier_ensure(c, (void **)&c->f_deg, &c->f_deg_cap, n * sizeof(int32_t));
+    return rc;
+}
+
+// The frontier index of a call: room for twice the largest frontier that draws (cap_nodes of the
+// last hop's dst side), a power of two of at least 1024 cells per slot; zero between calls.
+int ensure_table(tier_ctx *c, int64_t most_members, int *table_log2)
+{
+    int lg = 10;
+    while ((1ll << lg) < 2 * most_members) ++lg;
+    if (lg > 31) return TIER_EINVAL;
+    const size_t bytes = ((size_t)c->n_slots << lg) * sizeof(uint32_t);
+    if (!c->table || c->table_cap < bytes) {
+        int rc = tier_ensure(c, (void **)&c->table, &c->table_cap, bytes);
+        if (rc != TIER_OK) return rc;
+        k_fill_u32<<<4096, kBlock, 0, c->stream>>>(c->table, (int64_t)(bytes / sizeof(uint32_t)), 0u);
+        TIER_HIP(c, hipGetLastError());
+    }
+    *table_log2 = lg;
+    return TIER_OK;
+}
+
 wide_t make_wide(tier_ctx *c, const int32_t *seeds, int64_t n_seeds_total, int32_t batch_size, int32_t n_slots,
-                 int32_t *nodes, int64_t nodes_stride)
+                 int32_t *nodes, int64_t nodes_stride, int table_log2, int64_t deg_stride)
 {
     wide_t w = {};
     w.seeds = seeds;
@@ -698,13 +1055,21 @@ wide_t make_wide(tier_ctx *c, const int32_t *seeds, int64_t n_seeds_total, int32
     w.n_slots = n_slots;
     w.n_nodes = c->n_nodes;
     w.n_words = c->n_words;
+    w.bm_stride = c->bm_stride;
+    w.n_seg = c->n_seg;
+    w.flag_stride = c->flag_stride;
+    w.seg_log2 = c->seg_log2;
     w.nodes = nodes;
     w.nodes_stride = nodes_stride;
-    w.local_idx = c->local_idx;
-    w.bitmap = c->bitmap;
-    w.prev = c->prev;
-    w.summary = c->summary;
-    w.n_sum = c->n_sum;
+    w.fresh = c->fresh;
+    w.aux = c->aux;
+    w.flag = c->flag;
+    w.segbase = c->segbase;
+    w.table = c->table;
+    w.table_log2 = table_log2;
+    w.beg = c->f_beg;
+    w.deg = c->f_deg;
+    w.deg_stride = deg_stride;
     w.meta = c->meta;
     w.partial_hop = c->partial_hop;
     w.partial_bm = c->partial_bm;
@@ -755,22 +1120,24 @@ int tier_sample_minibatches(tier_ctx *ctx, const int32_t *seeds, int64_t n_seeds
     if (!out->nodes || !out->n_nodes || !out->n_edges) return TIER_EINVAL;
     if (out->nodes_stride < cap_nodes[n_layers]) return TIER_ECAPACITY;
     wide_out o = {};
-    o.blocks = true;
     for (int l = 0; l < n_layers; ++l) {
         if (!out->row_ptr[l] || !out->col[l] || !out->eid[l]) return TIER_EINVAL;
         if (out->row_ptr_stride[l] < cap_nodes[l] + 1 || out->edge_stride[l] < cap_edges[l]) return TIER_ECAPACITY;
         o.layer[l] = layer_out_t{out->row_ptr[l], out->row_ptr_stride[l], out->col[l], out->eid[l],
                                  out->edge_stride[l]};
     }
-    wide_t w = make_wide(ctx, seeds, n_seeds_total, batch_size, n_batches, out->nodes, out->nodes_stride);
-    w.frontier_bits = two_level(ctx) ? 0 : 1;
-    w.index_nodes = 1;
-    w.clear_bitmaps = w.frontier_bits;
+    int table_log2 = 0;
+    rc = ensure_table(ctx, cap_nodes[n_layers - 1], &table_log2);
+    const int64_t drawing = cap_nodes[n_layers - 1] > 0 ? cap_nodes[n_layers - 1] : 1;    // nodes that draw at the last hop
+    if (rc == TIER_OK) rc = ensure_degrees(ctx, drawing);
+    if (rc) return rc;
+    wide_t w = make_wide(ctx, seeds, n_seeds_total, batch_size, n_batches, out->nodes, out->nodes_stride, table_log2,
+                         drawing);
     for (int s = 0; s < n_batches; ++s) {
         w.key0[s] = (uint32_t)batch_seeds[s];
         w.key1[s] = (uint32_t)(batch_seeds[s] >> 32);
     }
-    rc = enqueue_wide(ctx, w, fanouts, n_layers, cap_nodes, cap_edges, o);
+    rc = enqueue_wide<MODE_BLOCKS>(ctx, w, fanouts, n_layers, cap_nodes, cap_edges, o);
     if (rc) return rc;
     rc = tier_sync_meta(ctx);
     for (int s = 0; s < n_batches; ++s) {
@@ -814,31 +1181,37 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
     rc = tier_blocks_bounds(ctx->n_nodes, first, fanouts, n_layers, cap_nodes, cap_edges);
     if (rc) return rc;
     if (first > ctx->n_nodes) return TIER_EINVAL;
-    const int64_t stride = cap_nodes[n_layers] > 0 ? cap_nodes[n_layers] : 1;
+    // only the nodes that draw are listed: the frontier before the last hop
+    const int64_t stride = cap_nodes[n_layers - 1] > 0 ? cap_nodes[n_layers - 1] : 1;
     rc = ensure_i32(ctx, &ctx->ps_nodes, &ctx->cap_ps_nodes, stride * ctx->n_slots);
+    if (rc == TIER_OK) rc = ensure_degrees(ctx, stride);
     if (rc) return rc;
+    const bool large = large_graph(ctx);
+    int table_log2 = 10;
+    if (large) {
+        rc = ensure_table(ctx, cap_nodes[n_layers - 1], &table_log2);
+        if (rc) return rc;
+    }
 
     k_fill_u32<<<clamp_grid(ctx->n_nodes, kBlock, 4096), kBlock, 0, ctx->stream>>>(counts, ctx->n_nodes, 0u);
     k_clear_totals<<<1, 1, 0, ctx->stream>>>(ctx->meta);
     wide_out o = {};
-    o.blocks = false;
     o.counts = counts;
     const int64_t n_batches = (n_train + batch_size - 1) / batch_size;
     for (int e = 0; e < epochs; ++e) {
         for (int64_t b = 0; b < n_batches; b += ctx->n_slots) {
             const int slots = (int)(n_batches - b < ctx->n_slots ? n_batches - b : ctx->n_slots);
             const int64_t lo = b * batch_size;
-            wide_t w = make_wide(ctx, train_ids + lo, n_train - lo, batch_size, slots, ctx->ps_nodes, stride);
-            w.frontier_bits = two_level(ctx) ? 0 : 1;
-            w.index_nodes = w.frontier_bits ? 0 : 1;       // small graphs: nothing is relabelled, local_idx[] stays untouched
-            w.clear_bitmaps = 0;                           // k_count_columns clears the bitmaps
+            wide_t w = make_wide(ctx, train_ids + lo, n_train - lo, batch_size, slots, ctx->ps_nodes, stride, table_log2,
+                                 stride);
             w.count_edges = total_edges != nullptr;
             for (int s = 0; s < slots; ++s) {
                 const uint64_t bs = tier_batch_seed(seed, (uint32_t)e, (uint32_t)(b + s));
                 w.key0[s] = (uint32_t)bs;
                 w.key1[s] = (uint32_t)(bs >> 32);
             }
-            rc = enqueue_wide(ctx, w, fanouts, n_layers, cap_nodes, cap_edges, o);
+            rc = large ? enqueue_wide<MODE_COUNT_LARGE>(ctx, w, fanouts, n_layers, cap_nodes, cap_edges, o)
+                       : enqueue_wide<MODE_COUNT_SMALL>(ctx, w, fanouts, n_layers, cap_nodes, cap_edges, o);
             if (rc) return rc;
         }
     }

@@ -64,14 +64,24 @@ struct tier_ctx {
     const uint8_t *host_rows;
     bool rows_on_host;       // the table is host memory read over the link (not a device allocation)
     int64_t row_bytes;
-    // per-node scratch, one copy per slot (mini-batch sampled side by side)
+    // sampler scratch over all nodes, one copy per slot (mini-batch sampled side by side); all of it
+    // is zero between mini-batches
     int n_slots;
-    int32_t *local_idx;      // [n_slots][n_nodes]; -1 = not in the slot's current frontier
-    uint32_t *bitmap;        // [n_slots][n_words]; frontier + nodes reached at the current hop; zero between mini-batches
-    uint32_t *prev;          // [n_slots][n_words]; the frontier before the current hop; zero between mini-batches
+    uint32_t *fresh;         // [n_slots][bm_stride]; bits of the nodes first reached at the current hop
+    uint32_t *aux;           // [n_slots][bm_stride]; access counting only: the frontier so far
+    uint8_t *flag;           // [n_slots][flag_stride]; != 0: the segment holds a bit of `fresh`
+    int32_t *segbase;        // [n_slots][n_seg]; start position of a segment's new nodes (last hop of a block call)
     int64_t n_words;         // ceil(n_nodes / 32)
-    uint32_t *summary;       // [n_slots][n_sum]; bit j of word i set <=> bitmap word 32 i + j is non-zero
-    int64_t n_sum;           // ceil(n_words / 32)
+    int64_t bm_stride;       // bitmap words per slot: n_words rounded up to whole 128-byte lines
+    int seg_log2;            // a segment is 1 << seg_log2 bitmap words: 0 up to 32 M nodes, 5 above
+    int64_t n_seg;           // segments per slot
+    int64_t flag_stride;     // n_seg rounded up to a multiple of 16
+    int64_t *f_beg;          // [n_slots][nodes that draw in the current call]: indptr[node] beside the frontier
+    size_t f_beg_cap;        // bytes
+    int32_t *f_deg;          // likewise: degrees
+    size_t f_deg_cap;
+    uint32_t *table;         // frontier index of the sampler, [n_slots][cells of the current call]; grown on demand
+    size_t table_cap;        // bytes
     // placement
     int32_t *slot;           // n_nodes
     uint8_t *cache;          // n_hot * row_bytes

@@ -21,7 +21,7 @@ _lib = None
 EXPORTS = (
     "tier_host_alloc", "tier_host_free", "tier_blocks_bounds", "tier_create", "tier_destroy",
     "tier_presample", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
-    "tier_sample_minibatches", "tier_max_batches",
+    "tier_sample_minibatches", "tier_max_batches", "tier_set_segment_words",
     "tier_score_degree", "tier_score_wrpr", "tier_rank_scores", "tier_place_scores",
     "tier_rank", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
     "tier_gather_features", "tier_gather_minibatches", "tier_set_gather_stream", "tier_set_gather_dedup", "tier_set_gather_split",
@@ -85,6 +85,7 @@ def _load():
         lib.tier_sample_minibatches.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, i32p,
                                                 C.c_int32, C.POINTER(C.c_uint64), C.POINTER(_BlocksBatch)]
         lib.tier_max_batches.argtypes = [C.c_void_p]
+        lib.tier_set_segment_words.argtypes = [C.c_void_p, C.c_int32]
         lib.tier_score_degree.argtypes = [C.c_void_p, C.c_void_p]
         lib.tier_score_wrpr.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_double, C.c_void_p]
         lib.tier_rank_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -384,6 +385,11 @@ class BlocksBatch:
 
 def tier_max_batches(ctx: Context) -> int:
     return int(_load().tier_max_batches(ctx.handle))
+
+
+def tier_set_segment_words(ctx: Context, words: int):
+    """Layout of the sampler's scratch: 1 or 32 bitmap words per segment (see tier.h)."""
+    _check(_load().tier_set_segment_words(ctx.handle, words), "tier_set_segment_words")
 
 
 def tier_sample_minibatches(ctx: Context, seeds: torch.Tensor, batch_size: int, batch_seeds, fanouts,

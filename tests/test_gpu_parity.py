@@ -19,7 +19,7 @@ class World:
     """A graph, a pinned feature table and a library context, with numpy views
     for the oracle."""
 
-    def __init__(self, indptr, indices, dim=32, dtype=torch.float32, feat_seed=3):
+    def __init__(self, indptr, indices, dim=32, dtype=torch.float32, feat_seed=3, seg_words=None):
         self.indptr_d = indptr.to(DEV); self.indices_d = indices.to(DEV)
         self.indptr = indptr.cpu().numpy().astype(np.int64); self.indices = indices.cpu().numpy()
         self.n = self.indptr.shape[0] - 1
@@ -28,6 +28,8 @@ class World:
         self.feat_bytes = self.feat.view(torch.uint8).numpy().reshape(self.n, -1)
         self.row_bytes = self.feat_bytes.shape[1]
         self.ctx = tier.tier_create(self.indptr_d, self.indices_d, self.feat)
+        if seg_words is not None:                       # e.g. the scratch layout of graphs above 32 M nodes
+            tier.tier_set_segment_words(self.ctx, seg_words)
         self.local_idx = np.full(self.n, -1, np.int32)
 
     def close(self):
@@ -55,16 +57,19 @@ def compare_blocks(w: World, seeds_np, fanouts, seed, blocks=None):
     return got, want
 
 
-@pytest.fixture(scope="module")
-def small():
-    w = rmat_world(5000, 60_000, dim=32)
+# Every sampling test runs under both layouts of the sampler's scratch: one bitmap word per
+# segment (what a graph of this size gets) and 32 (what graphs above 32 M nodes get, with
+# tier_presample keeping its frontiers in the sampler's index).
+@pytest.fixture(scope="module", params=[None, 32], ids=["seg1", "seg32"])
+def small(request):
+    w = rmat_world(5000, 60_000, dim=32, seg_words=request.param)
     yield w
     w.close()
 
 
-@pytest.fixture(scope="module")
-def small_i32():
-    w = rmat_world(3001, 40_000, seed=77, i64=False, dim=100)      # 400-byte rows, ragged sizes
+@pytest.fixture(scope="module", params=[None, 32], ids=["seg1", "seg32"])
+def small_i32(request):
+    w = rmat_world(3001, 40_000, seed=77, i64=False, dim=100, seg_words=request.param)      # 400-byte rows, ragged sizes
     yield w
     w.close()
 
@@ -160,11 +165,12 @@ def test_batched_sampling_matches_oracle(small, fanouts, batch_size, n_total):
                                      [1] * (B + 1), (3,), tier.BlocksBatch(small.n, 10, (3,), B + 1, DEV))
 
 
-def test_blocks_large_frontier_spans_many_tiles():
+@pytest.mark.parametrize("seg_words", [None, 32], ids=["seg1", "seg32"])
+def test_blocks_large_frontier_spans_many_tiles(seg_words):
     """Frontier above 1024 blocks x 256 nodes, so blocks walk several tiles."""
     say("large frontier")
     ip, ix = synth.erdos_renyi_csr(1_500_000, 30_000_000, 5, DEV)
-    w = World(ip, ix, dim=4)
+    w = World(ip, ix, dim=4, seg_words=seg_words)
     try:
         rng = np.random.default_rng(1)
         seeds = rng.choice(w.n, 8192, replace=False).astype(np.int32)
