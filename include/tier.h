@@ -203,6 +203,19 @@ int tier_place_scores(tier_ctx *ctx, const double *scores, uint64_t budget_bytes
  * the context's stream. */
 int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, int32_t *order);
 
+/* tier_rank for callers that cannot allocate memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same rank / order as tier_rank for the same
+ * counts, needs no context, calls no allocating routine and does not wait: it only enqueues
+ * kernels on `stream` (a hipStream_t, NULL = the default stream).  The sort's scratch lives in a
+ * device array inside the library, TIER_RANK_STATIC_MAX_NODES keys long (about 17 MB on every
+ * GPU the library is used on, held until the process ends); more nodes give TIER_ECAPACITY.
+ * All calls on one GPU share that scratch: calls that overlap in time on one GPU (different
+ * streams or threads) race on it; calls on one stream are safe one after the other.
+ * counts: (device) n_nodes entries; rank, order: (device, either may be NULL, not both) n_nodes
+ * entries each, complete in the order of `stream`. */
+#define TIER_RANK_STATIC_MAX_NODES (1 << 20)
+int tier_rank_static(const uint32_t *counts, int64_t n_nodes, int32_t *rank, int32_t *order, void *stream);
+
 /* Graph reordering (Sec. 3.2, Alg. 2): the context's graph with every node renamed to
  * rank[node]: new node r has the neighbour list of order[r], in its old order, values
  * renamed.  indptr_new: (device) n_nodes + 1 offsets of the context graph's offset type;

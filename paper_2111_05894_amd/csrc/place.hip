@@ -416,3 +416,91 @@ extern "C" int tier_place_boundary(tier_ctx *ctx, uint64_t budget_bytes, int64_t
     if (n_hot_out) *n_hot_out = n_hot;
     return TIER_OK;
 }
+
+// ---- ranking for callers that cannot allocate ---------------------------------------------------
+// Same ordering as tier_rank, with the sort's scratch (two key buffers, two id buffers, the digit
+// histograms and the block sums of their scan) in one file-scope device array instead of memory
+// the context allocates.  Nothing here calls hipMalloc, hipFree or any routine that allocates; all
+// four 8-bit digits are sorted, so the call does not have to wait for the set of varying digits
+// either and only enqueues kernels.  Every GPU holds its own copy of the array, at its own address,
+// which hipGetSymbolAddress reports once per device; host code uses that address only, never the
+// array's name.  Every kernel below overwrites what it reads of the scratch before it reads it
+// (histograms and block sums are written in full each pass), so nothing has to be cleared between
+// calls; two calls that overlap on one GPU would race on it.
+namespace {
+
+constexpr int64_t kStaticMaxNodes = TIER_RANK_STATIC_MAX_NODES;
+constexpr int64_t kStaticShares = 1024;                        // shares of at least 1024 keys: at most 1024 of them
+constexpr size_t kStaticKeys = (size_t)kStaticMaxNodes * sizeof(uint32_t);
+constexpr size_t kStaticHist = (size_t)kDigits * kStaticShares * sizeof(uint32_t);
+constexpr size_t kStaticPartial = 1024 * sizeof(uint32_t);
+constexpr size_t kStaticBytes = 4 * kStaticKeys + kStaticHist + kStaticPartial;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, once known
+
+// Address of this device's copy of `scratch` (looked up on the first call on the device).
+int static_scratch(unsigned char **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return TIER_EHIP;
+    }
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return TIER_EHIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = (unsigned char *)g_scratch_ptr[dev];
+    return TIER_OK;
+}
+
+}  // namespace
+
+extern "C" int tier_rank_static(const uint32_t *counts, int64_t n_nodes, int32_t *rank, int32_t *order, void *stream)
+{
+    if (n_nodes < 0 || (n_nodes > 0 && !counts) || (!rank && !order)) return TIER_EINVAL;
+    if (n_nodes > kStaticMaxNodes) return TIER_ECAPACITY;      // more nodes than the static scratch holds
+    if (n_nodes == 0) return TIER_OK;
+    unsigned char *base = nullptr;
+    int rc = static_scratch(&base);
+    if (rc != TIER_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t n = n_nodes;
+    uint32_t *keys[2] = {(uint32_t *)base, (uint32_t *)(base + kStaticKeys)};
+    int32_t *vals[2] = {(int32_t *)(base + 2 * kStaticKeys), (int32_t *)(base + 3 * kStaticKeys)};
+    uint32_t *hist = (uint32_t *)(base + 4 * kStaticKeys);
+    uint32_t *partial = (uint32_t *)(base + 4 * kStaticKeys + kStaticHist);
+
+    int64_t share = (n + kStaticShares - 1) / kStaticShares;
+    if (share < 16 * kWave) share = 16 * kWave;
+    share = (share + kWave - 1) / kWave * kWave;
+    const int n_shares = (int)((n + share - 1) / share);      // <= kStaticShares
+    const int64_t n_hist = (int64_t)kDigits * n_shares;
+    const int scan_grid = grid_for(n_hist, 4 * kScanBlock, 1024);
+    k_keys_from_counts<<<grid_for(n, 256, 4096), 256, 0, st>>>(counts, n, keys[0]);
+    // pass j reads buffers j % 2 and writes buffers (j + 1) % 2; the last pass writes the order where it is wanted
+    for (int j = 0; j < 4; ++j) {
+        const int src = j % 2, dst = (j + 1) % 2;
+        const bool last = j == 3;
+        int32_t *vals_out = last && order ? order : vals[dst];
+        k_radix_hist<uint32_t><<<n_shares, kWave, 0, st>>>(keys[src], n, share, 8 * j, hist, n_shares);
+        k_scan_partial<<<scan_grid, kScanBlock, 0, st>>>(hist, n_hist, partial);
+        k_scan_apply<<<scan_grid, kScanBlock, 0, st>>>(hist, n_hist, partial);
+        k_radix_scatter<uint32_t><<<n_shares, kWave, 0, st>>>(keys[src], j == 0 ? nullptr : vals[src], n, share, 8 * j, hist,
+                                                              n_shares, last ? nullptr : keys[dst], vals_out);
+    }
+    if (rank) k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order ? order : vals[0], n, n, rank);
+    if (hipGetLastError() != hipSuccess) return TIER_EHIP;
+    return TIER_OK;
+}

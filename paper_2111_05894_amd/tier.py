@@ -23,7 +23,7 @@ EXPORTS = (
     "tier_presample", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
     "tier_sample_minibatches", "tier_max_batches", "tier_set_segment_words",
     "tier_score_degree", "tier_score_wrpr", "tier_rank_scores", "tier_place_scores",
-    "tier_rank", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
+    "tier_rank", "tier_rank_static", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
     "tier_gather_features", "tier_gather_minibatches", "tier_set_gather_stream", "tier_set_gather_dedup", "tier_set_gather_split",
     "tier_strerror", "tier_last_hip_error",
 )
@@ -91,6 +91,7 @@ def _load():
         lib.tier_rank_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tier_place_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, i64p]
         lib.tier_rank.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.tier_rank_static.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tier_reorder_graph.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tier_reorder_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tier_relabel_ids.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
@@ -275,6 +276,24 @@ def tier_rank(ctx: Context, counts: torch.Tensor):
     order = torch.empty_like(rank)
     _check(_load().tier_rank(ctx.handle, _dev(counts, torch.int32, "counts"), _dev(rank, torch.int32, "rank"),
                              _dev(order, torch.int32, "order")), "tier_rank")
+    return rank, order
+
+
+RANK_STATIC_MAX_NODES = 1 << 20
+
+
+def tier_rank_static(counts: torch.Tensor, rank: torch.Tensor = None, order: torch.Tensor = None, stream=None):
+    """tier_rank without a context and without any allocation inside the library (see tier.h).
+    The outputs are the caller's: pass them in to keep the call itself free of allocations."""
+    n = counts.numel()
+    if rank is None:
+        rank = torch.empty(n, dtype=torch.int32, device=counts.device)
+    if order is None:
+        order = torch.empty(n, dtype=torch.int32, device=counts.device)
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(_load().tier_rank_static(_dev(counts, torch.int32, "counts"), n, _dev(rank, torch.int32, "rank"),
+                                    _dev(order, torch.int32, "order"), C.c_void_p(stream)), "tier_rank_static")
     return rank, order
 
 
