@@ -38,7 +38,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--workload", default="cfg3",
+                    help="cfg1..cfg5; the default is the largest configuration that fits one GPU and this host's pinned "
+                         "memory (cfg3: 111 M nodes, 56.8 GB of features)")
     ap.add_argument("--budget", type=float, default=None, help="override: fraction of feature bytes kept in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streams", action="store_true", help="skip the all-hit / all-miss gather runs")
@@ -50,9 +52,13 @@ def main():
                     help="also sweep the HBM budget and the sampling depth (analogues of the paper's Fig. 5 and 6)")
     ap.add_argument("--link-blocks", type=int, default=64,
                     help="blocks of the cold-row launch of the split gather (0: one uniform launch per call)")
-    ap.add_argument("--group", type=int, default=16,
+    ap.add_argument("--group", type=int, default=0,
                     help="mini-batches per sampling / gather call (at most what the context takes, up to 64); a larger "
-                         "group shares more cold rows per call and holds that many mini-batches' rows in HBM at once")
+                         "group shares more cold rows per call and holds that many mini-batches' rows in HBM at once.  "
+                         "0: 16, or 64 on the miss-dominated cfg5, where the rows held are small next to the cache")
+    ap.add_argument("--no-groups", action="store_true", help="skip the comparison of group sizes 16 / 32 / 64")
+    ap.add_argument("--no-budget-sweep", action="store_true",
+                    help="skip the placement + epoch at the other HBM budgets of the workload (cfg3: 5 % and 20 %)")
     ap.add_argument("--no-shared-misses", action="store_true",
                     help="read every requested cold row over the host link, also those a call requests more than once")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink nodes, edges and budget alike")
@@ -101,14 +107,19 @@ def main():
     n_batches = -(-n_train // bs)
     order = synth.random_order(n_train, synth.EPOCH_SEED, 1, dev)
     epoch_ids = train[order].contiguous()
-    B = tier.tier_max_batches(ctx)                 # mini-batches sampled side by side per call
-    if args.group > 0:
-        B = min(B, args.group)
-    groups = [list(range(g, min(g + B, n_batches))) for g in range(0, n_batches, B)]
+    B_max = tier.tier_max_batches(ctx)             # mini-batches sampled side by side per call
+    group = args.group if args.group > 0 else (64 if wl.name == "cfg5" else 16)
+    B = min(B_max, group)
+    group_sizes = sorted({min(B_max, g) for g in (16, 32, 64)} | {B}) if not args.no_groups else [B]
+
+    def grouping(size):
+        return [list(range(g, min(g + size, n_batches))) for g in range(0, n_batches, size)]
+
+    groups = grouping(B)
     bseed = [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in range(n_batches)]
     # three sets of block buffers: while up to two groups of mini-batches wait for or run their
     # gather (gather stream, host-link bound) the next group is sampled (main stream, latency bound)
-    blocks2 = [tier.BlocksBatch(n, bs, wl.fanouts, B, dev) for _ in range(3)]
+    blocks2 = [tier.BlocksBatch(n, bs, wl.fanouts, max(group_sizes), dev) for _ in range(3)]
     blocks = blocks2[0]
     out_buf = [torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=dev)]
     counts = torch.empty(n, dtype=torch.int32, device=dev)
@@ -139,7 +150,7 @@ def main():
             b_.record()
         return a, b_, rows
 
-    def epoch(record, begin=None):
+    def epoch(record, begin=None, groups=groups):
         """The measured epoch: every group of mini-batches sampled (main stream) and gathered (gather
         stream).  begin: event on the gather stream from which the epoch's wall time counts (the end
         of the cache fill, which the first sampling calls overlap); default: now."""
@@ -147,7 +158,7 @@ def main():
             torch.cuda.synchronize()
             with torch.cuda.stream(gs):
                 begin = ev(); begin.record()
-        rows = edges = 0
+        rows = edges = most = 0
         s_pairs, g_pairs = [], []
         NB = len(blocks2)
         reads_done = [None] * NB                   # last gather that reads blocks2[i]
@@ -163,6 +174,7 @@ def main():
             a, b_, r = timed_gather(blk, len(g))
             g_pairs.append((a, b_))
             rows += r; edges += sum(sum(blk.n_edges[i]) for i in range(len(g)))
+            most = max(most, r)
             reads_done[gi % NB] = b_
         torch.cuda.synchronize()
         if record is not None:
@@ -171,6 +183,7 @@ def main():
             record["gather_ms"].append(sum(a.elapsed_time(b_) for a, b_ in g_pairs))
             record["rows"] = rows; record["edges"] = edges
             record["gather_launches"] = len(g_pairs)
+            record["most_rows_per_call"] = most
         return rows, edges
 
     def step(record):
@@ -215,7 +228,7 @@ def main():
         tier.tier_set_gather_split(ctx, 0, 0)
         urec = {"sample_ms": [], "gather_ms": [], "epoch_wall_ms": []}
         epoch(None)
-        for _ in range(max(args.steps, 1)):
+        for _ in range(min(max(args.steps, 1), 3)):
             epoch(urec)
         tier.tier_set_gather_split(ctx, args.link_blocks, SPLIT_MIN_ROWS)
         tier.tier_set_gather_dedup(ctx, shared_on)
@@ -223,13 +236,39 @@ def main():
                    "gather_ms": round(sum(urec["gather_ms"]) / len(urec["gather_ms"]), 3),
                    "sample_ms": round(sum(urec["sample_ms"]) / len(urec["sample_ms"]), 3)}
 
+    def epoch_stats(groups):
+        """hit rows and rows over the host link of the measured epoch (asking for them waits per call)."""
+        hits = links = 0
+        for g in groups:
+            blk = sample_group(g)
+            _, _, h, m = tier.tier_gather_minibatches(ctx, blk, len(g), out_buf[0], want_stats=True)
+            hits += h
+            links += ctx.last_link_rows          # the misses, or with shared misses the distinct ones per call
+        return hits, links
+
+    # the same epoch (same placement) with other numbers of mini-batches per call
+    group_table = None
+    if len(group_sizes) > 1:
+        group_table = {}
+        for size in group_sizes:
+            gg = grouping(size)
+            grec = {"sample_ms": [], "gather_ms": [], "epoch_wall_ms": []}
+            epoch(None, groups=gg)                 # grows the output buffer
+            for _ in range(2):
+                epoch(grec, groups=gg)
+            hits, links = epoch_stats(gg)
+            cold = grec["rows"] - hits
+            group_table[str(size)] = {
+                "epoch_wall_ms": round(min(grec["epoch_wall_ms"]), 3), "gather_ms": round(min(grec["gather_ms"]), 3),
+                "sample_ms": round(min(grec["sample_ms"]), 3),
+                "cold_requests_crossing_the_link": round(links / cold, 4) if cold else 1.0,
+                "output_rows_held": grec["most_rows_per_call"], "output_bytes_held": grec["most_rows_per_call"] * R,
+                "gather_launches": grec["gather_launches"]}
+        group_table["note"] = ("same placement, whole epoch sampled and gathered `size` mini-batches per call (best of 2); "
+                               "a larger call shares more cold rows and holds that many mini-batches' output rows at once")
+
     # hit / miss rows of the measured epoch (outside the timed region: asking for them waits per batch)
-    hit_rows = link_rows = 0
-    for g in groups:
-        blk = sample_group(g)
-        _, _, h, m = tier.tier_gather_minibatches(ctx, blk, len(g), out_buf[0], want_stats=True)
-        hit_rows += h
-        link_rows += ctx.last_link_rows          # the misses, or with shared misses the distinct ones per call
+    hit_rows, link_rows = epoch_stats(groups)
     # the sampler on its own (in the timed region it shares the GPU with the gathers)
     torch.cuda.synchronize()
     a, b_ = ev(), ev()
@@ -260,8 +299,11 @@ def main():
     peak_time_additive = alg_bytes_row / (hbm_b / HBM_PEAK_GBPS + link_b / LINK_PEAK_GBPS)
     peak_overlap = alg_bytes_row / max(hbm_b / HBM_PEAK_GBPS, link_b / LINK_PEAK_GBPS)   # both streams fully overlapped
     peak_arithmetic = h * HBM_PEAK_GBPS + (1 - h) * LINK_PEAK_GBPS
+    link_share = (link_b / LINK_PEAK_GBPS) / (hbm_b / HBM_PEAK_GBPS + link_b / LINK_PEAK_GBPS)
     roofline = {
-        "bound": "hbm", "kernel": "k_gather", "achieved": round(achieved, 2),
+        "bound": "host-link+hbm", "binding_term": f"host link: {100 * link_share:.0f} % of the blend's time per row is the cold rows' "
+                                                  f"crossing of the PCIe link, the rest HBM traffic",
+        "kernel": "k_gather", "achieved": round(achieved, 2),
         "peak": round(peak_time_additive, 2), "unit": "GB/s",
         "frac": round(achieved / peak_time_additive, 4) if peak_time_additive else None,
         "traffic": measured_traffic(wl.name) if scale == 1.0 and args.budget is None else None,
@@ -281,6 +323,44 @@ def main():
         "arithmetic_blend_peak": round(peak_arithmetic, 1),
         "arithmetic_blend_frac": round(gathered_bytes / (gather_ms * 1e-3) / 1e9 / peak_arithmetic, 4) if gather_ms else None,
     }
+
+    # the workload's other HBM budgets: placement (cache fill included) and the measured epoch at each
+    budget_sweep = None
+    other = {"cfg3": (0.05, 0.20)}.get(wl.name, ())
+    if other and not args.no_budget_sweep and args.budget is None:
+        budget_sweep = {}
+        for frac in other:
+            bud = int(wl.budget_bytes(frac) * scale)
+            brec = {"sample_ms": [], "gather_ms": [], "epoch_wall_ms": []}
+            place_ms = []
+            for timed in (False, True):
+                torch.cuda.synchronize()
+                e0, e1 = ev(), ev()
+                e0.record()
+                _, bhot = tier.tier_place(ctx, counts, bud, want_slot_map=False)
+                with torch.cuda.stream(gs):
+                    e1.record()
+                epoch(brec if timed else None, e1)
+                if timed:
+                    place_ms.append(e0.elapsed_time(e1))
+            bhits, blinks = epoch_stats(groups)
+            brows = brec["rows"]
+            bh = bhits / brows
+            bd = blinks / (brows - bhits) if brows > bhits else 1.0
+            bpeak = alg_bytes_row / (((1 + bh + (1 - bh) * (1 - bd)) * R + 8) / HBM_PEAK_GBPS + (1 - bh) * bd * R / LINK_PEAK_GBPS)
+            bms = brec["gather_ms"][0]
+            budget_sweep[f"{frac:.2f}"] = {
+                "budget_bytes": bud, "n_hot": bhot, "hit_fraction": round(bh, 4),
+                "place_ms": round(place_ms[0], 3), "epoch_wall_ms": round(brec["epoch_wall_ms"][0], 3),
+                "gather_ms": round(bms, 3), "gather_GBps": round(brows * R / (bms * 1e-3) / 1e9, 2),
+                "host_link_bytes_tiered": blinks * R, "host_link_reduction": round(1 - blinks / brows, 4),
+                "roofline_frac": round(alg_bytes_row * brows / (bms * 1e-3) / 1e9 / bpeak, 4),
+                "step_ms_with_this_budget": round(mean(rec["presample_ms"]) + place_ms[0] + brec["epoch_wall_ms"][0], 3)}
+            log(f"[bench] budget {frac}: {budget_sweep[f'{frac:.2f}']}")
+        budget_sweep["note"] = ("same counts, other budgets: placement (order, slot map, cache fill over the host link) and the "
+                                "measured epoch, timed as in the step; roofline_frac as roofline.frac")
+        tier.tier_place(ctx, counts, budget, want_slot_map=False)
+        torch.cuda.synchronize()
 
     # the two streams on their own: every row from HBM, then every row over the host link
     streams = None
@@ -341,7 +421,7 @@ def main():
                             "gathered_GBps": round(rows * R / (ms * 1e-3) / 1e9, 2) if ms else None}
         tier.tier_set_gather_dedup(ctx, shared_on)
         shared["note"] = ("one pass over the measured epoch, gathers only; shared_misses reads every distinct cold row "
-                          "of a call (16 mini-batches) over the host link once")
+                          "of a call over the host link once")
 
     out = out_buf[0]
     if not args.no_scores:
@@ -382,8 +462,10 @@ def main():
                      "place_sort": round(mean(rec["place_sort_ms"]), 3),
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3),
                      "epoch_wall": round(mean(rec["epoch_wall_ms"]), 3)},
+        "budget_sweep": budget_sweep,
         "gather_launch": {"link_blocks": args.link_blocks, "min_rows": SPLIT_MIN_ROWS, "shared_misses": shared_on,
-                          "mini_batches_per_call": B, "output_rows_held": int(out_buf[0].shape[0]),
+                          "mini_batches_per_call": B, "output_rows_held": rec["most_rows_per_call"],
+                          "groups": group_table,
                           "note": "split launch: the first link_blocks blocks copy the cold rows (host link), all others the "
                                   "hot rows (HBM); uniform_launch_epoch is the same epoch with every block copying both",
                           "uniform_launch_epoch": uniform},
