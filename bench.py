@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for profiler byte counters)")
     ap.add_argument("--cpu-batches", type=int, default=192, help="mini-batches in the CPU baseline's sample")
+    ap.add_argument("--sampler-only", action="store_true",
+                    help="run only the sampler (presampling epoch, then the measured epoch's blocks, no gathers) and print "
+                         "its own JSON line: a clean subject for rocprofv3 runs on the sampling kernels")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -202,6 +205,35 @@ def main():
             record["place_sort_ms"].append(e_pre.elapsed_time(e_sorted))
             record["n_hot"] = n_hot
         return rows, edges
+
+    if args.sampler_only:
+        def timed_ms(f):
+            a, b_ = ev(), ev()
+            torch.cuda.synchronize()
+            a.record(); r = f(); b_.record(); torch.cuda.synchronize()
+            return r, a.elapsed_time(b_)
+        def sample_epoch():
+            e = 0
+            for g in groups:
+                blk = sample_group(g)
+                e += sum(sum(blk.n_edges[i]) for i in range(len(g)))
+            return e
+        pre, smp = [], []
+        for it in range(args.warmup + max(args.steps, 1)):
+            _, t_pre = timed_ms(lambda: tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts))
+            edges_e, t_smp = timed_ms(sample_epoch)
+            if it >= args.warmup:
+                pre.append(t_pre); smp.append(t_smp)
+        _, rows_p, edges_p = tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts, want_totals=True)
+        print(json.dumps({"workload": wl.name, "mini_batches": n_batches, "mini_batches_per_call": B,
+                          "presample_ms": round(min(pre), 3), "presample_rows": rows_p, "presample_edges": edges_p,
+                          "presample_edges_per_s": round(edges_p / (min(pre) * 1e-3)),
+                          "sample_epoch_ms": round(min(smp), 3), "sample_epoch_edges": edges_e,
+                          "sampled_edges_per_s": round(edges_e / (min(smp) * 1e-3)),
+                          "note": "presampling = one epoch in counting mode (up to 64 mini-batches per chain, no blocks); "
+                                  "sample_epoch = the measured epoch's blocks, mini_batches_per_call per call; best of steps"}), flush=True)
+        ctx.close()
+        return
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.int32, device=dev)       # 1 GiB read, 1 GiB written

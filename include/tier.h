@@ -29,8 +29,9 @@
  *     nothing is printed.  tier_strerror names a status; tier_last_hip_error gives
  *     the HIP error behind a TIER_EHIP.
  *   - A context must not be used from two threads at once.
- *   - Node ids are int32 in [0, n_nodes); adjacency lists hold no duplicates;
- *     every degree is below 2^31.
+ *   - Node ids are int32 in [0, n_nodes); every degree is below 2^31.  Adjacency lists
+ *     need not be sorted.  Positions of a list are what is sampled: a list that holds a
+ *     neighbour twice can have it drawn twice (two edges of the block, one frontier node).
  */
 #ifndef TIER_H
 #define TIER_H

@@ -153,3 +153,80 @@ def test_cfg4_fp16_rows_largest_that_can_be_pinned():
     """85.8 GiB of features at full size; where the host cannot pin that much the same
     recipe runs at 2/3 of the nodes, edges and budget (56.6 GiB of 1536-byte rows)."""
     run_config("cfg4", lambda nb: [0, nb - 1], fallback_scale=0.66)
+
+
+def test_cfg4_sampling_counts_and_placement_at_the_configured_size():
+    """The fourth configuration's 85.8 GiB table cannot be pinned on this pool, but presampling,
+    placement and mini-batch sampling do not read feature rows: they run here at the configured
+    60 M nodes / 1.2 G draws over a 16-byte-row table, against the oracle.  The placement keeps as
+    many rows as the configuration's 16 GiB of 1536-byte rows hold.  The tiered gather's 1536-byte
+    path at this node count is then checked with the whole fp16 table in device memory (92 GB: an
+    addressing check of ids, slot map and cache rows at full N, not a host-link measurement)."""
+    wl = synth.WORKLOADS["cfg4"]
+    t0 = time.time()
+    indptr, indices, train = synth.make_graph(wl, DEV, 1.0)
+    torch.cuda.synchronize()
+    n = indptr.numel() - 1
+    assert n == 60_000_000
+    say(f"cfg4 full: graph {n} nodes {indices.numel()} edges ({time.time() - t0:.0f}s)")
+    ip = indptr.cpu().numpy().astype(np.int64); ix = indices.cpu().numpy(); tr = train.cpu().numpy()
+    bs, fan = wl.batch_size, wl.fanouts
+    small = tier.tier_host_alloc(n, 4, torch.float32)                       # 16-byte rows, values irrelevant here
+    try:
+        ctx = tier.tier_create(indptr, indices, small)
+        counts, rows, edges = tier.tier_presample(ctx, train, bs, fan, 1, synth.PRESAMPLE_SEED, want_totals=True)
+        want_counts, wrows, wedges = orc.presample(ip, ix, tr, bs, fan, 1, synth.PRESAMPLE_SEED, threads=16)
+        assert (rows, edges) == (wrows, wedges)
+        assert np.array_equal(counts.cpu().numpy().view(np.uint32), want_counts)
+        say(f"cfg4 full: counts match, {rows} rows {edges} edges ({time.time() - t0:.0f}s)")
+        budget = wl.budget_bytes()                                          # 16 GiB of 1536-byte rows
+        _, oslot, ohot = orc.place(want_counts, wl.row_bytes, budget)
+        assert ohot == budget // wl.row_bytes == 11_184_810
+        slot, n_hot = tier.tier_place(ctx, counts, ohot * 16)               # the same number of 16-byte rows
+        assert n_hot == ohot and np.array_equal(slot.cpu().numpy(), oslot)
+        say(f"cfg4 full: slot map of {n_hot} hot rows matches ({time.time() - t0:.0f}s)")
+        order = synth.random_order(train.numel(), synth.EPOCH_SEED, 1, DEV)
+        ep = train[order].contiguous(); epn = ep.cpu().numpy()
+        n_batches = -(-len(epn) // bs)
+        blocks = tier.Blocks(n, bs, fan, DEV)
+        li = np.full(n, -1, np.int32)
+        frontiers = []
+        for b in (0, n_batches - 1):
+            bseed = tier.tier_batch_seed(synth.EPOCH_SEED, 0, b)
+            got = tier.tier_sample_minibatch(ctx, ep[b * bs:(b + 1) * bs], fan, bseed, blocks)
+            want = orc.sample_minibatch(ip, ix, epn[b * bs:(b + 1) * bs], fan, bseed, local_idx=li)
+            assert got.n_nodes == want["n_nodes"].tolist() and got.n_edges == want["n_edges"].tolist()
+            assert np.array_equal(got.frontier().cpu().numpy(), want["nodes"])
+            for l in range(len(fan)):
+                nd, ne = got.n_nodes[l], got.n_edges[l]
+                assert np.array_equal(got.row_ptr[l][: nd + 1].cpu().numpy(), want["row_ptr"][l])
+                assert np.array_equal(got.eid[l][:ne].cpu().numpy(), want["eid"][l])
+                assert np.array_equal(got.col[l][:ne].cpu().numpy(), want["col"][l])
+            frontiers.append(got.frontier().clone())
+            say(f"cfg4 full: batch {b}: {got.n_nodes[-1]} rows, {sum(got.n_edges)} edges match ({time.time() - t0:.0f}s)")
+        ctx.close()
+    finally:
+        small.free()
+    del ip, ix
+
+    # a5 at full N with 1536-byte rows: the table in device memory
+    table = torch.empty((n, wl.dim), dtype=torch.float16, device=DEV)
+    synth.fill_features(table, wl.dist, synth.GRAPH_SEED + 2, DEV)
+    ctx = tier.tier_create(indptr, indices, table)
+    try:
+        slot, n_hot = tier.tier_place(ctx, counts, budget)
+        assert n_hot == ohot and np.array_equal(slot.cpu().numpy(), oslot)
+        hot = oslot >= 0
+        for f in frontiers:
+            out, hit, miss = tier.tier_gather_features(ctx, f, want_stats=True)
+            whit = int(hot[f.cpu().numpy()].sum())
+            assert (hit, miss) == (whit, f.numel() - whit)
+            assert torch.equal(out, table[f.long()])                        # library indexing of the same table
+        tier.tier_set_gather_split(ctx, 64, 0)
+        ids = torch.cat(frontiers)
+        out, hit, miss = tier.tier_gather_features(ctx, ids, want_stats=True)
+        assert torch.equal(out, table[ids.long()]) and hit == int(hot[ids.cpu().numpy()].sum())
+        say(f"cfg4 full: {ids.numel()} rows of 1536 bytes gathered from a device table of {table.numel() * 2 / 2**30:.1f} GiB, "
+            f"{hit} from the cache ({time.time() - t0:.0f}s)")
+    finally:
+        ctx.close()

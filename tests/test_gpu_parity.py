@@ -181,6 +181,42 @@ def test_blocks_large_frontier_spans_many_tiles(seg_words):
         w.close()
 
 
+@pytest.mark.parametrize("seg_words", [None, 32], ids=["seg1", "seg32"])
+def test_repeated_and_unsorted_neighbours(seg_words):
+    """Adjacency lists as a caller may hand them over: not sorted, with repeated entries (the
+    generator of the other tests sorts and dedups).  Positions are what is sampled, so both
+    sides must still agree on blocks, counts and gathered rows."""
+    rng = np.random.default_rng(2024)
+    n, m = 3000, 45_000
+    dst = rng.integers(0, n, m)
+    src = rng.integers(0, n, m)
+    src[: m // 3] = rng.integers(0, 40, m // 3)                    # a few sources repeat often in many lists
+    order = np.lexsort((rng.random(m), dst))                        # rows grouped by dst, random order inside
+    dst, src = dst[order], src[order]
+    indptr = np.zeros(n + 1, np.int64); np.add.at(indptr, dst + 1, 1); indptr = np.cumsum(indptr)
+    lists = [src[indptr[v]:indptr[v + 1]] for v in range(n)]
+    assert any(len(l) != len(set(l)) for l in lists) and any(list(l) != sorted(l) for l in lists)
+    w = World(torch.from_numpy(indptr), torch.from_numpy(src.astype(np.int32)), dim=8, seg_words=seg_words)
+    try:
+        for fanouts, n_seeds in (((10, 5), 200), ((3, 3, 3), 64), ((40,), 500)):
+            seeds = rng.choice(n, n_seeds, replace=False).astype(np.int32)
+            got, want = compare_blocks(w, seeds, fanouts, 17 + n_seeds)
+        train = rng.choice(n, 900, replace=False).astype(np.int32)
+        wantc, wrows, wedges = orc.presample(w.indptr, w.indices, train, 100, (10, 5), 2, 5894, threads=2)
+        gotc, rows, edges = tier.tier_presample(w.ctx, torch.from_numpy(train).to(DEV), 100, (10, 5), 2, 5894, want_totals=True)
+        assert np.array_equal(gotc.cpu().numpy().view(np.uint32), wantc) and (rows, edges) == (wrows, wedges)
+        slot, n_hot = tier.tier_place(w.ctx, gotc, 700 * w.row_bytes)
+        _, oslot, ohot = orc.place(wantc, w.row_bytes, 700 * w.row_bytes)
+        assert n_hot == ohot and np.array_equal(slot.cpu().numpy(), oslot)
+        out, hit, miss = tier.tier_gather_features(w.ctx, got.frontier(), want_stats=True)
+        cache = orc.fill_cache(w.feat_bytes, oslot, ohot)
+        wout, whit, wmiss = orc.gather(w.feat_bytes, cache, oslot, want["nodes"])
+        assert (hit, miss) == (whit, wmiss)
+        assert np.array_equal(out.view(torch.uint8).cpu().numpy().reshape(len(want["nodes"]), -1), wout)
+    finally:
+        w.close()
+
+
 # ------------------------------------------------------------------------------
 # access counts
 # ------------------------------------------------------------------------------
