@@ -242,7 +242,8 @@ int tier_relabel_ids(tier_ctx *ctx, const int32_t *rank, const int32_t *ids, int
  * indexed by id - n_hot) and reads no map.  Replaces any earlier placement.  Waits. */
 int tier_place_boundary(tier_ctx *ctx, uint64_t budget_bytes, int64_t *n_hot);
 
-/* One mini-batch (Sec. 2.2).  seeds: (device) n_seeds distinct node ids.  At hop l
+/* One mini-batch (Sec. 2.2).  seeds: (device) n_seeds distinct node ids (an id outside the
+ * graph or a repeated seed makes the call return TIER_EINVAL, its outputs undefined).  At hop l
  * every node of frontier_l draws min(fanouts[l], degree) distinct neighbours
  * uniformly at random (all of them, in adjacency order, when degree <= fanouts[l]);
  * draws are a pure function of (seed, node, hop, draw index), so a mini-batch is

@@ -286,13 +286,23 @@ __global__ __launch_bounds__(kBlock) void k_init_seeds(wide_t w, int gx, const O
         v.beg[i] = (int64_t)first_edge;
         v.deg[i] = (int32_t)(indptr[u + 1] - first_edge);
         const uint32_t word = (uint32_t)u >> 5, bit = 1u << (u & 31);
+        bool twice = false;                          // the seeds of a mini-batch must be distinct
         if (MODE == MODE_COUNT_SMALL) {
-            atomicOr(&v.fresh[word], bit);
+            twice = (atomicOr(&v.fresh[word], bit) & bit) != 0u;
             atomicOr(&v.aux[word], bit);
         } else {
-            index_insert_cas(v.table, w.table_log2, home_of((uint32_t)u, w.table_log2), (uint32_t)i);
+            __threadfence();                         // nodes[i] before the cell that points to it
+            const uint32_t mask = (1u << w.table_log2) - 1u;
+            uint32_t h = home_of((uint32_t)u, w.table_log2);
+            for (;;) {
+                const uint32_t cell = atomicCAS(&v.table[h], 0u, (uint32_t)i + 1u);
+                if (cell == 0u) break;
+                if (__hip_atomic_load(&v.nodes[cell - 1u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == u) twice = true;
+                h = (h + 1u) & mask;
+            }
             if (MODE == MODE_COUNT_LARGE) atomicOr(&v.aux[word], bit);
         }
+        if (twice) atomicOr((int *)&w.meta[META_ERROR], 1);
     }
 }
 
@@ -554,12 +564,14 @@ __global__ __launch_bounds__(kBlock) void k_bm_partial(wide_t w, int gx)
 
 // The new nodes of one bitmap word, ascending, to nodes[pos ..); keep == 0: each also enters the
 // frontier index (first half: a plain store into an empty home cell).
-__device__ inline int64_t emit_word(const slot_view &v, int table_log2, int64_t word, uint32_t bits, int64_t pos, int keep)
+__device__ inline int64_t emit_word(const slot_view &v, int table_log2, int64_t cap, int64_t word, uint32_t bits, int64_t pos,
+                                    int keep)
 {
     while (bits) {
         const int b = __ffs(bits) - 1;
         bits &= bits - 1;
         const int32_t u = (int32_t)(word * 32 + b);
+        if (pos >= cap) break;                       // only after repeated seeds (an error the call reports)
         v.nodes[pos] = u;
         if (!keep) {
             const uint32_t h = home_of((uint32_t)u, table_log2);
@@ -576,7 +588,7 @@ __device__ inline int64_t emit_word(const slot_view &v, int table_log2, int64_t 
 // on into `all`).  keep != 0 (last hop of a block call): nothing draws from them; the segment's
 // start position is recorded for k_relabel and the bits stay until k_finish.
 template <int MODE>
-__global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer, int keep)
+__global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer, int keep, int64_t cap_next)
 {
     __shared__ int s_wave[kBlock / 64];
     __shared__ int s_list[kSegTile];
@@ -589,7 +601,9 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer,
     int carry, all;
     partial_prefix(p, v.partial_bm, carry, all, s_wave);
     const int64_t base = v.meta[META_NFRONT + layer];
-    if (p.bx == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all;
+    // cap_next = the bound of tier_blocks_bounds on the next frontier; only repeated seeds (an error
+    // the call reports) can take the sum beyond it
+    if (p.bx == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all < cap_next ? base + all : cap_next;
     if (w.seg_log2 == 0) {
         for (int64_t tile = lo; tile < hi; tile += kBlock) {
             const int64_t i = tile + threadIdx.x;
@@ -606,7 +620,7 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer,
                     v.fresh[i] = 0u;
                     if (MODE == MODE_COUNT_LARGE) v.aux[i] |= bits;      // this thread alone owns the word here
                 }
-                emit_word(v, w.table_log2, i, bits, base + before, keep);
+                emit_word(v, w.table_log2, cap_next, i, bits, base + before, keep);
             }
         }
         return;
@@ -648,10 +662,10 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer,
                 }
                 const int64_t word = (seg << 5) + lane8 * 4;
                 int64_t pos = base + before + ahead;
-                pos = emit_word(v, w.table_log2, word, piece.x, pos, keep);
-                pos = emit_word(v, w.table_log2, word + 1, piece.y, pos, keep);
-                pos = emit_word(v, w.table_log2, word + 2, piece.z, pos, keep);
-                emit_word(v, w.table_log2, word + 3, piece.w, pos, keep);
+                pos = emit_word(v, w.table_log2, cap_next, word, piece.x, pos, keep);
+                pos = emit_word(v, w.table_log2, cap_next, word + 1, piece.y, pos, keep);
+                pos = emit_word(v, w.table_log2, cap_next, word + 2, piece.z, pos, keep);
+                emit_word(v, w.table_log2, cap_next, word + 3, piece.w, pos, keep);
             }
         }
         carry += tot & 0xfffff;
@@ -700,7 +714,7 @@ __global__ __launch_bounds__(kBlock) void k_bm_partial_flat(wide_t w, int gx)
     if (threadIdx.x == 0) v.partial_bm[p.bx] = tot;
 }
 
-__global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int gx, int layer)
+__global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int gx, int layer, int64_t cap_next)
 {
     __shared__ int s_wave[kBlock / 64];
     spot_t p;
@@ -711,7 +725,9 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int gx, int l
     int carry, all;
     partial_prefix(p, v.partial_bm, carry, all, s_wave);
     const int64_t base = v.meta[META_NFRONT + layer];
-    if (p.bx == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all;
+    // cap_next = the bound of tier_blocks_bounds on the next frontier; only repeated seeds (an error
+    // the call reports) can take the sum beyond it
+    if (p.bx == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all < cap_next ? base + all : cap_next;
     for (int64_t tile = lo; tile < hi; tile += kBlock) {
         const int64_t i = tile + threadIdx.x;
         const uint32_t cur = i < hi ? v.fresh[i] : 0u;
@@ -724,7 +740,7 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit_flat(wide_t w, int gx, int l
             while (bits) {
                 int b = __ffs(bits) - 1;
                 bits &= bits - 1;
-                v.nodes[pos] = (int32_t)(i * 32 + b);
+                if (pos < cap_next) v.nodes[pos] = (int32_t)(i * 32 + b);
                 ++pos;
             }
         }
@@ -912,6 +928,12 @@ __global__ void k_clear_totals(int64_t *meta)
     meta[META_TOTAL_EDGES] = 0;
 }
 
+// Blocks per slot of the kernels whose blocks loop over their slot's items.  The bounds the grids are
+// sized from are several times the real sizes (degrees below the fanout, repeated neighbours), and a
+// slot is served by one XCD, which holds 256 blocks at a time: more blocks than twice that only queue
+// up to find nothing to do (measured best of 128 / 256 / 512 / 1024 and no cap).
+constexpr int kLoopBlocks = 512;
+
 int clamp_grid(int64_t items, int per_block, int cap)
 {
     int64_t g = (items + per_block - 1) / per_block;
@@ -934,7 +956,7 @@ bool large_graph(const tier_ctx *c) { return c->seg_log2 != 0; }
 template <int G, int MODE>
 void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, bool last, const wide_out &o)
 {
-    const int gx = clamp_grid(cap_dst, (kBlock / G) * kAtOnce, 16384);
+    const int gx = clamp_grid(cap_dst, (kBlock / G) * kAtOnce, kLoopBlocks);
     k_hop_sample<G, MODE><<<grid_of(gx, w.n_slots), kBlock, 0, c->stream>>>(
         w, gx, c->indices, layer, k, last ? 1 : 0, MODE == MODE_BLOCKS ? o.layer[layer] : layer_out_t{});
 }
@@ -943,7 +965,7 @@ template <int MODE>
 void launch_hop(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, bool last, const wide_out &o)
 {
     if (MODE == MODE_BLOCKS) {
-        const int gx = clamp_grid(cap_dst, kBlock, TIER_SCAN_BLOCKS);
+        const int gx = clamp_grid(cap_dst, kBlock, kLoopBlocks);
         const unsigned grid = grid_of(gx, w.n_slots);
         k_hop_partial<<<grid, kBlock, 0, c->stream>>>(w, gx, layer, k);
         k_hop_rowptr<<<grid, kBlock, 0, c->stream>>>(w, gx, layer, k, o.layer[layer]);
@@ -976,13 +998,13 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
         if (MODE != MODE_BLOCKS && last) break;               // counted from the bitmaps, never listed
         if (MODE == MODE_COUNT_SMALL) {
             k_bm_partial_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx);
-            k_bm_emit_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx, l);
+            k_bm_emit_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx, l, cap_nodes[l + 1]);
         } else {
             k_bm_partial<<<grid_of(seg_gx, slots), kBlock, 0, st>>>(w, seg_gx);
-            k_bm_emit<MODE><<<grid_of(seg_gx, slots), kBlock, 0, st>>>(w, seg_gx, l, last ? 1 : 0);
+            k_bm_emit<MODE><<<grid_of(seg_gx, slots), kBlock, 0, st>>>(w, seg_gx, l, last ? 1 : 0, cap_nodes[l + 1]);
         }
         if (!last) {
-            const int gx = clamp_grid(cap_nodes[l + 1], kBlock, 4096);
+            const int gx = clamp_grid(cap_nodes[l + 1], kBlock, kLoopBlocks);
             k_settle<MODE, OffT><<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, indptr, l);
         }
     }
@@ -995,7 +1017,7 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
             r.stride[l] = o.layer[l].edge_stride;
             if (cap_edges[l] > most) most = cap_edges[l];
         }
-        const int gx = clamp_grid(most, kBlock, 4096);
+        const int gx = clamp_grid(most, kBlock, kLoopBlocks);
         k_relabel<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, r);
     } else {
         k_count_columns<<<clamp_grid(c->n_words, kBlock, 1 << 22), kBlock, 0, st>>>(w, MODE == MODE_COUNT_LARGE ? 1 : 0,
@@ -1003,7 +1025,7 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
     }
     if (MODE != MODE_COUNT_SMALL) {
         const int64_t cells4 = (1ll << w.table_log2) / 4;
-        const int gx = clamp_grid(cells4 > w.n_seg ? cells4 : w.n_seg, 4 * kBlock, 2048);
+        const int gx = clamp_grid(cells4 > w.n_seg ? cells4 : w.n_seg, 4 * kBlock, kLoopBlocks);
         k_finish<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, MODE == MODE_BLOCKS ? 1 : 0);
     }
     TIER_HIP(c, hipGetLastError());

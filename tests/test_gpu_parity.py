@@ -132,6 +132,11 @@ def test_blocks_bad_arguments(small):
     bad = torch.tensor([1, small.n], dtype=torch.int32, device=DEV)           # id out of range: reported, no fault
     with pytest.raises(tier.TierError):
         tier.tier_sample_minibatch(small.ctx, bad, (3,), 1)
+    twice = torch.tensor([5, 9, 5, 7], dtype=torch.int32, device=DEV)         # a repeated seed: reported as well
+    with pytest.raises(tier.TierError):
+        tier.tier_sample_minibatch(small.ctx, twice, (3, 2), 1)
+    with pytest.raises(tier.TierError):
+        tier.tier_presample(small.ctx, twice, 4, (3, 2), 1, 1, want_totals=True)
     compare_blocks(small, np.arange(10, dtype=np.int32), (3,), 1)             # context still good
 
 
