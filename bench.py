@@ -206,6 +206,13 @@ def main():
             record["n_hot"] = n_hot
         return rows, edges
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)       # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        torch.bitwise_not(src, out=dst)                                # a plain streaming kernel, by name in the trace
+        torch.cuda.synchronize()
+        del src, dst
+
     if args.sampler_only:
         def timed_ms(f):
             a, b_ = ev(), ev()
@@ -234,13 +241,6 @@ def main():
                                   "sample_epoch = the measured epoch's blocks, mini_batches_per_call per call; best of steps"}), flush=True)
         ctx.close()
         return
-
-    if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)       # 1 GiB read, 1 GiB written
-        dst = torch.empty_like(src)
-        torch.bitwise_not(src, out=dst)                                # a plain streaming kernel, by name in the trace
-        torch.cuda.synchronize()
-        del src, dst
 
     for _ in range(args.warmup):
         step(None)
