@@ -123,6 +123,7 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipFree(ctx->f_beg);
     (void)hipFree(ctx->f_deg);
     (void)hipFree(ctx->slot);
+    (void)hipFree(ctx->hot_bits);
     (void)hipFree(ctx->cache);
     (void)hipStreamSynchronize(ctx->gather_stream);
     (void)hipFree(ctx->claim);
@@ -188,6 +189,7 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     TIER_HIP(c, hipMalloc(&c->flag, (size_t)flags4 * 4));
     TIER_HIP(c, hipMalloc(&c->segbase, (size_t)segs * sizeof(int32_t)));
     TIER_HIP(c, hipMalloc(&c->slot, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
+    TIER_HIP(c, hipMalloc(&c->hot_bits, (size_t)(c->n_words > 0 ? c->n_words : 1) * sizeof(uint32_t)));
     TIER_HIP(c, hipMalloc(&c->meta, S * META_WORDS * sizeof(int64_t)));
     TIER_HIP(c, hipHostMalloc((void **)&c->meta_host, S * META_WORDS * sizeof(int64_t), hipHostMallocDefault));
     TIER_HIP(c, hipMalloc(&c->gmeta, GMETA_WORDS * sizeof(int64_t)));
@@ -199,6 +201,7 @@ static int create_impl(tier_ctx *c, const tier_csr *csr, const tier_feat *feat)
     k_fill_i32<<<grid_for(words, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->aux, words, 0);
     k_fill_i32<<<grid_for(flags4, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->flag, flags4, 0);
     k_fill_i32<<<grid_for(n, 256, 8192), 256, 0, c->stream>>>(c->slot, n, -1);          // nothing placed yet
+    k_fill_i32<<<grid_for(c->n_words, 256, 8192), 256, 0, c->stream>>>((int32_t *)c->hot_bits, c->n_words, 0);
     k_fill_i32<<<1, 64, 0, c->stream>>>((int32_t *)c->gmeta, GMETA_WORDS * 2, 0);
     k_fill_i32<<<4, 256, 0, c->stream>>>((int32_t *)c->meta, (int64_t)S * META_WORDS * 2, 0);
     TIER_HIP(c, hipGetLastError());

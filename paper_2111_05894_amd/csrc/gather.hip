@@ -51,11 +51,14 @@ struct cold_t {
 };
 
 // An id outside the graph is nobody's cold row: the blocks that copy hot rows write its row of zeros.
+// The cold workers only need to know whether a row is placed, not where: one bit per node
+// (tier_place builds it beside the slot map) instead of the 4-byte slot, whose 128-byte line
+// the hot blocks fetch anyway.  The bitmap is 1/32 of the map and mostly stays in cache.
 template <int MODE>
-__device__ inline int is_cold(int32_t id, const int32_t *__restrict__ slot, int64_t n_nodes, int64_t n_hot)
+__device__ inline int is_cold(int32_t id, const uint32_t *__restrict__ hot_bits, int64_t n_nodes, int64_t n_hot)
 {
     if ((uint32_t)id >= (uint64_t)n_nodes) return 0;
-    return MODE == GATHER_SLOT ? slot[id] < 0 : id >= n_hot;
+    return MODE == GATHER_SLOT ? !((hot_bits[(uint32_t)id >> 5] >> (id & 31)) & 1u) : id >= n_hot;
 }
 
 // The cold workers of a split launch: the first `workers` blocks of grid row 0.  The
@@ -69,7 +72,7 @@ __device__ inline int is_cold(int32_t id, const int32_t *__restrict__ slot, int6
 // copies never wait for any of them.  The last wave to run dry leaves both counters at
 // zero for the next launch on the stream.
 template <int LPR, int MODE, bool DEDUP>
-__device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, const int32_t *__restrict__ slot,
+__device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, const uint32_t *__restrict__ hot_bits,
                                       int64_t n_nodes, int64_t n_hot, const cold_t &cold,
                                       const uint4 *__restrict__ host, uint4 *__restrict__ out_base, int cpr,
                                       int64_t *__restrict__ meta, int count_rows)
@@ -116,7 +119,7 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
         const int64_t i = c * 64 + lane64;
         if (i < lists.n[b]) u.id = lists.ids[b][i];
     };
-    auto classify = [&](unit_t &u) { u.fetch = u.id >= 0 ? is_cold<MODE>(u.id, slot, n_nodes, n_hot) : 0; };
+    auto classify = [&](unit_t &u) { u.fetch = u.id >= 0 ? is_cold<MODE>(u.id, hot_bits, n_nodes, n_hot) : 0; };
 
     // shared misses: the first request of an id in this call fetches the row, the others
     // get a deferred copy from that request's output row
@@ -264,6 +267,7 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
 //         and skips its cold rows.  DEDUP: the workers fetch every distinct cold row once.
 template <int LPR, int MODE, bool SPLIT, bool DEDUP>
 __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32_t *__restrict__ slot,
+                                                   const uint32_t *__restrict__ hot_bits,
                                                    const uint4 *__restrict__ cache,
                                                    const uint4 *__restrict__ host,
                                                    uint4 *__restrict__ out_base, int cpr, int64_t n_nodes,
@@ -272,7 +276,7 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
 {
     constexpr int kGroups = kBlock / LPR;
     if (SPLIT && blockIdx.y == 0) {
-        scan_cold_rows<LPR, MODE, DEDUP>(lists, (int)gridDim.y - 1, slot, n_nodes, n_hot, cold, host, out_base, cpr,
+        scan_cold_rows<LPR, MODE, DEDUP>(lists, (int)gridDim.y - 1, hot_bits, n_nodes, n_hot, cold, host, out_base, cpr,
                                          meta, count_hits);
         return;
     }
@@ -452,7 +456,7 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
     }
     const dim3 grid((unsigned)blocks, (unsigned)(n_lists + (split ? 1 : 0)));
 #define GATHER_LAUNCH(L, M, P, D)                                                                    \
-    k_gather<L, M, P, D><<<grid, kBlock, 0, st>>>(lists, ctx->slot, (const uint4 *)ctx->cache,       \
+    k_gather<L, M, P, D><<<grid, kBlock, 0, st>>>(lists, ctx->slot, ctx->hot_bits, (const uint4 *)ctx->cache, \
                                                   (const uint4 *)ctx->host_rows, (uint4 *)out, cpr,  \
                                                   ctx->n_nodes, ctx->n_hot, meta, count_hits ? 1 : 0, cold)
 #define GATHER_CASE(L)                                                                               \

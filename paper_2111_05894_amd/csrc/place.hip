@@ -190,6 +190,20 @@ __global__ void k_slot_map(const int32_t *__restrict__ order, int64_t n, int64_t
         slot[order[r]] = r < n_hot ? (int32_t)r : -1;
 }
 
+// hot_bits: bit v set <=> slot[v] >= 0.  One thread per word reads its 32 slots in order.
+__global__ void k_hot_bits(const int32_t *__restrict__ slot, int64_t n, uint32_t *__restrict__ hot_bits)
+{
+    const int64_t n_words = (n + 31) / 32;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; w < n_words; w += stride) {
+        uint32_t bits = 0u;
+        const int64_t first = w * 32;
+        const int lim = n - first < 32 ? (int)(n - first) : 32;
+        for (int b = 0; b < lim; ++b) bits |= (slot[first + b] >= 0 ? 1u : 0u) << b;
+        hot_bits[w] = bits;
+    }
+}
+
 __global__ void k_zero_u64(unsigned long long *p) { *p = 0; }
 
 int grid_for(int64_t n, int block, int cap)
@@ -321,7 +335,10 @@ static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget
     ctx->placed = false;
     ctx->boundary = false;
     ctx->n_hot = 0;
-    if (n > 0) k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n, n_hot, ctx->slot);
+    if (n > 0) {
+        k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n, n_hot, ctx->slot);
+        k_hot_bits<<<grid_for((n + 31) / 32, 256, 4096), 256, 0, st>>>(ctx->slot, n, ctx->hot_bits);
+    }
     TIER_HIP(ctx, hipGetLastError());
 
     // (re)build the HBM cache: cache row r = feature row of the node of rank r

@@ -84,6 +84,7 @@ struct tier_ctx {
     size_t table_cap;        // bytes
     // placement
     int32_t *slot;           // n_nodes
+    uint32_t *hot_bits;      // ceil(n_nodes / 32): bit v set <=> slot[v] >= 0 (what the split gather's cold workers ask)
     uint8_t *cache;          // n_hot * row_bytes
     size_t cache_cap;        // bytes allocated (kept across placements, grown on demand)
     tier_sort_bufs sort;
