@@ -120,6 +120,11 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipFree(ctx->flag);
     (void)hipFree(ctx->segbase);
     (void)hipFree(ctx->table);
+    (void)hipFree(ctx->part_rec);
+    (void)hipFree(ctx->part_rank);
+    (void)hipFree(ctx->part_stage);
+    (void)hipFree(ctx->part_rows);
+    (void)hipFree(ctx->part_bk);
     (void)hipFree(ctx->f_beg);
     (void)hipFree(ctx->f_deg);
     (void)hipFree(ctx->slot);

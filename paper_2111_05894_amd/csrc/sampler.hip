@@ -70,6 +70,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kXcds = 8;             // XCDs of an MI355X; workgroup i of a launch runs on XCD i % 8
+constexpr int kPartBlocks = 32;      // blocks per slot that sort the last hop's new neighbours into buckets
 
 enum { MODE_BLOCKS = 0, MODE_COUNT_SMALL = 1, MODE_COUNT_LARGE = 2 };
 
@@ -101,6 +102,15 @@ struct wide_t {
     int64_t *meta;               // [slot][META_WORDS]; totals and the error flag live in slot 0
     int32_t *partial_hop;        // [slot][TIER_SCAN_BLOCKS]
     int32_t *partial_bm;         // [slot][TIER_SCAN_BLOCKS]
+    // last hop of a block call by buckets (n_buckets != 0): see k_part_hist
+    unsigned long long *rec;     // [slot][rec_stride]  node << 32 | edge, grouped by bucket
+    int32_t *lrank;              // [slot][rec_stride]  rank of the record's node among its bucket's distinct nodes
+    int32_t *stage;              // [slot][rec_stride]  a bucket's distinct nodes, ascending, from the bucket's start
+    int64_t rec_stride;
+    int32_t *rows;               // [slot][kPartBlocks][n_buckets]
+    int32_t *bk;                 // [slot][3][n_buckets + 1]
+    int32_t n_buckets;           // 0: the last hop marks `fresh` like the others
+    int32_t bucket_log2;         // a bucket is 1 << bucket_log2 consecutive node ids
     uint32_t key0[TIER_MAX_BATCHES], key1[TIER_MAX_BATCHES];   // halves of each slot's seed
 };
 
@@ -130,6 +140,13 @@ struct slot_view {
     int64_t *meta;
     int32_t *partial_hop;
     int32_t *partial_bm;
+    unsigned long long *rec;
+    int32_t *lrank;
+    int32_t *stage;
+    int32_t *rows;
+    int32_t *bk_start;           // [n_buckets + 1] first record of a bucket; the last entry is the number of records
+    int32_t *bk_cnt;             // [n_buckets]     distinct nodes of a bucket
+    int32_t *bk_before;          // [n_buckets]     distinct nodes of the buckets before it
 };
 
 // Which slot and which of the slot's gx blocks this workgroup is.  The launch has
@@ -168,6 +185,13 @@ __device__ inline slot_view view_of(const wide_t &w, int slot)
     v.meta = w.meta + s * META_WORDS;
     v.partial_hop = w.partial_hop + s * TIER_SCAN_BLOCKS;
     v.partial_bm = w.partial_bm + s * TIER_SCAN_BLOCKS;
+    v.rec = w.rec + s * w.rec_stride;
+    v.lrank = w.lrank + s * w.rec_stride;
+    v.stage = w.stage + s * w.rec_stride;
+    v.rows = w.rows + s * kPartBlocks * (int64_t)w.n_buckets;
+    v.bk_start = w.bk + s * 3 * (int64_t)(w.n_buckets + 1);
+    v.bk_cnt = v.bk_start + (w.n_buckets + 1);
+    v.bk_before = v.bk_cnt + (w.n_buckets + 1);
     return v;
 }
 
@@ -232,6 +256,26 @@ __device__ inline int block_excl_scan(int x, int &total, int *s_wave)
     int base = 0, tot = 0;
 #pragma unroll
     for (int i = 0; i < kBlock / 64; ++i) {
+        int t = s_wave[i];
+        base += (i < w) ? t : 0;
+        tot += t;
+    }
+    total = tot;
+    return base + incl - x;
+}
+
+// The same for a block of NW waves.
+template <int NW>
+__device__ inline int block_excl_scan_n(int x, int &total, int *s_wave)
+{
+    const int incl = wave_incl_scan(x);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 63) s_wave[w] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
         int t = s_wave[i];
         base += (i < w) ? t : 0;
         tot += t;
@@ -364,7 +408,7 @@ constexpr int kAtOnce = 4;       // dst nodes a lane group works on at a time
 // stage by stage, so that the reads of one stage are in flight together.
 template <int G, int MODE>
 __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const int32_t *__restrict__ indices, int layer,
-                                                       int k, int last, layer_out_t o)
+                                                       int k, int last, int mark, layer_out_t o)
 {
     __shared__ int s_wave[kBlock / 64];
     constexpr int kGroups = kBlock / G;
@@ -469,7 +513,7 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const i
                 eid[rp[j] + lane] = beg[j] + pos[j];
                 col[rp[j] + lane] = at >= 0 ? at : ~u[j];        // negative: new at this hop, k_relabel finds its place
             }
-            if (at < 0) {
+            if (at < 0 && mark) {                                // mark == 0: the k_part_* kernels read ~node from col[]
                 const uint32_t word = (uint32_t)u[j] >> 5, bit = 1u << (u[j] & 31);
                 if (MODE == MODE_COUNT_LARGE && last) {
                     atomicOr(&v.aux[word], bit);                 // nobody lists the last hop's nodes: straight into `all`
@@ -698,6 +742,290 @@ __global__ __launch_bounds__(kBlock) void k_settle(wide_t w, int gx, const OffT 
     }
 }
 
+// ---- last hop of a block call on the large-graph layout: buckets instead of the bitmap ----------
+// Nothing draws from the nodes reached at the last hop, but they are most of a mini-batch, and on a
+// graph of 10^8 nodes every one of them sits alone in its 128-byte line of `fresh`: an atomic to set
+// the bit, then the line read again to count, to list, to relabel and to clear.  Instead
+// k_hop_sample leaves ~node in col[] (as it does anyway) and sets nothing, and the edges whose
+// neighbour is new are sorted by node id into buckets of 2^bucket_log2 consecutive ids (at most
+// 8192 buckets, a few dozen records each), with LDS atomics only:
+//   k_part_hist     each of kPartBlocks blocks per slot counts its share of the edges per bucket
+//   k_part_cols     per bucket: records of the blocks before each block, and of all blocks
+//   k_part_scan     first record of every bucket
+//   k_part_scatter  records (node, edge) to their bucket's range (order inside a bucket: any)
+//   k_part_bucket   one wave per bucket: the bucket's nodes as a bitmap in LDS -> distinct nodes,
+//                   ascending, and the rank of every record's node among them
+//   k_part_scan     distinct nodes before every bucket; size of the final frontier
+//   k_part_final    col[] of the records' edges and the new nodes appended to the frontier
+// A slot's records, counts and lists stay in its XCD's L2 like the frontier index.
+
+__global__ __launch_bounds__(kBlock) void k_part_hist(wide_t w, int layer, layer_out_t o)
+{
+    extern __shared__ int s_bins[];
+    spot_t p;
+    if (!my_spot(w, kPartBlocks, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int32_t *col = o.col + (int64_t)p.slot * o.edge_stride;
+    for (int i = threadIdx.x; i < w.n_buckets; i += kBlock) s_bins[i] = 0;
+    __syncthreads();
+    int64_t lo, hi;
+    block_range(p, v.meta[META_NEDGES + layer], lo, hi);
+    for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += 4 * kBlock) {
+        int32_t c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[j] = e0 + j * kBlock < hi ? col[e0 + j * kBlock] : 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (c[j] < 0) atomicAdd(&s_bins[(uint32_t)~c[j] >> w.bucket_log2], 1);
+    }
+    __syncthreads();
+    int32_t *row = v.rows + (int64_t)p.bx * w.n_buckets;
+    for (int i = threadIdx.x; i < w.n_buckets; i += kBlock) row[i] = s_bins[i];
+}
+
+// One thread per bucket: rows[b][i] becomes the records of bucket i in the blocks before b, and
+// bk_start[i] the records of bucket i in all blocks (k_part_scan turns them into start positions).
+__global__ __launch_bounds__(kBlock) void k_part_cols(wide_t w, int gx)
+{
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int i = p.bx * kBlock + threadIdx.x;
+    if (i >= w.n_buckets) return;
+    int32_t t[kPartBlocks];
+#pragma unroll
+    for (int b = 0; b < kPartBlocks; ++b) t[b] = v.rows[(int64_t)b * w.n_buckets + i];
+    int32_t run = 0;
+#pragma unroll
+    for (int b = 0; b < kPartBlocks; ++b) {
+        v.rows[(int64_t)b * w.n_buckets + i] = run;
+        run += t[b];
+    }
+    v.bk_start[i] = run;
+}
+
+constexpr int kScanThreads = 1024;
+
+// One block per slot, exclusive prefix sum over the buckets.  which == 0: bk_start[] in place (records
+// per bucket -> first record), the total to bk_start[n_buckets].  which == 1: bk_cnt[] -> bk_before[],
+// and the size of the final frontier (at most cap_next: the bound of tier_blocks_bounds; only
+// repeated seeds, which the call reports, can take the sum beyond it).
+__global__ __launch_bounds__(kScanThreads) void k_part_scan(wide_t w, int which, int layer, int64_t cap_next)
+{
+    __shared__ int s_wave[kScanThreads / 64];
+    spot_t p;
+    if (!my_spot(w, 1, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int32_t *in = which ? v.bk_cnt : v.bk_start;
+    int32_t *out = which ? v.bk_before : v.bk_start;
+    const int nb = w.n_buckets;
+    int carry = 0;
+    for (int tile = 0; tile < nb; tile += 4 * kScanThreads) {
+        const int first = tile + 4 * (int)threadIdx.x;
+        int x[4], sum = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            x[j] = first + j < nb ? in[first + j] : 0;
+            sum += x[j];
+        }
+        int tot;
+        int run = carry + block_excl_scan_n<kScanThreads / 64>(sum, tot, s_wave);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (first + j < nb) out[first + j] = run;
+            run += x[j];
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) {
+        if (which == 0) {
+            out[nb] = carry;
+        } else {
+            const int64_t base = v.meta[META_NFRONT + layer];
+            v.meta[META_NFRONT + layer + 1] = base + carry < cap_next ? base + carry : cap_next;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_part_scatter(wide_t w, int layer, layer_out_t o)
+{
+    extern __shared__ int s_bins[];
+    spot_t p;
+    if (!my_spot(w, kPartBlocks, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int32_t *col = o.col + (int64_t)p.slot * o.edge_stride;
+    const int32_t *row = v.rows + (int64_t)p.bx * w.n_buckets;
+    for (int i = threadIdx.x; i < w.n_buckets; i += kBlock) s_bins[i] = v.bk_start[i] + row[i];
+    __syncthreads();
+    int64_t lo, hi;
+    block_range(p, v.meta[META_NEDGES + layer], lo, hi);          // the same share as in k_part_hist
+    for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += 4 * kBlock) {
+        int32_t c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[j] = e0 + j * kBlock < hi ? col[e0 + j * kBlock] : 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (c[j] < 0) {
+                const uint32_t u = (uint32_t)~c[j];
+                const int at = atomicAdd(&s_bins[u >> w.bucket_log2], 1);
+                v.rec[at] = ((unsigned long long)u << 32) | (uint32_t)(e0 + j * kBlock);
+            }
+    }
+}
+
+// One bucket with more than 64 records (a node that many edges of the hop lead to): the nodes of its
+// records as bits of an LDS bitmap over the bucket's id range; per-word prefix counts give every
+// record's node its rank among the bucket's distinct nodes, and the set bits, in order, are those
+// nodes.  Called by the whole block (one wave) at once.
+__device__ inline void bucket_by_bitmap(const wide_t &w, const slot_view &v, int q, int lo, int hi, uint32_t *bits,
+                                        uint32_t *before, int n_words)
+{
+    const int lane = threadIdx.x;
+    const uint32_t id_mask = (1u << w.bucket_log2) - 1u;
+    const int per_lane = (n_words + 63) / 64;
+    const int first = lane * per_lane;
+    for (int i = lane; i < n_words; i += 64) bits[i] = 0u;
+    __syncthreads();
+    for (int r = lo + lane; r < hi; r += 64) {
+        const uint32_t local = (uint32_t)(v.rec[r] >> 32) & id_mask;
+        atomicOr(&bits[local >> 5], 1u << (local & 31));
+    }
+    __syncthreads();
+    int mine = 0;
+    for (int j = 0; j < per_lane; ++j)
+        if (first + j < n_words) mine += __popc(bits[first + j]);
+    const int incl = wave_incl_scan(mine);
+    const int total = __shfl(incl, 63);
+    int run = incl - mine;
+    int32_t at = lo + run;                                           // distinct nodes <= records: they fit from lo on
+    for (int j = 0; j < per_lane; ++j)
+        if (first + j < n_words) {
+            uint32_t x = bits[first + j];
+            before[first + j] = (uint32_t)run;
+            run += __popc(x);
+            while (x) {
+                const int b = __ffs(x) - 1;
+                x &= x - 1;
+                v.stage[at++] = (int32_t)(((uint32_t)q << w.bucket_log2) + (uint32_t)(first + j) * 32u + (uint32_t)b);
+            }
+        }
+    if (lane == 0) v.bk_cnt[q] = total;
+    __syncthreads();
+    for (int r = lo + lane; r < hi; r += 64) {
+        const uint32_t local = (uint32_t)(v.rec[r] >> 32) & id_mask;
+        v.lrank[r] = (int32_t)(before[local >> 5] + __popc(bits[local >> 5] & ((1u << (local & 31)) - 1u)));
+    }
+    __syncthreads();                                                 // before another bucket clears the bitmap
+}
+
+// Ascending bitonic sort of one key per lane over the 64 lanes of a wave.
+__device__ inline uint32_t wave_sort(uint32_t key)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const uint32_t other = (uint32_t)__shfl_xor((int)key, j);
+            const bool rising = (lane & k) == 0;                     // k == 64: the whole wave
+            const bool lower = (lane & j) == 0;
+            const uint32_t mn = key < other ? key : other, mx = key < other ? other : key;
+            key = lower == rising ? mn : mx;
+        }
+    }
+    return key;
+}
+
+// A block of one wave takes kBucketsPerWave consecutive buckets at a time (their bounds with one
+// load) and goes through them in windows of whole buckets with at most 64 records together, the
+// usual case being several buckets per window: lane i takes record i of the window, the wave sorts
+// (node, lane) pairs, and in sorted order a node is new where it differs from its left neighbour, a
+// bucket begins where the bucket number does; the rank of a record's node among its bucket's distinct
+// nodes is the number of new nodes between the bucket's first lane and its own.  A bucket with more
+// than 64 records of its own goes through the LDS bitmap (2 x n_words words).
+constexpr int kBucketsPerWave = 8;
+
+__global__ __launch_bounds__(64) void k_part_bucket(wide_t w, int gx, int n_words)
+{
+    extern __shared__ uint32_t s_mem[];
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    const int lane = threadIdx.x;
+    const int nb = w.n_buckets;
+    const int b = w.bucket_log2;
+    const int n_groups = (nb + kBucketsPerWave - 1) / kBucketsPerWave;
+    const unsigned long long through_me = (2ull << lane) - 1ull;    // lanes 0 .. lane
+    for (int g = p.bx; g < n_groups; g += gx) {                      // g and every branch on scalars below: the same for all lanes
+        const int q0 = g * kBucketsPerWave;
+        int bound = q0 + lane;                                       // lanes 0..8: where the group's buckets begin and end
+        bound = bound < nb ? bound : nb;
+        const int my_start = lane <= kBucketsPerWave ? v.bk_start[bound] : 0;
+        const int next_start = __shfl_down(my_start, 1);
+        // empty buckets have no lane of their own below
+        if (lane < kBucketsPerWave && q0 + lane < nb && next_start == my_start) v.bk_cnt[q0 + lane] = 0;
+        auto lo = [&](int j) { return __builtin_amdgcn_readlane(my_start, j); };   // first record of bucket q0 + j
+        int j = 0;
+        while (j < kBucketsPerWave && q0 + j < nb) {
+            if (lo(j + 1) - lo(j) > 64) {
+                bucket_by_bitmap(w, v, q0 + j, lo(j), lo(j + 1), s_mem, s_mem + n_words, n_words);
+                ++j;
+                continue;
+            }
+            int end = j + 1;                                         // window = buckets j .. end - 1
+            while (end < kBucketsPerWave && lo(end + 1) - lo(j) <= 64) ++end;
+            const int first = lo(j), n = lo(end) - first;
+            const int q_first = q0 + j;
+            j = end;
+            if (n == 0) continue;
+            // (node - first id of the window's first bucket) << 6 | lane: below 2^(bucket_log2 + 3 + 6) <= 2^27
+            uint32_t key = 0xffffffffu;                              // lanes beyond the records sort to the end
+            if (lane < n) key = ((((uint32_t)(v.rec[first + lane] >> 32)) - ((uint32_t)q_first << b)) << 6) | (uint32_t)lane;
+            key = wave_sort(key);
+            const bool there = key != 0xffffffffu;
+            const uint32_t local = key >> 6;                         // node, counted from the window's first id
+            const int from = (int)(key & 63u);                       // the record is number `from` of the window
+            const uint32_t left = (uint32_t)__shfl_up((int)local, 1);
+            const bool new_node = there && (lane == 0 || left != local);
+            const bool new_bucket = there && (lane == 0 || (left >> b) != (local >> b));
+            const unsigned long long nodes_mask = __ballot(new_node), buckets_mask = __ballot(new_bucket);
+            if (there) {
+                const int begin = 63 - __clzll(buckets_mask & through_me);             // first lane of my bucket
+                const unsigned long long mine = nodes_mask & ~((1ull << begin) - 1ull);    // new nodes from there on
+                const int rank = __popcll(mine & through_me) - 1;
+                v.lrank[first + from] = rank;
+                if (new_node) v.stage[first + begin + rank] = (int32_t)(local + ((uint32_t)q_first << b));
+                if (new_bucket) {                                    // distinct nodes of the bucket: up to the next bucket's first lane
+                    const unsigned long long later = buckets_mask & ~through_me;
+                    const int stop = later ? __ffsll((long long)later) - 1 : 64;
+                    const unsigned long long upto = stop == 64 ? ~0ull : (1ull << stop) - 1ull;
+                    v.bk_cnt[q_first + (int)(local >> b)] = __popcll(mine & upto);
+                }
+            }
+        }
+    }
+}
+
+// One thread per record: col[] of its edge, and (the first `distinct` records of a bucket) one of the
+// bucket's nodes to its place in the frontier.
+__global__ __launch_bounds__(kBlock) void k_part_final(wide_t w, int gx, int layer, int64_t cap_next, layer_out_t o)
+{
+    spot_t p;
+    if (!my_spot(w, gx, p)) return;
+    const slot_view v = view_of(w, p.slot);
+    int32_t *col = o.col + (int64_t)p.slot * o.edge_stride;
+    const int64_t n_rec = v.bk_start[w.n_buckets];
+    const int64_t hop_base = v.meta[META_NFRONT + layer];
+    for (int64_t r = (int64_t)p.bx * kBlock + threadIdx.x; r < n_rec; r += (int64_t)gx * kBlock) {
+        const unsigned long long rec = v.rec[r];
+        const uint32_t q = (uint32_t)(rec >> 32) >> w.bucket_log2;
+        const int64_t place = hop_base + v.bk_before[q];
+        col[(uint32_t)rec] = (int32_t)(place + v.lrank[r]);
+        const int64_t i = r - v.bk_start[q];
+        if (i < v.bk_cnt[q] && place + i < cap_next) v.nodes[place + i] = v.stage[r];
+    }
+}
+
 // Flat variant for access counting on graphs whose whole bitmap is cheap to walk: every thread
 // owns one bitmap word; new = seen ^ prev, then prev = seen.
 __global__ __launch_bounds__(kBlock) void k_bm_partial_flat(wide_t w, int gx)
@@ -812,14 +1140,14 @@ __global__ __launch_bounds__(kBlock) void k_count_columns(wide_t w, int large, u
 // its segment + the bits below its own in the segment (the bitmap still holds the hop's bits).
 // With 32 words per segment those bits are one 128-byte line: the 8 lanes of a group take the
 // group's edges one at a time, each lane 16 bytes of the line.
-__global__ __launch_bounds__(kBlock) void k_relabel(wide_t w, int gx, relabel_t r)
+__global__ __launch_bounds__(kBlock) void k_relabel(wide_t w, int gx, relabel_t r, int n_layers)
 {
     spot_t p;
     if (!my_spot(w, gx, p)) return;
     const slot_view v = view_of(w, p.slot);
     const int64_t stride = (int64_t)gx * kBlock;
     const int64_t t = (int64_t)p.bx * kBlock + threadIdx.x;
-    for (int l = 0; l < r.n_layers; ++l) {
+    for (int l = 0; l < n_layers; ++l) {                          // n_layers < r.n_layers: k_part_final has done the last
         int32_t *col = r.col[l] + (int64_t)p.slot * r.stride[l];
         const int64_t n = v.meta[META_NEDGES + l];
         const bool last = l == r.n_layers - 1;
@@ -933,6 +1261,7 @@ __global__ void k_clear_totals(int64_t *meta)
 // slot is served by one XCD, which holds 256 blocks at a time: more blocks than twice that only queue
 // up to find nothing to do (measured best of 128 / 256 / 512 / 1024 and no cap).
 constexpr int kLoopBlocks = 512;
+constexpr int kBucketBlocks = 1024;  // one-wave blocks per slot of k_part_bucket
 
 int clamp_grid(int64_t items, int per_block, int cap)
 {
@@ -954,15 +1283,16 @@ struct wide_out {             // where the mini-batches' results go
 bool large_graph(const tier_ctx *c) { return c->seg_log2 != 0; }
 
 template <int G, int MODE>
-void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, bool last, const wide_out &o)
+void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, bool last, bool mark,
+                       const wide_out &o)
 {
     const int gx = clamp_grid(cap_dst, (kBlock / G) * kAtOnce, kLoopBlocks);
     k_hop_sample<G, MODE><<<grid_of(gx, w.n_slots), kBlock, 0, c->stream>>>(
-        w, gx, c->indices, layer, k, last ? 1 : 0, MODE == MODE_BLOCKS ? o.layer[layer] : layer_out_t{});
+        w, gx, c->indices, layer, k, last ? 1 : 0, mark ? 1 : 0, MODE == MODE_BLOCKS ? o.layer[layer] : layer_out_t{});
 }
 
 template <int MODE>
-void launch_hop(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, bool last, const wide_out &o)
+void launch_hop(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k, bool last, bool mark, const wide_out &o)
 {
     if (MODE == MODE_BLOCKS) {
         const int gx = clamp_grid(cap_dst, kBlock, kLoopBlocks);
@@ -970,11 +1300,11 @@ void launch_hop(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer, int k,
         k_hop_partial<<<grid, kBlock, 0, c->stream>>>(w, gx, layer, k);
         k_hop_rowptr<<<grid, kBlock, 0, c->stream>>>(w, gx, layer, k, o.layer[layer]);
     }
-    if (k <= 4) launch_hop_sample<4, MODE>(c, w, cap_dst, layer, k, last, o);
-    else if (k <= 8) launch_hop_sample<8, MODE>(c, w, cap_dst, layer, k, last, o);
-    else if (k <= 16) launch_hop_sample<16, MODE>(c, w, cap_dst, layer, k, last, o);
-    else if (k <= 32) launch_hop_sample<32, MODE>(c, w, cap_dst, layer, k, last, o);
-    else launch_hop_sample<64, MODE>(c, w, cap_dst, layer, k, last, o);
+    if (k <= 4) launch_hop_sample<4, MODE>(c, w, cap_dst, layer, k, last, mark, o);
+    else if (k <= 8) launch_hop_sample<8, MODE>(c, w, cap_dst, layer, k, last, mark, o);
+    else if (k <= 16) launch_hop_sample<16, MODE>(c, w, cap_dst, layer, k, last, mark, o);
+    else if (k <= 32) launch_hop_sample<32, MODE>(c, w, cap_dst, layer, k, last, mark, o);
+    else launch_hop_sample<64, MODE>(c, w, cap_dst, layer, k, last, mark, o);
 }
 
 // Enqueue w.n_slots mini-batches.  cap_nodes / cap_edges: the bounds of tier_blocks_bounds
@@ -992,10 +1322,28 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
     }
     const int seg_gx = clamp_grid(w.n_seg, kBlock, TIER_SCAN_BLOCKS);
     const int flat_gx = clamp_grid(w.n_words, 4 * kBlock, TIER_SCAN_BLOCKS);
+    const bool by_buckets = MODE == MODE_BLOCKS && w.n_buckets > 0;      // the last hop's new nodes: k_part_*
     for (int l = 0; l < n_layers; ++l) {
         const bool last = l == n_layers - 1;
-        launch_hop<MODE>(c, w, cap_nodes[l], l, fanouts[l], last, o);
+        launch_hop<MODE>(c, w, cap_nodes[l], l, fanouts[l], last, !(last && by_buckets), o);
         if (MODE != MODE_BLOCKS && last) break;               // counted from the bitmaps, never listed
+        if (last && by_buckets) {
+            const int nb = w.n_buckets;
+            const size_t bins = (size_t)nb * sizeof(int);
+            const int n_words = w.bucket_log2 > 5 ? 1 << (w.bucket_log2 - 5) : 1;
+            const unsigned part_grid = grid_of(kPartBlocks, slots);
+            k_part_hist<<<part_grid, kBlock, bins, st>>>(w, l, o.layer[l]);
+            const int cols_gx = clamp_grid(nb, kBlock, 1 << 16);
+            k_part_cols<<<grid_of(cols_gx, slots), kBlock, 0, st>>>(w, cols_gx);
+            k_part_scan<<<grid_of(1, slots), kScanThreads, 0, st>>>(w, 0, l, cap_nodes[l + 1]);
+            k_part_scatter<<<part_grid, kBlock, bins, st>>>(w, l, o.layer[l]);
+            const int bucket_gx = clamp_grid(nb, kBucketsPerWave, kBucketBlocks);
+            k_part_bucket<<<grid_of(bucket_gx, slots), 64, 2 * (size_t)n_words * sizeof(uint32_t), st>>>(w, bucket_gx, n_words);
+            k_part_scan<<<grid_of(1, slots), kScanThreads, 0, st>>>(w, 1, l, cap_nodes[l + 1]);
+            const int final_gx = clamp_grid(cap_edges[l], kBlock, kLoopBlocks);
+            k_part_final<<<grid_of(final_gx, slots), kBlock, 0, st>>>(w, final_gx, l, cap_nodes[l + 1], o.layer[l]);
+            break;
+        }
         if (MODE == MODE_COUNT_SMALL) {
             k_bm_partial_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx);
             k_bm_emit_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx, l, cap_nodes[l + 1]);
@@ -1012,13 +1360,14 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
         relabel_t r = {};
         r.n_layers = n_layers;
         int64_t most = 1;
+        const int relabelled = by_buckets ? n_layers - 1 : n_layers;       // k_part_final has done the last hop's col[]
         for (int l = 0; l < n_layers; ++l) {
             r.col[l] = o.layer[l].col;
             r.stride[l] = o.layer[l].edge_stride;
-            if (cap_edges[l] > most) most = cap_edges[l];
+            if (l < relabelled && cap_edges[l] > most) most = cap_edges[l];
         }
         const int gx = clamp_grid(most, kBlock, kLoopBlocks);
-        k_relabel<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, r);
+        if (relabelled > 0) k_relabel<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, r, relabelled);
     } else {
         k_count_columns<<<clamp_grid(c->n_words, kBlock, 1 << 22), kBlock, 0, st>>>(w, MODE == MODE_COUNT_LARGE ? 1 : 0,
                                                                                  o.counts);
@@ -1026,7 +1375,7 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
     if (MODE != MODE_COUNT_SMALL) {
         const int64_t cells4 = (1ll << w.table_log2) / 4;
         const int gx = clamp_grid(cells4 > w.n_seg ? cells4 : w.n_seg, 4 * kBlock, kLoopBlocks);
-        k_finish<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, MODE == MODE_BLOCKS ? 1 : 0);
+        k_finish<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, MODE == MODE_BLOCKS && !by_buckets ? 1 : 0);
     }
     TIER_HIP(c, hipGetLastError());
     return TIER_OK;
@@ -1098,6 +1447,37 @@ wide_t make_wide(tier_ctx *c, const int32_t *seeds, int64_t n_seeds_total, int32
     return w;
 }
 
+// Scratch of the last hop by buckets for a call of n_slots mini-batches with at most `edges` edges each
+// at that hop.  A bucket is 2^b consecutive ids with b such that there are at most 8192 buckets
+// (their counters fit a block's LDS) and b >= 5 (a bucket is at least one bitmap word).
+int ensure_buckets(tier_ctx *c, wide_t *w, int64_t edges, int n_slots)
+{
+    int lg = 0;
+    while ((1ll << lg) < c->n_nodes) ++lg;
+    const int b = lg - 13 > 5 ? lg - 13 : 5;
+    const int64_t nb = (c->n_nodes + (1ll << b) - 1) >> b;
+    if (nb < 1) return TIER_OK;                                  // no nodes: nothing to sort
+    const size_t per = (size_t)(edges > 0 ? edges : 1) * (size_t)n_slots;
+    int rc = tier_ensure(c, (void **)&c->part_rec, &c->part_rec_cap, per * sizeof(unsigned long long));
+    if (rc == TIER_OK) rc = tier_ensure(c, (void **)&c->part_rank, &c->part_rank_cap, per * sizeof(int32_t));
+    if (rc == TIER_OK) rc = tier_ensure(c, (void **)&c->part_stage, &c->part_stage_cap, per * sizeof(int32_t));
+    if (rc == TIER_OK)
+        rc = tier_ensure(c, (void **)&c->part_rows, &c->part_rows_cap,
+                         (size_t)n_slots * kPartBlocks * (size_t)nb * sizeof(int32_t));
+    if (rc == TIER_OK)
+        rc = tier_ensure(c, (void **)&c->part_bk, &c->part_bk_cap, (size_t)n_slots * 3 * (size_t)(nb + 1) * sizeof(int32_t));
+    if (rc) return rc;
+    w->rec = c->part_rec;
+    w->lrank = c->part_rank;
+    w->stage = c->part_stage;
+    w->rec_stride = edges > 0 ? edges : 1;
+    w->rows = c->part_rows;
+    w->bk = c->part_bk;
+    w->n_buckets = (int32_t)nb;
+    w->bucket_log2 = b;
+    return TIER_OK;
+}
+
 int ensure_i32(tier_ctx *c, int32_t **buf, int64_t *cap, int64_t want)
 {
     if (want <= *cap) return TIER_OK;
@@ -1158,6 +1538,10 @@ int tier_sample_minibatches(tier_ctx *ctx, const int32_t *seeds, int64_t n_seeds
     for (int s = 0; s < n_batches; ++s) {
         w.key0[s] = (uint32_t)batch_seeds[s];
         w.key1[s] = (uint32_t)(batch_seeds[s] >> 32);
+    }
+    if (large_graph(ctx)) {
+        rc = ensure_buckets(ctx, &w, cap_edges[n_layers - 1], n_batches);
+        if (rc) return rc;
     }
     rc = enqueue_wide<MODE_BLOCKS>(ctx, w, fanouts, n_layers, cap_nodes, cap_edges, o);
     if (rc) return rc;

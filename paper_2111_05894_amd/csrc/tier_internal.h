@@ -82,6 +82,18 @@ struct tier_ctx {
     size_t f_deg_cap;
     uint32_t *table;         // frontier index of the sampler, [n_slots][cells of the current call]; grown on demand
     size_t table_cap;        // bytes
+    // last hop of a block call on the large-graph layout: its new neighbours are sorted into buckets of
+    // consecutive node ids instead of marked in `fresh` (sampler.hip); all grown on demand
+    unsigned long long *part_rec;   // [slots of the call][edges of the last hop]: node << 32 | edge
+    size_t part_rec_cap;            // bytes
+    int32_t *part_rank;             // likewise: rank of the record's node among its bucket's distinct nodes
+    size_t part_rank_cap;
+    int32_t *part_stage;            // likewise: every bucket's distinct nodes, ascending, at the bucket's start
+    size_t part_stage_cap;
+    int32_t *part_rows;             // [slots][blocks that scatter][buckets]: records of a block per bucket
+    size_t part_rows_cap;
+    int32_t *part_bk;               // [slots][3][buckets + 1]: start, distinct nodes, distinct nodes before, per bucket
+    size_t part_bk_cap;
     // placement
     int32_t *slot;           // n_nodes
     uint32_t *hot_bits;      // ceil(n_nodes / 32): bit v set <=> slot[v] >= 0 (what the split gather's cold workers ask)

@@ -222,6 +222,42 @@ def test_repeated_and_unsorted_neighbours(seg_words):
         w.close()
 
 
+@pytest.mark.parametrize("seg_words", [None, 32], ids=["seg1", "seg32"])
+def test_last_hop_crowded_and_sparse_id_ranges(seg_words):
+    """The last hop's new nodes by id range: thousands of edges that lead to a few dozen
+    neighbouring ids (far more than a wave holds at once), next to ranges that get one edge or
+    none, in a single call and with several mini-batches side by side."""
+    rng = np.random.default_rng(77)
+    n = 40_000
+    crowd = np.arange(20_000, 20_050)                               # 50 ids next to each other
+    deg = rng.integers(1, 9, n)
+    indptr = np.zeros(n + 1, np.int64); indptr[1:] = np.cumsum(deg)
+    src = rng.integers(0, n, int(indptr[-1]))
+    to_crowd = rng.random(src.shape[0]) < 0.6
+    src[to_crowd] = rng.choice(crowd, int(to_crowd.sum()))
+    w = World(torch.from_numpy(indptr), torch.from_numpy(src.astype(np.int32)), dim=4, seg_words=seg_words)
+    try:
+        for fanouts, n_seeds in (((6,), 3000), ((2, 6), 1500), ((1, 1, 1), 10)):
+            seeds = rng.choice(np.setdiff1d(np.arange(n), crowd), n_seeds, replace=False).astype(np.int32)
+            got, _ = compare_blocks(w, seeds, fanouts, 5 + n_seeds)
+            say("crowded", fanouts, got.n_nodes, got.n_edges)
+        B, bs, fanouts = 5, 400, (3, 4)
+        seeds = rng.choice(n, B * bs - 150, replace=False).astype(np.int32)      # the last mini-batch is short
+        bseeds = [tier.tier_batch_seed(99, 0, b) for b in range(B)]
+        got = tier.tier_sample_minibatches(w.ctx, torch.from_numpy(seeds).to(DEV), bs, bseeds, fanouts)
+        for b in range(B):
+            want = orc.sample_minibatch(w.indptr, w.indices, seeds[b * bs:(b + 1) * bs], fanouts, bseeds[b],
+                                        local_idx=w.local_idx)
+            assert got.n_nodes[b] == want["n_nodes"].tolist() and got.n_edges[b] == want["n_edges"].tolist()
+            assert np.array_equal(got.frontier(b).cpu().numpy(), want["nodes"])
+            for l in range(len(fanouts)):
+                ne = got.n_edges[b][l]
+                assert np.array_equal(got.col[l][b][:ne].cpu().numpy(), want["col"][l]), (b, l)
+                assert np.array_equal(got.eid[l][b][:ne].cpu().numpy(), want["eid"][l]), (b, l)
+    finally:
+        w.close()
+
+
 # ------------------------------------------------------------------------------
 # access counts
 # ------------------------------------------------------------------------------
