@@ -52,6 +52,10 @@
 // A segment is one bitmap word on graphs of up to 32 M nodes and 32 words above, so
 // the kernels that read the bitmap walk one byte per 32 or 1024 nodes and touch only
 // the words of flagged segments: their cost follows the mini-batch, not the graph.
+// With 32 words per segment nearly every new node of the last hop, where most of a
+// mini-batch's nodes are found, would sit alone in its 128-byte line; there the last
+// hop of a block call does without the bitmap and sorts its new neighbours into
+// buckets of consecutive ids instead (k_part_*, further down).
 //
 // tier_presample runs the same chains without materialising blocks (no offsets, no
 // edge ids, no relabel).  Up to 32 M nodes it keeps the frontier itself in two bitmaps
@@ -70,7 +74,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kXcds = 8;             // XCDs of an MI355X; workgroup i of a launch runs on XCD i % 8
-constexpr int kPartBlocks = 32;      // blocks per slot that sort the last hop's new neighbours into buckets
+constexpr int kPartBlocks = 16;      // blocks per slot that sort the last hop's new neighbours into buckets (best of 8 .. 64)
 
 enum { MODE_BLOCKS = 0, MODE_COUNT_SMALL = 1, MODE_COUNT_LARGE = 2 };
 
