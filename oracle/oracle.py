@@ -57,6 +57,10 @@ def _load():
         _lib.orc_presample.argtypes = [
             C.c_int64, _i64p, _i32p, _i32p, C.c_int64, C.c_int64, _i32p, C.c_int, C.c_int, C.c_uint64,
             C.c_int64, C.c_int64, _i32p, _i32p, C.c_int64, _u32p, _i64p, _i64p]
+        _lib.orc_presample_draws.restype = C.c_int
+        _lib.orc_presample_draws.argtypes = [
+            C.c_int64, _i64p, _i32p, _i32p, C.c_int64, C.c_int64, _i32p, C.c_int, C.c_int, C.c_uint64,
+            C.c_int64, C.c_int64, _i32p, _i32p, C.c_int64, _i64p, C.c_int64, _u32p, _i64p]
         _lib.orc_place.restype = C.c_int
         _lib.orc_place.argtypes = [_u32p, C.c_int64, C.c_int64, C.c_uint64, _i32p, _i32p, _i64p]
         _lib.orc_fill_cache.restype = None
@@ -185,6 +189,43 @@ def presample(indptr, indices, train_ids, batch_size, fanouts, epochs, seed, thr
     for c, _, _ in parts[1:]:
         counts += c
     return counts, sum(p[1] for p in parts), sum(p[2] for p in parts)
+
+
+def presample_draws(indptr, indices, train_ids, batch_size, fanouts, epochs, seed, threads=1):
+    """Counts of the other reading: one per seed and one per sampled edge's source.  Returns
+    (counts, number of seeds + sampled edges); ``threads`` as in presample."""
+    indptr = _as(indptr, np.int64); indices = _as(indices, np.int32)
+    train_ids = _as(train_ids, np.int32); fan = _as(fanouts, np.int32)
+    n_graph = indptr.shape[0] - 1
+    n_train = train_ids.shape[0]
+    n_batches = (n_train + batch_size - 1) // batch_size
+    nn_b, ne_b = frontier_bounds(min(batch_size, n_train), fan.tolist(), n_graph)
+    lib = _load()
+
+    def work(lo, hi):
+        local_idx = np.full(n_graph, -1, np.int32)
+        scratch = np.empty(max(nn_b[-1], 1), np.int32)
+        eids = np.empty(max(sum(ne_b), 1), np.int64)
+        counts = np.zeros(n_graph, np.uint32)
+        tot = C.c_int64(0)
+        rc = lib.orc_presample_draws(n_graph, _p(indptr, _i64p), _p(indices, _i32p), _p(train_ids, _i32p), n_train,
+                                     batch_size, _p(fan, _i32p), fan.shape[0], epochs, seed, lo, hi,
+                                     _p(local_idx, _i32p), _p(scratch, _i32p), scratch.shape[0],
+                                     _p(eids, _i64p), eids.shape[0], _p(counts, _u32p), C.byref(tot))
+        if rc:
+            raise RuntimeError("oracle capacity error")
+        return counts, tot.value
+
+    threads = max(1, min(threads, n_batches if n_batches else 1))
+    if threads == 1:
+        return work(0, n_batches)
+    cuts = [n_batches * t // threads for t in range(threads + 1)]
+    with ThreadPoolExecutor(threads) as ex:
+        parts = list(ex.map(lambda t: work(cuts[t], cuts[t + 1]), range(threads)))
+    counts = parts[0][0]
+    for c, _ in parts[1:]:
+        counts += c
+    return counts, sum(p[1] for p in parts)
 
 
 def place(counts, row_bytes: int, budget_bytes: int):

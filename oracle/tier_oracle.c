@@ -261,6 +261,48 @@ int orc_presample(int64_t n_nodes_graph, const int64_t *indptr, const int32_t *i
 }
 
 /* ------------------------------------------------------------------------ */
+/* Access counts, the other reading of "number of samples" (Sec. 3.1): every  */
+/* time a node is drawn as a neighbour counts, and so does every seed, i.e.   */
+/* counts[v] = occurrences of v among the seeds and among the source ends of  */
+/* all sampled edges, over the same mini-batches as orc_presample.  The sum   */
+/* of counts is the number of seeds plus the number of sampled edges.         */
+/* eid_scratch: room for the edges of one mini-batch.                         */
+/* ------------------------------------------------------------------------ */
+int orc_presample_draws(int64_t n_nodes_graph, const int64_t *indptr, const int32_t *indices,
+                        const int32_t *train_ids, int64_t n_train, int64_t batch_size,
+                        const int32_t *fanouts, int n_layers, int epochs, uint64_t seed,
+                        int64_t batch_begin, int64_t batch_end,
+                        int32_t *local_idx, int32_t *nodes_scratch, int64_t cap_nodes,
+                        int64_t *eid_scratch, int64_t cap_edges,
+                        uint32_t *counts, int64_t *draws_out)
+{
+    int64_t n_batches = (n_train + batch_size - 1) / batch_size;
+    int64_t nn[16], ne[16];
+    int64_t draws = 0;
+    if (batch_end > n_batches) batch_end = n_batches;
+    memset(counts, 0, (size_t)n_nodes_graph * sizeof(uint32_t));
+    for (int e = 0; e < epochs; ++e) {
+        for (int64_t b = batch_begin; b < batch_end; ++b) {
+            int64_t lo = b * batch_size;
+            int64_t n = n_train - lo < batch_size ? n_train - lo : batch_size;
+            int rc = orc_sample_minibatch(n_nodes_graph, indptr, indices, train_ids + lo, n,
+                                          fanouts, n_layers,
+                                          orc_batch_seed(seed, (uint32_t)e, (uint32_t)b),
+                                          local_idx, nodes_scratch, cap_nodes,
+                                          NULL, 0, NULL, eid_scratch, cap_edges, nn, ne);
+            if (rc) return rc;
+            int64_t n_e = 0;
+            for (int l = 0; l < n_layers; ++l) n_e += ne[l];
+            for (int64_t i = 0; i < n; ++i) counts[train_ids[lo + i]] += 1u;
+            for (int64_t i = 0; i < n_e; ++i) counts[indices[eid_scratch[i]]] += 1u;
+            draws += n + n_e;
+        }
+    }
+    if (draws_out) *draws_out = draws;
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Placement (Sec. 3.2, Sec. 4.1): order the nodes by descending score, map   */
 /* old id -> rank, keep the top part in GPU memory.  The score is the access  */
 /* count.  Readings: equal counts are ordered by ascending id; the budget in  */

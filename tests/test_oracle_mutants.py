@@ -51,6 +51,14 @@ MUTANTS = [
      [pins.test_counts_equal_histogram_of_batch_frontiers]),
     ("counts skip the seeds", "for (int64_t i = 0; i < nn[n_layers]; ++i) counts", "for (int64_t i = nn[0]; i < nn[n_layers]; ++i) counts",
      [pins.test_counts_equal_histogram_of_batch_frontiers]),
+    ("draw counts skip the seeds", "for (int64_t i = 0; i < n; ++i) counts[train_ids[lo + i]] += 1u;", "",
+     [pins.test_draw_counts_equal_histogram_of_seeds_and_edge_sources]),
+    ("draw counts take the edge position for the node", "counts[indices[eid_scratch[i]]] += 1u;",
+     "counts[eid_scratch[i] % n_nodes_graph] += 1u;",
+     [pins.test_draw_counts_equal_histogram_of_seeds_and_edge_sources, pins.test_draw_counts_full_fanout_closed_form]),
+    ("draw counts miss the last hop", "for (int l = 0; l < n_layers; ++l) n_e += ne[l];\n            for (int64_t i = 0; i < n; ++i)",
+     "for (int l = 0; l + 1 < n_layers; ++l) n_e += ne[l];\n            for (int64_t i = 0; i < n; ++i)",
+     [pins.test_draw_counts_full_fanout_closed_form]),
     ("ranking ascending", "return x->count > y->count ? -1 : 1;   /* descending */", "return x->count > y->count ? 1 : -1;",
      [pins.test_rank_matches_papers_worked_example]),
     ("ties by descending id", "return (x->id > y->id) - (x->id < y->id);                        /* ascending  */",
@@ -123,7 +131,7 @@ def run_checks(lib_path, idx):
     good = orc._load()
     # give the mutant the same prototypes as the real library
     for sym in ("orc_bounded", "orc_batch_seed", "orc_philox4x32_10", "orc_draw_positions", "orc_sample_minibatch",
-                "orc_presample", "orc_place", "orc_fill_cache", "orc_gather", "orc_reorder_graph", "orc_reorder_rows",
+                "orc_presample", "orc_presample_draws", "orc_place", "orc_fill_cache", "orc_gather", "orc_reorder_graph", "orc_reorder_rows",
                 "orc_gather_boundary", "orc_score_degree", "orc_score_wrpr", "orc_rank_scores"):
         getattr(lib, sym).restype = getattr(good, sym).restype
         getattr(lib, sym).argtypes = getattr(good, sym).argtypes

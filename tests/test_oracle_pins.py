@@ -336,6 +336,86 @@ def test_counts_empty_training_set():
 
 
 # ----------------------------------------------------------------------------
+# access counts, the other reading: every draw of a node counts
+# ----------------------------------------------------------------------------
+def test_draw_counts_equal_histogram_of_seeds_and_edge_sources():
+    indptr, indices = _graph(500, 4000, 13)
+    train = synth.train_set(500, 0.3, 1).numpy()
+    fan, bs, seed, epochs = (4, 3), 32, 77, 2
+    counts, draws = orc.presample_draws(indptr, indices, train, bs, fan, epochs, seed)
+    by_eid = np.zeros(500, np.int64); by_col = np.zeros(500, np.int64); tot = 0
+    nb = -(-len(train) // bs)
+    for e in range(epochs):
+        for b in range(nb):
+            seeds = train[b * bs:(b + 1) * bs]
+            out = orc.sample_minibatch(indptr, indices, seeds, fan, orc.batch_seed(seed, e, b))
+            np.add.at(by_eid, seeds, 1); np.add.at(by_col, seeds, 1); tot += len(seeds)
+            for l in range(len(fan)):
+                np.add.at(by_eid, indices[out["eid"][l]], 1)            # the edge's source in the graph
+                np.add.at(by_col, out["nodes"][out["col"][l]], 1)       # the same node through the block
+                tot += len(out["eid"][l])
+    assert np.array_equal(counts, by_eid) and np.array_equal(counts, by_col)
+    assert counts.sum() == draws == tot                                 # counts sum to the samples
+    frontier_counts, _, edges = orc.presample(indptr, indices, train, bs, fan, epochs, seed)
+    assert draws == epochs * len(train) + edges
+    assert np.all(counts >= frontier_counts)                            # a listed node was drawn or is a seed
+    assert np.array_equal(counts > 0, frontier_counts > 0)
+    c4, d4 = orc.presample_draws(indptr, indices, train, bs, fan, epochs, seed, threads=4)
+    assert np.array_equal(c4, counts) and d4 == draws
+
+
+def test_draw_counts_full_fanout_closed_form():
+    """Fanouts above every degree: at hop l each node reached within l steps hands one count to each
+    entry of its adjacency list (repeats included), and each seed gets one."""
+    indptr, indices = _graph(300, 1200, 17, "er")
+    maxdeg = int(np.max(np.diff(indptr)))
+    assert 1 < maxdeg <= 64
+    train = synth.train_set(300, 0.2, 3).numpy()
+    bs, hops = 16, 2
+    counts, _ = orc.presample_draws(indptr, indices, train, bs, (maxdeg,) * hops, 1, 5)
+    want = np.zeros(300, np.int64)
+    for b in range(-(-len(train) // bs)):
+        seeds = train[b * bs:(b + 1) * bs].tolist()
+        levels = _bfs_levels(indptr, indices, seeds, hops)
+        for v in seeds:
+            want[v] += 1
+        for l in range(hops):
+            for d in levels[l]:
+                np.add.at(want, indices[indptr[d]: indptr[d + 1]], 1)
+    assert np.array_equal(counts, want)
+
+
+def test_draw_counts_one_hop_expectation():
+    """One hop: the expected count of v is its seed occurrences plus, over the seeds u that list v,
+    (entries of v in u's list) x min(1, k / deg u) -- exact, since every position is kept with that
+    probability."""
+    indptr, indices = _graph(60, 400, 19)
+    n = 60; k = 2; bs = 8
+    train = np.arange(0, 24, dtype=np.int32)
+    deg = np.diff(indptr)
+    mean_want = np.zeros(n)
+    for u in train:
+        mean_want[u] += 1
+        if deg[u]:
+            np.add.at(mean_want, indices[indptr[u]: indptr[u + 1]], min(1.0, k / deg[u]))
+    runs = 3000
+    acc = np.zeros(n)
+    for s in range(runs):
+        c, _ = orc.presample_draws(indptr, indices, train, bs, (k,), 1, 1000 + s)
+        acc += c
+    mean = acc / runs
+    sd = np.sqrt(np.maximum(mean_want, 1e-9) / runs) + 1e-9            # loose (variance <= mean)
+    assert np.all(np.abs(mean - mean_want) < 5 * sd + 1e-12)
+    assert np.all(mean[mean_want == 0] == 0)
+
+
+def test_draw_counts_empty_training_set():
+    indptr, indices = _graph()
+    counts, draws = orc.presample_draws(indptr, indices, np.zeros(0, np.int32), 8, (3,), 1, 1)
+    assert counts.sum() == 0 and draws == 0
+
+
+# ----------------------------------------------------------------------------
 # placement
 # ----------------------------------------------------------------------------
 def test_rank_matches_papers_worked_example():
