@@ -529,6 +529,9 @@ def score_comparison(tier, synth, torch, ctx, wl, counts, train, budget, groups,
     _, t = timed(lambda: tier.tier_presample(ctx, train, wl.batch_size, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts))
     makers = {
         "presampled_counts": (lambda: counts, t, "int"),
+        # the other reading of the access count: every draw of a node and every seed counts
+        "presampled_draw_counts": (lambda: tier.tier_presample_draws(ctx, train, wl.batch_size, wl.fanouts, 1,
+                                                                      synth.PRESAMPLE_SEED), None, "int"),
         "out_degree": (lambda: tier.tier_score_degree(ctx), None, "int"),
         "reverse_pagerank_5": (lambda: tier.tier_score_wrpr(ctx, none, 5, 0.85), None, "real"),
         "weighted_reverse_pagerank_5": (lambda: tier.tier_score_wrpr(ctx, train, 5, 0.85), None, "real"),

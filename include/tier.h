@@ -155,6 +155,17 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
                    const int32_t *fanouts /* host */, int32_t n_layers, int32_t epochs, uint64_t seed,
                    uint32_t *counts, int64_t *total_rows, int64_t *total_edges);
 
+/* Access counts by the other reading of Sec. 3.1's "number of samples": the same
+ * mini-batches as tier_presample, but counts[v] (device, n_nodes entries, overwritten) is
+ * the number of times v is a seed plus the number of sampled edges whose source it is,
+ * so a node that a mini-batch reaches over many edges counts that many times and the sum
+ * of counts is the number of seeds plus the number of sampled edges.  A score for
+ * tier_place like the counts of tier_presample.  Asynchronous; total_draws (host,
+ * optional) receives that sum and makes the call wait. */
+int tier_presample_draws(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
+                         const int32_t *fanouts /* host */, int32_t n_layers, int32_t epochs, uint64_t seed,
+                         uint32_t *counts, int64_t *total_draws);
+
 /* Seed of mini-batch `batch` of epoch `epoch` derived from a run seed (host only). */
 uint64_t tier_batch_seed(uint64_t seed, uint32_t epoch, uint32_t batch);
 

@@ -67,6 +67,10 @@
 // slots' bitmaps column by column (k_count_columns: no atomics; the nodes of the last
 // hop are never listed).  Within a mini-batch the frontier nodes are distinct, so no
 // counter is a hot spot that LDS staging could absorb.
+//
+// tier_presample_draws counts by the other reading (every seed and every drawn neighbour adds
+// one): the same chains, k_hop_sample<.., DRAWS> adding as it draws, through a small table per
+// block in LDS; k_count_columns then only clears the bitmaps.
 #include "rng.h"
 #include "tier_internal.h"
 
@@ -106,6 +110,7 @@ struct wide_t {
     int64_t *meta;               // [slot][META_WORDS]; totals and the error flag live in slot 0
     int32_t *partial_hop;        // [slot][TIER_SCAN_BLOCKS]
     int32_t *partial_bm;         // [slot][TIER_SCAN_BLOCKS]
+    uint32_t *draws;             // tier_presample_draws: counts[] that every seed and every drawn neighbour adds to
     // last hop of a block call by buckets (n_buckets != 0): see k_part_hist
     unsigned long long *rec;     // [slot][rec_stride]  node << 32 | edge, grouped by bucket
     int32_t *lrank;              // [slot][rec_stride]  rank of the record's node among its bucket's distinct nodes
@@ -330,6 +335,7 @@ __global__ __launch_bounds__(kBlock) void k_init_seeds(wide_t w, int gx, const O
             u = 0;                                   // keep every later index in range
         }
         v.nodes[i] = u;
+        if (MODE != MODE_BLOCKS && w.draws) atomicAdd(&w.draws[u], 1u);
         const OffT first_edge = indptr[u];
         v.beg[i] = (int64_t)first_edge;
         v.deg[i] = (int32_t)(indptr[u + 1] - first_edge);
@@ -410,14 +416,29 @@ constexpr int kAtOnce = 4;       // dst nodes a lane group works on at a time
 // algorithm, draw i on lane i: t_i uniform in [0, d-k+i]; position = t_i unless an earlier draw
 // already took t_i, then d-k+i.  A group takes kAtOnce dst nodes at a time and goes through them
 // stage by stage, so that the reads of one stage are in flight together.
-template <int G, int MODE>
+//
+// DRAWS (tier_presample_draws): every drawn neighbour adds one to w.draws[].  Most draws of a block
+// lead to few nodes (the hubs), so a block keeps a small table of (node, count) in LDS, adds there
+// when the node's cell is free or its own, and hands the sums over with one global atomic per cell
+// when it is through; a draw whose cell is taken by another node goes to the global counter at once.
+constexpr int kPrivCells = 1024;
+
+template <int G, int MODE, bool DRAWS>
 __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const int32_t *__restrict__ indices, int layer,
                                                        int k, int last, int mark, layer_out_t o)
 {
     __shared__ int s_wave[kBlock / 64];
+    __shared__ uint32_t s_priv_key[DRAWS ? kPrivCells : 1], s_priv_cnt[DRAWS ? kPrivCells : 1];
     constexpr int kGroups = kBlock / G;
     spot_t p;
     if (!my_spot(w, gx, p)) return;
+    if (DRAWS) {
+        for (int i = threadIdx.x; i < kPrivCells; i += kBlock) {
+            s_priv_key[i] = 0xffffffffu;
+            s_priv_cnt[i] = 0u;
+        }
+        __syncthreads();
+    }
     const slot_view v = view_of(w, p.slot);
     const int s = p.slot;
     const int32_t *row_ptr = MODE == MODE_BLOCKS ? o.row_ptr + (int64_t)s * o.row_ptr_stride : nullptr;
@@ -472,6 +493,17 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const i
         for (int j = 0; j < kAtOnce; ++j) {
             take[j] = lane < (d[j] < k ? d[j] : k);
             u[j] = take[j] ? indices[beg[j] + pos[j]] : 0;
+        }
+        if (DRAWS) {
+#pragma unroll
+            for (int j = 0; j < kAtOnce; ++j)
+                if (take[j]) {
+                    const uint32_t cell = ((uint32_t)u[j] * 0x9E3779B1u) >> 22;          // kPrivCells = 2^10
+                    const uint32_t was = atomicCAS(&s_priv_key[cell], 0xffffffffu, (uint32_t)u[j]);
+                    if (was == 0xffffffffu || was == (uint32_t)u[j]) atomicAdd(&s_priv_cnt[cell], 1u);
+                    else atomicAdd(&w.draws[u[j]], 1u);
+                }
+            if (last) continue;                       // nothing is listed after the last hop, and nothing marked
         }
         if (MODE == MODE_COUNT_SMALL) {
             // one bit per node: in the frontier already?  `prev` does not change during the hop, so
@@ -532,6 +564,11 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const i
         int tot = block_sum(edges, s_wave);
         if (threadIdx.x == 0 && tot)
             atomicAdd((unsigned long long *)&w.meta[META_TOTAL_EDGES], (unsigned long long)tot);
+    }
+    if (DRAWS) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < kPrivCells; i += kBlock)
+            if (s_priv_cnt[i]) atomicAdd(&w.draws[s_priv_key[i]], s_priv_cnt[i]);
     }
 }
 
@@ -1094,7 +1131,7 @@ __global__ __launch_bounds__(kBlock) void k_count_columns(wide_t w, int large, u
         uint32_t plane[5] = {0u, 0u, 0u, 0u, 0u};
         int held = 0;
         auto flush = [&]() {
-            if (plane[0] | plane[1] | plane[2] | plane[3] | plane[4]) {
+            if (counts && (plane[0] | plane[1] | plane[2] | plane[3] | plane[4])) {    // no counts: the bitmaps are only cleared
                 uint32_t *c = counts + i * 32;
                 const int64_t left = w.n_nodes - i * 32;         // the last word may be ragged
 #pragma unroll
@@ -1291,8 +1328,12 @@ void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer,
                        const wide_out &o)
 {
     const int gx = clamp_grid(cap_dst, (kBlock / G) * kAtOnce, kLoopBlocks);
-    k_hop_sample<G, MODE><<<grid_of(gx, w.n_slots), kBlock, 0, c->stream>>>(
-        w, gx, c->indices, layer, k, last ? 1 : 0, mark ? 1 : 0, MODE == MODE_BLOCKS ? o.layer[layer] : layer_out_t{});
+    if (MODE != MODE_BLOCKS && w.draws)
+        k_hop_sample<G, MODE == MODE_BLOCKS ? MODE_COUNT_SMALL : MODE, true><<<grid_of(gx, w.n_slots), kBlock, 0, c->stream>>>(
+            w, gx, c->indices, layer, k, last ? 1 : 0, mark ? 1 : 0, layer_out_t{});
+    else
+        k_hop_sample<G, MODE, false><<<grid_of(gx, w.n_slots), kBlock, 0, c->stream>>>(
+            w, gx, c->indices, layer, k, last ? 1 : 0, mark ? 1 : 0, MODE == MODE_BLOCKS ? o.layer[layer] : layer_out_t{});
 }
 
 template <int MODE>
@@ -1373,8 +1414,9 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
         const int gx = clamp_grid(most, kBlock, kLoopBlocks);
         if (relabelled > 0) k_relabel<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, r, relabelled);
     } else {
+        // tier_presample_draws has counted on the way: only the bitmaps are cleared
         k_count_columns<<<clamp_grid(c->n_words, kBlock, 1 << 22), kBlock, 0, st>>>(w, MODE == MODE_COUNT_LARGE ? 1 : 0,
-                                                                                 o.counts);
+                                                                                 w.draws ? nullptr : o.counts);
     }
     if (MODE != MODE_COUNT_SMALL) {
         const int64_t cells4 = (1ll << w.table_log2) / 4;
@@ -1578,9 +1620,9 @@ int tier_sample_minibatch(tier_ctx *ctx, const int32_t *seeds, int32_t n_seeds, 
     return tier_sample_minibatches(ctx, seeds, n_seeds, n_seeds > 0 ? n_seeds : 1, 1, fanouts, n_layers, &seed, &b);
 }
 
-int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
-                   const int32_t *fanouts, int32_t n_layers, int32_t epochs, uint64_t seed, uint32_t *counts,
-                   int64_t *total_rows, int64_t *total_edges)
+static int presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
+                     const int32_t *fanouts, int32_t n_layers, int32_t epochs, uint64_t seed, uint32_t *counts,
+                     int64_t *total_rows, int64_t *total_edges, bool draws)
 {
     if (!ctx || !counts || n_train < 0 || (n_train > 0 && !train_ids) || batch_size < 1 || epochs < 0)
         return TIER_EINVAL;
@@ -1615,6 +1657,7 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
             wide_t w = make_wide(ctx, train_ids + lo, n_train - lo, batch_size, slots, ctx->ps_nodes, stride, table_log2,
                                  stride);
             w.count_edges = total_edges != nullptr;
+            w.draws = draws ? counts : nullptr;
             for (int s = 0; s < slots; ++s) {
                 const uint64_t bs = tier_batch_seed(seed, (uint32_t)e, (uint32_t)(b + s));
                 w.key0[s] = (uint32_t)bs;
@@ -1632,6 +1675,25 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
         return rc;
     }
     return TIER_OK;
+}
+
+int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
+                   const int32_t *fanouts, int32_t n_layers, int32_t epochs, uint64_t seed, uint32_t *counts,
+                   int64_t *total_rows, int64_t *total_edges)
+{
+    return presample(ctx, train_ids, n_train, batch_size, fanouts, n_layers, epochs, seed, counts, total_rows,
+                     total_edges, false);
+}
+
+int tier_presample_draws(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
+                         const int32_t *fanouts, int32_t n_layers, int32_t epochs, uint64_t seed, uint32_t *counts,
+                         int64_t *total_draws)
+{
+    int64_t edges = 0;
+    const int rc = presample(ctx, train_ids, n_train, batch_size, fanouts, n_layers, epochs, seed, counts, nullptr,
+                             total_draws ? &edges : nullptr, true);
+    if (rc == TIER_OK && total_draws) *total_draws = edges + (int64_t)epochs * n_train;
+    return rc;
 }
 
 }  // extern "C"

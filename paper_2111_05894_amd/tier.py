@@ -20,7 +20,7 @@ _lib = None
 
 EXPORTS = (
     "tier_host_alloc", "tier_host_free", "tier_blocks_bounds", "tier_create", "tier_destroy",
-    "tier_presample", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
+    "tier_presample", "tier_presample_draws", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
     "tier_sample_minibatches", "tier_max_batches", "tier_set_segment_words",
     "tier_score_degree", "tier_score_wrpr", "tier_rank_scores", "tier_place_scores",
     "tier_rank", "tier_rank_static", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
@@ -78,6 +78,8 @@ def _load():
         lib.tier_destroy.argtypes = [C.c_void_p]; lib.tier_destroy.restype = None
         lib.tier_presample.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, i32p, C.c_int32, C.c_int32,
                                        C.c_uint64, C.c_void_p, i64p, i64p]
+        lib.tier_presample_draws.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, i32p, C.c_int32, C.c_int32,
+                                             C.c_uint64, C.c_void_p, i64p]
         lib.tier_batch_seed.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]; lib.tier_batch_seed.restype = C.c_uint64
         lib.tier_place.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, i64p]
         lib.tier_sample_minibatch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, i32p, C.c_int32, C.c_uint64,
@@ -228,6 +230,20 @@ def tier_presample(ctx: Context, train_ids: torch.Tensor, batch_size: int, fanou
                                 C.byref(tr) if want_totals else None, C.byref(te) if want_totals else None)
     _check(rc, "tier_presample")
     return (counts, tr.value, te.value) if want_totals else counts
+
+
+def tier_presample_draws(ctx: Context, train_ids: torch.Tensor, batch_size: int, fanouts, epochs: int, seed: int,
+                         counts: torch.Tensor = None, want_total: bool = False):
+    """Returns counts (uint32 values in an int32 tensor), or (counts, seeds + sampled edges)."""
+    fan, L = _fan(fanouts)
+    if counts is None:
+        counts = torch.empty(ctx.n_nodes, dtype=torch.int32, device=train_ids.device)
+    td = C.c_int64(0)
+    rc = _load().tier_presample_draws(ctx.handle, _dev(train_ids, torch.int32, "train_ids"), train_ids.numel(),
+                                      batch_size, fan, L, epochs, seed, _dev(counts, torch.int32, "counts"),
+                                      C.byref(td) if want_total else None)
+    _check(rc, "tier_presample_draws")
+    return (counts, td.value) if want_total else counts
 
 
 def tier_place(ctx: Context, counts: torch.Tensor, budget_bytes: int, want_slot_map: bool = True):

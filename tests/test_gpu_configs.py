@@ -55,6 +55,16 @@ def run_config(name, check_batches, budget_fraction=None, host_threads=16, fallb
         assert (rows, edges) == (wrows, wedges)
         assert np.array_equal(counts.cpu().numpy().view(np.uint32), want_counts)
 
+        # the other reading of the counts (one per seed and per sampled edge's source), in full
+        t1 = time.time()
+        dcounts, draws = tier.tier_presample_draws(ctx, train, bs, fan, 1, synth.PRESAMPLE_SEED, want_total=True)
+        t2 = time.time()
+        want_d, wdraws = orc.presample_draws(ip, ix, tr, bs, fan, 1, synth.PRESAMPLE_SEED, threads=host_threads)
+        say(f"{name}: draw counts gpu {t2 - t1:.2f}s oracle {time.time() - t2:.1f}s draws {draws}")
+        assert draws == wdraws == len(tr) + wedges
+        assert np.array_equal(dcounts.cpu().numpy().view(np.uint32), want_d)
+        del dcounts, want_d
+
         # placement, in full
         budget = int(wl.budget_bytes(budget_fraction) * scale)
         slot, n_hot = tier.tier_place(ctx, counts, budget)

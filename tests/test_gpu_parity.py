@@ -280,6 +280,47 @@ def test_counts_empty_training_set(small):
     assert int(got.sum()) == 0 and rows == 0 and edges == 0
 
 
+@pytest.mark.parametrize("fanouts,batch,epochs", [((10, 5), 100, 1), ((4, 3, 2), 64, 2), ((15,), 333, 1),
+                                                  ((5, 3), 16, 2), ((64, 2), 50, 1)])
+def test_draw_counts_match_oracle(small, fanouts, batch, epochs):
+    """The other reading of the access count: one per seed and one per sampled edge's source."""
+    train = synth.train_set(small.n, 0.2, 5).numpy()
+    want, wdraws = orc.presample_draws(small.indptr, small.indices, train, batch, fanouts, epochs, 5894, threads=4)
+    got, draws = tier.tier_presample_draws(small.ctx, torch.from_numpy(train).to(DEV), batch, fanouts, epochs, 5894,
+                                           want_total=True)
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want)
+    assert draws == wdraws == int(want.sum())
+    # sampler state is clean afterwards: counts by frontier and a mini-batch still match
+    wantc, _, _ = orc.presample(small.indptr, small.indices, train, batch, fanouts, 1, 7, threads=4)
+    gotc = tier.tier_presample(small.ctx, torch.from_numpy(train).to(DEV), batch, fanouts, 1, 7)
+    assert np.array_equal(gotc.cpu().numpy().view(np.uint32), wantc)
+    compare_blocks(small, train[:50], fanouts, 1)
+    got0, d0 = tier.tier_presample_draws(small.ctx, torch.zeros(0, dtype=torch.int32, device=DEV), 8, (3,), 1, 1,
+                                         want_total=True)
+    assert int(got0.sum()) == 0 and d0 == 0
+
+
+def test_draw_counts_on_a_hub():
+    """Nearly every draw leads to one of three nodes: the per-block tables in LDS take almost all
+    increments, and three counters take the blocks' sums."""
+    n = 20_000
+    deg = np.full(n, 6); deg[:3] = 0
+    indptr = np.zeros(n + 1, np.int64); indptr[1:] = np.cumsum(deg)
+    rng = np.random.default_rng(3)
+    src = rng.integers(0, 3, int(indptr[-1])).astype(np.int32)
+    far = rng.random(src.shape[0]) < 0.02
+    src[far] = rng.integers(3, n, int(far.sum()))
+    w = World(torch.from_numpy(indptr), torch.from_numpy(src), dim=4)
+    try:
+        train = np.arange(3, n, dtype=np.int32)
+        want, wdraws = orc.presample_draws(w.indptr, w.indices, train, 1024, (4, 2), 1, 9, threads=4)
+        got, draws = tier.tier_presample_draws(w.ctx, torch.from_numpy(train).to(DEV), 1024, (4, 2), 1, 9, want_total=True)
+        assert np.array_equal(got.cpu().numpy().view(np.uint32), want) and draws == wdraws
+        assert want[:3].sum() > 0.9 * (wdraws - len(train))
+    finally:
+        w.close()
+
+
 # ------------------------------------------------------------------------------
 # placement and gather
 # ------------------------------------------------------------------------------
