@@ -59,6 +59,10 @@ def main():
     ap.add_argument("--no-groups", action="store_true", help="skip the comparison of group sizes 16 / 32 / 64")
     ap.add_argument("--no-budget-sweep", action="store_true",
                     help="skip the placement + epoch at the other HBM budgets of the workload (cfg3: 5 % and 20 %)")
+    ap.add_argument("--no-prefetch", action="store_true",
+                    help="presample in one piece; default: the counts of the first quarter of the mini-batches pick rows "
+                         "that are fetched into HBM while the rest is presampled (tier_prefetch)")
+    ap.add_argument("--prefetch-share", type=float, default=0.3, help="share of the cache's rows fetched ahead")
     ap.add_argument("--no-shared-misses", action="store_true",
                     help="read every requested cold row over the host link, also those a call requests more than once")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink nodes, edges and budget alike")
@@ -189,10 +193,26 @@ def main():
             record["most_rows_per_call"] = most
         return rows, edges
 
-    def step(record):
+    # Fetching ahead: the host link has nothing to do while the access counts are collected, and the
+    # counts of the first mini-batches already name the hottest rows.  So the first quarter of the
+    # mini-batches (whole chains of 64) is presampled, the rows that rank first by those counts start
+    # moving into HBM on the gather stream, and the rest is presampled meanwhile; the placement then
+    # fills the cache from HBM where it can.  Same counts, same slot map, same cache.
+    first_batches = (n_batches // 4) // 64 * 64
+    if first_batches == 0 and n_batches > 64:
+        first_batches = 64
+    prefetch_rows = int(args.prefetch_share * min(n, budget // R)) if (first_batches and not args.no_prefetch) else 0
+
+    def step(record, prefetch=True):
         e_begin, e_pre, e_sorted, e_fill = ev(), ev(), ev(), ev()
         e_begin.record()
-        tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
+        if prefetch and prefetch_rows > 0:
+            tier.tier_presample_range(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, 0, first_batches, counts)
+            tier.tier_prefetch(ctx, counts, prefetch_rows)
+            tier.tier_presample_range(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, first_batches, 1 << 40, counts,
+                                      accumulate=True)
+        else:
+            tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts)
         e_pre.record()
         _, n_hot = tier.tier_place(ctx, counts, budget, want_slot_map=False)
         e_sorted.record()                          # order and slot map; the cache fill runs on the gather stream
@@ -242,6 +262,7 @@ def main():
         ctx.close()
         return
 
+    mean = lambda xs: sum(xs) / len(xs) if xs else 0.0
     for _ in range(args.warmup):
         step(None)
     rec = {"presample_ms": [], "place_ms": [], "place_sort_ms": [], "sample_ms": [], "gather_ms": [], "epoch_wall_ms": []}
@@ -252,6 +273,27 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_begin
     ms_per_step = wall * 1e3 / max(args.steps, 1)
+
+    # the same step without fetching ahead (one presampling call, the whole cache filled after the ranking)
+    prefetch = None
+    if prefetch_rows > 0:
+        prec = {"presample_ms": [], "place_ms": [], "place_sort_ms": [], "sample_ms": [], "gather_ms": [], "epoch_wall_ms": []}
+        step(None, False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = min(max(args.steps, 1), 2)
+        for _ in range(reps):
+            step(prec, False)
+        torch.cuda.synchronize()
+        prefetch = {"first_mini_batches": first_batches, "rows_fetched_ahead": prefetch_rows,
+                    "share_of_the_cache": args.prefetch_share,
+                    "step_ms_without": round((time.perf_counter() - t0) * 1e3 / reps, 3),
+                    "presample_ms_without": round(mean(prec["presample_ms"]), 3),
+                    "place_ms_without": round(mean(prec["place_ms"]), 3),
+                    "note": "timed step: the first mini-batches' counts rank the rows, the first of them move into HBM "
+                            "on the gather stream while the rest is presampled (phase presample then includes that "
+                            "ranking), the placement fills the cache from HBM where it can; without: one presampling "
+                            "call, then the whole cache over the host link.  Counts, slot map and cache are the same"}
 
     # the same epoch with the uniform gather launch (every block copies hot and cold rows)
     uniform = None
@@ -311,7 +353,6 @@ def main():
     sample_alone_ms = a.elapsed_time(b_)
     rows, edges = rec["rows"], rec["edges"]
     h = hit_rows / rows if rows else 0.0
-    mean = lambda xs: sum(xs) / len(xs) if xs else 0.0
     gather_ms, sample_ms = mean(rec["gather_ms"]), mean(rec["sample_ms"])
     gathered_bytes = rows * R
     value = gathered_bytes / (ms_per_step * 1e-3) / 1e9
@@ -495,6 +536,7 @@ def main():
                      "sample": round(sample_ms, 3), "gather": round(gather_ms, 3),
                      "epoch_wall": round(mean(rec["epoch_wall_ms"]), 3)},
         "budget_sweep": budget_sweep,
+        "prefetch": prefetch,
         "gather_launch": {"link_blocks": args.link_blocks, "min_rows": SPLIT_MIN_ROWS, "shared_misses": shared_on,
                           "mini_batches_per_call": B, "output_rows_held": rec["most_rows_per_call"],
                           "groups": group_table,

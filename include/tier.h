@@ -155,6 +155,15 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
                    const int32_t *fanouts /* host */, int32_t n_layers, int32_t epochs, uint64_t seed,
                    uint32_t *counts, int64_t *total_rows, int64_t *total_edges);
 
+/* A part of tier_presample (Sec. 3.1): the mini-batches [first_batch, first_batch + n_batches)
+ * of every epoch, cut from train_ids and seeded exactly as there, so that the ranges of several
+ * calls add up to tier_presample's counts.  accumulate != 0: counts[] is added to, not
+ * overwritten.  What it is for: counts of the first mini-batches already tell which rows will
+ * be hottest (see tier_prefetch).  Asynchronous. */
+int tier_presample_range(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
+                         const int32_t *fanouts /* host */, int32_t n_layers, int32_t epochs, uint64_t seed,
+                         int64_t first_batch, int64_t n_batches, int32_t accumulate, uint32_t *counts);
+
 /* Access counts by the other reading of Sec. 3.1's "number of samples": the same
  * mini-batches as tier_presample, but counts[v] (device, n_nodes entries, overwritten) is
  * the number of times v is a seed plus the number of sampled edges whose source it is,
@@ -247,6 +256,19 @@ int tier_reorder_rows(tier_ctx *ctx, const int32_t *rank, void *rows_new);
 /* out[i] = rank[ids[i]] (e.g. the training ids of the reordered graph).  ids, out:
  * (device) n entries.  Waits; TIER_EINVAL if an id is outside [0, n_nodes). */
 int tier_relabel_ids(tier_ctx *ctx, const int32_t *rank, const int32_t *ids, int64_t n, int32_t *out);
+
+/* Fetch ahead of a placement (Sec. 4.1's hot part, moved early).  The max_rows first rows by
+ * `counts` (device, n_nodes entries; count descending, id ascending: the order of tier_place)
+ * are copied from the feature table to a staging area in HBM, on the gather stream behind
+ * whatever is queued there.  The next tier_place / tier_place_scores takes every row of its
+ * cache that it finds staged from HBM instead of the table; the placement itself (slot map,
+ * cache contents) is the same with or without this call, whatever counts were given here.
+ * For callers whose host link is idle while counts are still being collected: counts of the
+ * first mini-batches (tier_presample_range) already name the hottest rows.  The staged rows
+ * serve one placement and must not change in the table before it.  Scratch owned by the
+ * context: max_rows * row_bytes + 4.2 bytes per node.  Waits for the ranking's digits, not
+ * for the copy. */
+int tier_prefetch(tier_ctx *ctx, const uint32_t *counts, int64_t max_rows);
 
 /* Placement for a context whose graph and table are already in rank order (created on
  * the outputs of tier_reorder_graph / tier_reorder_rows): the hot part is the first

@@ -130,6 +130,10 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipFree(ctx->slot);
     (void)hipFree(ctx->hot_bits);
     (void)hipFree(ctx->cache);
+    (void)hipFree(ctx->staged_ids);
+    (void)hipFree(ctx->staging);
+    (void)hipFree(ctx->staged_of);
+    (void)hipFree(ctx->staged_bits);
     (void)hipStreamSynchronize(ctx->gather_stream);
     (void)hipFree(ctx->claim);
     (void)hipFree(ctx->deferred);

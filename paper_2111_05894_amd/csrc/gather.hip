@@ -429,9 +429,19 @@ int lanes_per_row(int cpr)
 
 // One k_gather launch on stream st, bookkeeping words in meta.  split: with cold workers;
 // dedup (with split only): they fetch every distinct cold row of the launch once.
+// The hot tier a launch reads: the context's placement, or the rows staged ahead of one.
+struct hot_tier_t {
+    const int32_t *slot;
+    const uint32_t *hot_bits;
+    const void *rows;
+    int64_t n_hot;
+};
+
 static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, void *out,
-                        bool count_hits, hipStream_t st, int64_t *meta, bool split = false, bool dedup = false)
+                        bool count_hits, hipStream_t st, int64_t *meta, bool split = false, bool dedup = false,
+                        const hot_tier_t *other_tier = nullptr, int link_blocks_cap = 0)
 {
+    const hot_tier_t hot = other_tier ? *other_tier : hot_tier_t{ctx->slot, ctx->hot_bits, ctx->cache, ctx->n_hot};
     if (count_hits) k_gather_prepare<<<1, META_HIT_STRIPES, 0, st>>>(meta);
     if (n_max <= 0) return TIER_OK;
     const int cpr = (int)(ctx->row_bytes / 16);
@@ -443,6 +453,7 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
     if (mode == GATHER_HOST && ctx->rows_on_host) {
         // every row over the host link: a few dozen blocks fill it, more only queue up
         if (blocks > kLinkBlocks) blocks = kLinkBlocks;
+        if (link_blocks_cap > 0 && blocks > link_blocks_cap) blocks = link_blocks_cap;
     }
     cold_t cold = {};
     if (split) {
@@ -456,9 +467,9 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
     }
     const dim3 grid((unsigned)blocks, (unsigned)(n_lists + (split ? 1 : 0)));
 #define GATHER_LAUNCH(L, M, P, D)                                                                    \
-    k_gather<L, M, P, D><<<grid, kBlock, 0, st>>>(lists, ctx->slot, ctx->hot_bits, (const uint4 *)ctx->cache, \
+    k_gather<L, M, P, D><<<grid, kBlock, 0, st>>>(lists, hot.slot, hot.hot_bits, (const uint4 *)hot.rows, \
                                                   (const uint4 *)ctx->host_rows, (uint4 *)out, cpr,  \
-                                                  ctx->n_nodes, ctx->n_hot, meta, count_hits ? 1 : 0, cold)
+                                                  ctx->n_nodes, hot.n_hot, meta, count_hits ? 1 : 0, cold)
 #define GATHER_CASE(L)                                                                               \
     case L:                                                                                          \
         if (mode == GATHER_SLOT && split && dedup) GATHER_LAUNCH(L, GATHER_SLOT, true, true);        \
@@ -491,12 +502,23 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
     return TIER_OK;
 }
 
-int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, void *out, bool count_hits)
+int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, void *out, bool count_hits,
+                       int link_blocks_cap)
 {
     id_lists_t lists = {};
     lists.ids[0] = ids;
     lists.n[0] = n;
-    return launch_lists(ctx, lists, 1, n, mode, out, count_hits, ctx->gather_stream, ctx->gmeta);
+    return launch_lists(ctx, lists, 1, n, mode, out, count_hits, ctx->gather_stream, ctx->gmeta, false, false, nullptr,
+                        link_blocks_cap);
+}
+
+int tier_launch_fill_staged(tier_ctx *ctx, const int32_t *ids, int64_t n, void *out)
+{
+    id_lists_t lists = {};
+    lists.ids[0] = ids;
+    lists.n[0] = n;
+    const hot_tier_t staged = {ctx->staged_of, ctx->staged_bits, ctx->staging, ctx->staged_rows};
+    return launch_lists(ctx, lists, 1, n, GATHER_SLOT, out, false, ctx->gather_stream, ctx->gmeta, true, false, &staged);
 }
 
 // Claims hold an output row in kClaimRowBits bits.

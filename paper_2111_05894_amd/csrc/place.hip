@@ -354,9 +354,12 @@ static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget
     }
     if (n_hot > 0) {
         if (gs != st) ctx->fill_pending = true;
-        int rc = tier_launch_gather(ctx, order, n_hot, GATHER_HOST, ctx->cache, false);
+        // rows that tier_prefetch has staged come from HBM, the others over the host link
+        int rc = ctx->staged_rows > 0 ? tier_launch_fill_staged(ctx, order, n_hot, ctx->cache)
+                                      : tier_launch_gather(ctx, order, n_hot, GATHER_HOST, ctx->cache, false);
         if (rc != TIER_OK) return rc;
     }
+    ctx->staged_rows = 0;        // staged for one placement: the table may change before the next
     ctx->n_hot = n_hot;
     if (slot_map && n > 0)
         TIER_HIP(ctx, hipMemcpyAsync(slot_map, ctx->slot, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
@@ -407,6 +410,50 @@ extern "C" int tier_place_scores(tier_ctx *ctx, const double *scores, uint64_t b
     return place_from_order(ctx, order, budget_bytes, slot_map, n_hot_out);
 }
 
+constexpr int kPrefetchBlocks = 32;
+
+// Fetch ahead of a placement: the max_rows first rows by `counts` (count descending, id ascending)
+// go to a staging area in HBM on the gather stream, and the next placement's cache fill takes every
+// row it finds there from HBM.
+extern "C" int tier_prefetch(tier_ctx *ctx, const uint32_t *counts, int64_t max_rows)
+{
+    if (!ctx || (!counts && ctx->n_nodes > 0) || max_rows < 0) return TIER_EINVAL;
+    const int64_t n = ctx->n_nodes;
+    hipStream_t st = ctx->stream, gs = ctx->gather_stream;
+    if (max_rows > n) max_rows = n;
+    // an earlier fill may still read the staging area and its maps
+    if (gs != st) TIER_HIP(ctx, hipStreamSynchronize(gs));
+    ctx->fill_pending = false;
+    ctx->staged_rows = 0;
+    if (max_rows == 0) return TIER_OK;
+    sort_bufs &b = ctx->sort;
+    int32_t *order = nullptr;
+    int rc = sort_by_count(ctx, counts, b, &order);
+    if (rc == TIER_OK) rc = tier_ensure(ctx, (void **)&ctx->staged_ids, &ctx->staged_ids_cap, (size_t)max_rows * sizeof(int32_t));
+    if (rc == TIER_OK) rc = tier_ensure(ctx, (void **)&ctx->staged_of, &ctx->staged_of_cap, (size_t)n * sizeof(int32_t));
+    if (rc == TIER_OK)
+        rc = tier_ensure(ctx, (void **)&ctx->staged_bits, &ctx->staged_bits_cap, (size_t)((n + 31) / 32) * sizeof(uint32_t));
+    if (rc == TIER_OK)
+        rc = tier_ensure(ctx, (void **)&ctx->staging, &ctx->staging_cap, (size_t)max_rows * (size_t)ctx->row_bytes);
+    if (rc != TIER_OK) return rc;
+    // the order lives in the sort's scratch, which the next sort overwrites: keep the part that is fetched
+    TIER_HIP(ctx, hipMemcpyAsync(ctx->staged_ids, order, (size_t)max_rows * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n, max_rows, ctx->staged_of);
+    k_hot_bits<<<grid_for((n + 31) / 32, 256, 4096), 256, 0, st>>>(ctx->staged_of, n, ctx->staged_bits);
+    TIER_HIP(ctx, hipGetLastError());
+    if (gs != st) {
+        TIER_HIP(ctx, hipEventRecord(ctx->ev_place, st));
+        TIER_HIP(ctx, hipStreamWaitEvent(gs, ctx->ev_place, 0));
+    }
+    // Half the blocks that a fill takes: this copy runs beside other work, whose kernel launches themselves
+    // cross the host link and slow down the more requests are queued there (cfg3, 260 presampling launches
+    // beside it: +4 ms with 32 blocks, +12 ms with 64; with 16 the copy loses more than the launches gain).
+    rc = tier_launch_gather(ctx, ctx->staged_ids, max_rows, GATHER_HOST, ctx->staging, false, kPrefetchBlocks);
+    if (rc != TIER_OK) return rc;
+    ctx->staged_rows = max_rows;
+    return TIER_OK;
+}
+
 // Placement for a graph and table already ordered by rank (Sec. 3.2 second method,
 // Sec. 4.1): the first n_hot rows are the hot part, copied to HBM in one piece.
 extern "C" int tier_place_boundary(tier_ctx *ctx, uint64_t budget_bytes, int64_t *n_hot_out)
@@ -419,6 +466,7 @@ extern "C" int tier_place_boundary(tier_ctx *ctx, uint64_t budget_bytes, int64_t
     TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
     ctx->placed = false;
     ctx->fill_pending = false;
+    ctx->staged_rows = 0;
     ctx->n_hot = 0;
     if (n_hot > 0) {
         int rc = tier_ensure(ctx, (void **)&ctx->cache, &ctx->cache_cap, (size_t)n_hot * (size_t)ctx->row_bytes);

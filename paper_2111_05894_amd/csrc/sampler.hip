@@ -1620,12 +1620,15 @@ int tier_sample_minibatch(tier_ctx *ctx, const int32_t *seeds, int32_t n_seeds, 
     return tier_sample_minibatches(ctx, seeds, n_seeds, n_seeds > 0 ? n_seeds : 1, 1, fanouts, n_layers, &seed, &b);
 }
 
+// The mini-batches [first_batch, first_batch + n_run) of every epoch; accumulate: counts[] is added to.
 static int presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
                      const int32_t *fanouts, int32_t n_layers, int32_t epochs, uint64_t seed, uint32_t *counts,
-                     int64_t *total_rows, int64_t *total_edges, bool draws)
+                     int64_t *total_rows, int64_t *total_edges, bool draws, int64_t first_batch = 0,
+                     int64_t n_run = INT64_MAX, bool accumulate = false)
 {
     if (!ctx || !counts || n_train < 0 || (n_train > 0 && !train_ids) || batch_size < 1 || epochs < 0)
         return TIER_EINVAL;
+    if (first_batch < 0 || n_run < 0) return TIER_EINVAL;
     int rc = check_fanouts(fanouts, n_layers);
     if (rc) return rc;
     const int64_t first = n_train < batch_size ? n_train : batch_size;
@@ -1645,13 +1648,15 @@ static int presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, i
         if (rc) return rc;
     }
 
-    k_fill_u32<<<clamp_grid(ctx->n_nodes, kBlock, 4096), kBlock, 0, ctx->stream>>>(counts, ctx->n_nodes, 0u);
+    if (!accumulate)
+        k_fill_u32<<<clamp_grid(ctx->n_nodes, kBlock, 4096), kBlock, 0, ctx->stream>>>(counts, ctx->n_nodes, 0u);
     k_clear_totals<<<1, 1, 0, ctx->stream>>>(ctx->meta);
     wide_out o = {};
     o.counts = counts;
-    const int64_t n_batches = (n_train + batch_size - 1) / batch_size;
+    const int64_t all_batches = (n_train + batch_size - 1) / batch_size;
+    const int64_t n_batches = n_run < all_batches - first_batch ? first_batch + n_run : all_batches;   // end of the range
     for (int e = 0; e < epochs; ++e) {
-        for (int64_t b = 0; b < n_batches; b += ctx->n_slots) {
+        for (int64_t b = first_batch; b < n_batches; b += ctx->n_slots) {
             const int slots = (int)(n_batches - b < ctx->n_slots ? n_batches - b : ctx->n_slots);
             const int64_t lo = b * batch_size;
             wide_t w = make_wide(ctx, train_ids + lo, n_train - lo, batch_size, slots, ctx->ps_nodes, stride, table_log2,
@@ -1683,6 +1688,14 @@ int tier_presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int
 {
     return presample(ctx, train_ids, n_train, batch_size, fanouts, n_layers, epochs, seed, counts, total_rows,
                      total_edges, false);
+}
+
+int tier_presample_range(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,
+                         const int32_t *fanouts, int32_t n_layers, int32_t epochs, uint64_t seed, int64_t first_batch,
+                         int64_t n_batches, int32_t accumulate, uint32_t *counts)
+{
+    return presample(ctx, train_ids, n_train, batch_size, fanouts, n_layers, epochs, seed, counts, nullptr, nullptr,
+                     false, first_batch, n_batches, accumulate != 0);
 }
 
 int tier_presample_draws(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, int32_t batch_size,

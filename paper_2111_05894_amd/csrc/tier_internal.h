@@ -103,6 +103,16 @@ struct tier_ctx {
     hipEvent_t ev_place;     // orders the cache fill (gather stream) after the slot map (main stream)
     bool fill_pending;       // a cache fill may still be reading sort.vals on the gather stream
     int64_t n_hot;
+    // rows fetched ahead of a placement (tier_prefetch): the next cache fill takes them from `staging`
+    int64_t staged_rows;     // 0: nothing staged
+    int32_t *staged_ids;     // staged_rows node ids, in the order of the ranking they were chosen by
+    size_t staged_ids_cap;   // bytes
+    uint8_t *staging;        // staged_rows x row_bytes: row i = feature row of staged_ids[i]
+    size_t staging_cap;
+    int32_t *staged_of;      // n_nodes: position in `staging`, or -1
+    size_t staged_of_cap;
+    uint32_t *staged_bits;   // ceil(n_nodes / 32): bit v set <=> staged_of[v] >= 0
+    size_t staged_bits_cap;
     bool placed;
     bool boundary;           // true: rows are in rank order, hot <=> id < n_hot (no slot map)
     // sampler scratch
@@ -131,8 +141,13 @@ struct tier_ctx {
 
 // gather.hip: row copy used by tier_gather_features and by the cache fill of tier_place.
 // mode 0: every row from host_rows; 1: through the slot map; 2: by the boundary n_hot.
+// link_blocks_cap > 0 (mode 0, table in host memory): fewer blocks than the launch would take by itself.
 enum { GATHER_HOST = 0, GATHER_SLOT = 1, GATHER_BOUNDARY = 2 };
-int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, void *out, bool count_hits);
+int tier_launch_gather(tier_ctx *ctx, const int32_t *ids, int64_t n, int mode, void *out, bool count_hits,
+                       int link_blocks_cap = 0);
+// gather.hip: the cache fill when rows are staged: out row i = feature row of ids[i], from `staging`
+// where staged_of[ids[i]] >= 0 and from host_rows otherwise (a split launch on the gather stream).
+int tier_launch_fill_staged(tier_ctx *ctx, const int32_t *ids, int64_t n, void *out);
 
 // context.hip: make *buf at least `bytes` long (contents are not kept).  Growing waits for both streams.
 int tier_ensure(tier_ctx *ctx, void **buf, size_t *cap, size_t bytes);

@@ -20,7 +20,7 @@ _lib = None
 
 EXPORTS = (
     "tier_host_alloc", "tier_host_free", "tier_blocks_bounds", "tier_create", "tier_destroy",
-    "tier_presample", "tier_presample_draws", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
+    "tier_presample", "tier_presample_range", "tier_presample_draws", "tier_prefetch", "tier_batch_seed", "tier_place", "tier_sample_minibatch",
     "tier_sample_minibatches", "tier_max_batches", "tier_set_segment_words",
     "tier_score_degree", "tier_score_wrpr", "tier_rank_scores", "tier_place_scores",
     "tier_rank", "tier_rank_static", "tier_reorder_graph", "tier_reorder_rows", "tier_relabel_ids", "tier_place_boundary",
@@ -78,6 +78,9 @@ def _load():
         lib.tier_destroy.argtypes = [C.c_void_p]; lib.tier_destroy.restype = None
         lib.tier_presample.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, i32p, C.c_int32, C.c_int32,
                                        C.c_uint64, C.c_void_p, i64p, i64p]
+        lib.tier_presample_range.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, i32p, C.c_int32, C.c_int32,
+                                             C.c_uint64, C.c_int64, C.c_int64, C.c_int32, C.c_void_p]
+        lib.tier_prefetch.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
         lib.tier_presample_draws.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, i32p, C.c_int32, C.c_int32,
                                              C.c_uint64, C.c_void_p, i64p]
         lib.tier_batch_seed.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]; lib.tier_batch_seed.restype = C.c_uint64
@@ -230,6 +233,26 @@ def tier_presample(ctx: Context, train_ids: torch.Tensor, batch_size: int, fanou
                                 C.byref(tr) if want_totals else None, C.byref(te) if want_totals else None)
     _check(rc, "tier_presample")
     return (counts, tr.value, te.value) if want_totals else counts
+
+
+def tier_presample_range(ctx: Context, train_ids: torch.Tensor, batch_size: int, fanouts, epochs: int, seed: int,
+                         first_batch: int, n_batches: int, counts: torch.Tensor = None, accumulate: bool = False):
+    """Counts of the mini-batches [first_batch, first_batch + n_batches) of every epoch; with
+    ``accumulate`` they are added to ``counts``."""
+    fan, L = _fan(fanouts)
+    if counts is None:
+        if accumulate:
+            raise ValueError("accumulate needs counts")
+        counts = torch.empty(ctx.n_nodes, dtype=torch.int32, device=train_ids.device)
+    rc = _load().tier_presample_range(ctx.handle, _dev(train_ids, torch.int32, "train_ids"), train_ids.numel(),
+                                      batch_size, fan, L, epochs, seed, first_batch, n_batches, 1 if accumulate else 0,
+                                      _dev(counts, torch.int32, "counts"))
+    _check(rc, "tier_presample_range")
+    return counts
+
+
+def tier_prefetch(ctx: Context, counts: torch.Tensor, max_rows: int):
+    _check(_load().tier_prefetch(ctx.handle, _dev(counts, torch.int32, "counts"), max_rows), "tier_prefetch")
 
 
 def tier_presample_draws(ctx: Context, train_ids: torch.Tensor, batch_size: int, fanouts, epochs: int, seed: int,

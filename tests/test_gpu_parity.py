@@ -618,6 +618,98 @@ def test_hot_rows_come_from_the_cache():
         w.close()
 
 
+def test_presample_ranges_add_up(small):
+    """tier_presample_range: a range alone equals the literal histogram of its mini-batches'
+    frontiers, and ranges that cover every mini-batch add up to tier_presample's counts."""
+    train = synth.train_set(small.n, 0.3, 8).numpy()
+    bs, fan, seed, epochs = 64, (5, 4), 4242, 2
+    nb = -(-len(train) // bs)
+    tr = torch.from_numpy(train).to(DEV)
+    full = tier.tier_presample(small.ctx, tr, bs, fan, epochs, seed).cpu().numpy()
+    lo, cnt = 3, 7
+    part = tier.tier_presample_range(small.ctx, tr, bs, fan, epochs, seed, lo, cnt).cpu().numpy()
+    want = np.zeros(small.n, np.int64)
+    for e in range(epochs):
+        for b in range(lo, lo + cnt):
+            out = orc.sample_minibatch(small.indptr, small.indices, train[b * bs:(b + 1) * bs], fan, orc.batch_seed(seed, e, b),
+                                       local_idx=small.local_idx)
+            want[out["nodes"]] += 1
+    assert np.array_equal(part, want)
+    acc = tier.tier_presample_range(small.ctx, tr, bs, fan, epochs, seed, 0, lo)
+    tier.tier_presample_range(small.ctx, tr, bs, fan, epochs, seed, lo, cnt, acc, accumulate=True)
+    tier.tier_presample_range(small.ctx, tr, bs, fan, epochs, seed, lo + cnt, nb + 5, acc, accumulate=True)   # past the end: clipped
+    tier.tier_presample_range(small.ctx, tr, bs, fan, epochs, seed, nb + 2, 3, acc, accumulate=True)         # nothing there
+    assert np.array_equal(acc.cpu().numpy(), full)
+    wantc, _, _ = orc.presample(small.indptr, small.indices, train, bs, fan, epochs, seed, threads=4)
+    assert np.array_equal(full.view(np.uint32), wantc)
+    with pytest.raises(tier.TierError):
+        tier.tier_presample_range(small.ctx, tr, bs, fan, epochs, seed, -1, 3)
+
+
+@pytest.mark.parametrize("own_stream", [False, True], ids=["one_stream", "two_streams"])
+def test_prefetch_leaves_the_placement_as_it_is(own_stream):
+    """Rows staged ahead of a placement (by counts of the first mini-batches, by counts that
+    predict nothing, all rows, one row, none) change neither the slot map nor a byte of the
+    cache, and the staged rows really are what the fill reads."""
+    ip, ix = synth.rmat_csr(30_000, 300_000, 11, "cpu")
+    w = World(ip, ix, dim=100)
+    gs = torch.cuda.Stream() if own_stream else None
+    if own_stream:
+        tier.tier_set_gather_stream(w.ctx, gs)
+    try:
+        rng = np.random.default_rng(12)
+        train = synth.train_set(w.n, 0.2, 5)
+        tr = train.to(DEV)
+        bs, fan = 256, (6, 4)
+        all_ids = torch.arange(w.n, dtype=torch.int32, device=DEV)
+        wantc, _, _ = orc.presample(w.indptr, w.indices, train.numpy(), bs, fan, 1, 5894, threads=4)
+        first = tier.tier_presample_range(w.ctx, tr, bs, fan, 1, 5894, 0, 6)
+        junk = torch.from_numpy(rng.integers(0, 1000, w.n).astype(np.int32)).to(DEV)
+        for guess, max_rows, hot_rows in ((first, 2000, 6000), (junk, 5000, 3000), (first, w.n + 10, 6000), (first, 1, 10),
+                                          (first, 0, 500), (junk, 4000, 0), (first, 3000, w.n)):
+            torch.cuda.synchronize()
+            w.feat += 1.0                               # a cache row that this round does not fill would show
+            tier.tier_prefetch(w.ctx, guess, max_rows)
+            counts = tier.tier_presample_range(w.ctx, tr, bs, fan, 1, 5894, 0, 6)              # while the rows come in
+            tier.tier_presample_range(w.ctx, tr, bs, fan, 1, 5894, 6, 1 << 30, counts, accumulate=True)
+            slot, n_hot = tier.tier_place(w.ctx, counts, hot_rows * w.row_bytes)
+            assert np.array_equal(counts.cpu().numpy().view(np.uint32), wantc)
+            _, oslot, ohot = orc.place(wantc, w.row_bytes, hot_rows * w.row_bytes)
+            assert n_hot == ohot and np.array_equal(slot.cpu().numpy(), oslot)
+            if own_stream:
+                with torch.cuda.stream(gs):
+                    out, hit, miss = tier.tier_gather_features(w.ctx, all_ids, want_stats=True)
+            else:
+                out, hit, miss = tier.tier_gather_features(w.ctx, all_ids, want_stats=True)
+            assert (hit, miss) == (ohot, w.n - ohot)
+            assert np.array_equal(out.view(torch.uint8).cpu().numpy().reshape(w.n, -1), w.feat_bytes)
+        # the staged rows are what the fill reads: change the table after they are in
+        tier.tier_prefetch(w.ctx, first, 2500)
+        torch.cuda.synchronize()
+        order = np.lexsort((np.arange(w.n), -first.cpu().numpy().view(np.uint32).astype(np.int64)))
+        staged = np.zeros(w.n, bool); staged[order[:2500]] = True
+        orig = w.feat.clone()
+        w.feat += 1.0
+        slot, n_hot = tier.tier_place(w.ctx, counts, 6000 * w.row_bytes)
+        torch.cuda.synchronize()
+        w.feat += 1.0                                                   # cold rows are read at gather time
+        if own_stream:
+            with torch.cuda.stream(gs):
+                out = tier.tier_gather_features(w.ctx, all_ids)
+        else:
+            out = tier.tier_gather_features(w.ctx, all_ids)
+        torch.cuda.synchronize()                                        # the gather may be on its own stream
+        out = out.cpu()
+        hot = slot.cpu().numpy() >= 0
+        old = torch.from_numpy(hot & staged); mid = torch.from_numpy(hot & ~staged); cold = torch.from_numpy(~hot)
+        assert int(old.sum()) > 2000 and int(mid.sum()) > 2000
+        assert torch.equal(out[old], orig[old]) and torch.equal(out[mid], orig[mid] + 1.0) and torch.equal(out[cold], w.feat[cold])
+    finally:
+        if own_stream:
+            tier.tier_set_gather_stream(w.ctx, None)
+        w.close()
+
+
 # ------------------------------------------------------------------------------
 # the whole path on the smallest benchmark configuration, full size
 # ------------------------------------------------------------------------------
