@@ -428,10 +428,12 @@ def main():
                 "gather_ms": round(bms, 3), "gather_GBps": round(brows * R / (bms * 1e-3) / 1e9, 2),
                 "host_link_bytes_tiered": blinks * R, "host_link_reduction": round(1 - blinks / brows, 4),
                 "roofline_frac": round(alg_bytes_row * brows / (bms * 1e-3) / 1e9 / bpeak, 4),
-                "step_ms_with_this_budget": round(mean(rec["presample_ms"]) + place_ms[0] + brec["epoch_wall_ms"][0], 3)}
+                "step_ms_with_this_budget": round((prefetch["presample_ms_without"] if prefetch else mean(rec["presample_ms"]))
+                                                  + place_ms[0] + brec["epoch_wall_ms"][0], 3)}
             log(f"[bench] budget {frac}: {budget_sweep[f'{frac:.2f}']}")
-        budget_sweep["note"] = ("same counts, other budgets: placement (order, slot map, cache fill over the host link) and the "
-                                "measured epoch, timed as in the step; roofline_frac as roofline.frac")
+        budget_sweep["note"] = ("same counts, other budgets: placement (order, slot map, cache fill over the host link, no rows "
+                                "fetched ahead) and the measured epoch, timed as in the step; step_ms_with_this_budget = "
+                                "presampling in one piece + these two; roofline_frac as roofline.frac")
         tier.tier_place(ctx, counts, budget, want_slot_map=False)
         torch.cuda.synchronize()
 
