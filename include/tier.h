@@ -266,8 +266,8 @@ int tier_relabel_ids(tier_ctx *ctx, const int32_t *rank, const int32_t *ids, int
  * For callers whose host link is idle while counts are still being collected: counts of the
  * first mini-batches (tier_presample_range) already name the hottest rows.  The staged rows
  * serve one placement and must not change in the table before it.  Scratch owned by the
- * context: max_rows * row_bytes + 4.2 bytes per node.  Waits for the ranking's digits, not
- * for the copy. */
+ * context: max_rows * row_bytes + 4.2 bytes per node.  Asynchronous once that scratch is
+ * there (it waits for the gather stream first when that is a stream of its own). */
 int tier_prefetch(tier_ctx *ctx, const uint32_t *counts, int64_t max_rows);
 
 /* Placement for a context whose graph and table are already in rank order (created on

@@ -134,6 +134,7 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipFree(ctx->staging);
     (void)hipFree(ctx->staged_of);
     (void)hipFree(ctx->staged_bits);
+    (void)hipFree(ctx->select);
     (void)hipStreamSynchronize(ctx->gather_stream);
     (void)hipFree(ctx->claim);
     (void)hipFree(ctx->deferred);

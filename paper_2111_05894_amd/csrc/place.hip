@@ -412,9 +412,192 @@ extern "C" int tier_place_scores(tier_ctx *ctx, const double *scores, uint64_t b
 
 constexpr int kPrefetchBlocks = 32;
 
-// Fetch ahead of a placement: the max_rows first rows by `counts` (count descending, id ascending)
-// go to a staging area in HBM on the gather stream, and the next placement's cache fill takes every
-// row it finds there from HBM.
+// ---- which rows to fetch ahead: the max_rows largest counts, without sorting ---------------------
+// Four passes find the max_rows-th largest count t, one byte of it per pass from the top (a
+// histogram of that byte over the counts that agree with t in the bytes above, then a walk down the
+// histogram); a last pass takes every node with a larger count and as many of those with count t
+// as are still missing, both by ascending id (two more passes: per-block counts, their prefix sums,
+// then the places).  All on the device; nothing here waits.
+constexpr int kSelectBlocks = 8192;  // most blocks of the last two passes; each owns a contiguous share of the nodes
+
+struct select_t {
+    uint32_t prefix;                 // the bytes of t found so far
+    uint32_t pad_;
+    unsigned long long remaining;    // rows still to find among the counts that agree with prefix
+    uint32_t hist[256];
+    uint32_t above[kSelectBlocks];   // per block: nodes of its share with count > t (then: of the shares before it)
+    uint32_t equal[kSelectBlocks];   // likewise with count == t
+};
+
+__global__ void k_select_init(select_t *sel, unsigned long long max_rows)
+{
+    if (threadIdx.x == 0) {
+        sel->prefix = 0u;
+        sel->remaining = max_rows;
+    }
+    sel->hist[threadIdx.x] = 0u;     // 256 threads
+}
+
+__global__ __launch_bounds__(256) void k_select_hist(const uint32_t *__restrict__ counts, int64_t n, int shift, select_t *sel)
+{
+    __shared__ uint32_t s_h[256];
+    s_h[threadIdx.x] = 0u;
+    __syncthreads();
+    const uint32_t prefix = sel->prefix;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
+        const uint32_t key = counts[v];
+        const bool in = shift == 24 || (key >> (shift + 8)) == (prefix >> (shift + 8));
+        const uint32_t digit = (key >> shift) & 255u;
+        // counts are small numbers: most lanes of a wave hold the same digit, so one lane adds for all of them
+        unsigned long long todo = __ballot(in);
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const uint32_t d = (uint32_t)__shfl((int)digit, leader);
+            const unsigned long long same = __ballot(in && digit == d);
+            if ((threadIdx.x & 63) == leader) atomicAdd(&s_h[d], (uint32_t)__popcll(same));
+            todo &= ~same;
+        }
+    }
+    __syncthreads();
+    if (s_h[threadIdx.x]) atomicAdd(&sel->hist[threadIdx.x], s_h[threadIdx.x]);
+}
+
+// The byte of t at `shift`: the largest digit d such that the counts with a digit >= d (and the bytes
+// above as in prefix) number at least `remaining`.
+__global__ void k_select_digit(select_t *sel, int shift)
+{
+    __shared__ uint32_t s_h[256];
+    s_h[threadIdx.x] = sel->hist[threadIdx.x];
+    sel->hist[threadIdx.x] = 0u;     // for the next pass
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long rem = sel->remaining;
+        int d = 255;
+        for (; d > 0; --d) {
+            if (s_h[d] >= rem) break;
+            rem -= s_h[d];
+        }
+        sel->prefix |= (uint32_t)d << shift;
+        sel->remaining = rem;
+    }
+}
+
+// Block b owns the nodes [b * share, (b + 1) * share), share a multiple of 256: how many of them
+// lie above t, how many on it.
+__global__ __launch_bounds__(256) void k_select_count(const uint32_t *__restrict__ counts, int64_t n, int64_t share, select_t *sel)
+{
+    __shared__ int s_a[4], s_e[4];
+    const uint32_t t = sel->prefix;
+    const int64_t lo = (int64_t)blockIdx.x * share;
+    int64_t hi = lo + share;
+    if (hi > n) hi = n;
+    int a = 0, e = 0;
+    for (int64_t v = lo + threadIdx.x; v < hi; v += 256) {
+        const uint32_t key = counts[v];
+        a += key > t;
+        e += key == t;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        a += __shfl_xor(a, off);
+        e += __shfl_xor(e, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_a[threadIdx.x >> 6] = a;
+        s_e[threadIdx.x >> 6] = e;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        sel->above[blockIdx.x] = (uint32_t)(s_a[0] + s_a[1] + s_a[2] + s_a[3]);
+        sel->equal[blockIdx.x] = (uint32_t)(s_e[0] + s_e[1] + s_e[2] + s_e[3]);
+    }
+}
+
+// Exclusive prefix sums over the blocks' two counts, in place (one block of 1024 threads).
+__global__ __launch_bounds__(1024) void k_select_scan(select_t *sel, int n_blocks)
+{
+    __shared__ uint32_t s_w[2][16];
+    constexpr int kPer = kSelectBlocks / 1024;
+    const int first = threadIdx.x * kPer, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int which = 0; which < 2; ++which) {
+        uint32_t *x = which ? sel->equal : sel->above;
+        uint32_t mine[kPer], sum = 0u;
+        for (int j = 0; j < kPer; ++j) {
+            mine[j] = first + j < n_blocks ? x[first + j] : 0u;
+            sum += mine[j];
+        }
+        uint32_t incl = sum;
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t y = (uint32_t)__shfl_up((int)incl, d);
+            if (lane >= d) incl += y;
+        }
+        if (lane == 63) s_w[which][wave] = incl;
+        __syncthreads();
+        uint32_t run = incl - sum;
+        for (int w = 0; w < wave; ++w) run += s_w[which][w];
+        for (int j = 0; j < kPer; ++j) {
+            if (first + j < n_blocks) x[first + j] = run;
+            run += mine[j];
+        }
+    }
+}
+
+// staged_of[v] = place of v's row in the staging area, or -1; staged_ids[place] = v; staged_bits as
+// k_hot_bits would make them.  Places go by node id: first the nodes above t, then, as long as rows
+// are missing, those on it.  A wave takes 64 consecutive nodes at a time.
+__global__ __launch_bounds__(256) void k_select_take(const uint32_t *__restrict__ counts, int64_t n, int64_t share,
+                                                      int64_t max_rows, const select_t *sel, int32_t *__restrict__ staged_ids,
+                                                      int32_t *__restrict__ staged_of, uint32_t *__restrict__ staged_bits)
+{
+    __shared__ int s_a[4], s_e[4];
+    const uint32_t t = sel->prefix;
+    const int64_t want_equal = (int64_t)sel->remaining;              // of the counts == t
+    const int64_t n_above = max_rows - want_equal;                   // counts > t: all of them
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long below_me = (1ull << lane) - 1ull;
+    const int64_t lo = (int64_t)blockIdx.x * share;
+    int64_t hi = lo + share;
+    if (hi > n) hi = n;
+    int64_t base_a = sel->above[blockIdx.x], base_e = sel->equal[blockIdx.x];
+    for (int64_t v0 = lo; v0 < hi; v0 += 256) {                      // the whole block takes every step
+        const int64_t v = v0 + threadIdx.x;
+        const uint32_t key = v < hi ? counts[v] : 0u;
+        const bool above = v < hi && key > t, equal = v < hi && key == t;
+        const unsigned long long m_above = __ballot(above), m_equal = __ballot(equal);
+        __syncthreads();
+        if (lane == 0) {
+            s_a[wave] = __popcll(m_above);
+            s_e[wave] = __popcll(m_equal);
+        }
+        __syncthreads();
+        int64_t wa = base_a, we = base_e;
+        for (int w = 0; w < wave; ++w) {
+            wa += s_a[w];
+            we += s_e[w];
+        }
+        int64_t place = -1;
+        if (above) place = wa + __popcll(m_above & below_me);
+        if (equal) {
+            const int64_t j = we + __popcll(m_equal & below_me);
+            if (j < want_equal) place = n_above + j;
+        }
+        if (v < hi) {
+            staged_of[v] = (int32_t)place;
+            if (place >= 0) staged_ids[place] = (int32_t)v;
+        }
+        const unsigned long long m_in = __ballot(place >= 0);
+        const int64_t w0 = v0 + 64 * wave;                           // this wave's first node
+        if (lane == 0 && w0 < hi) {
+            staged_bits[w0 >> 5] = (uint32_t)m_in;
+            if (w0 + 32 < n) staged_bits[(w0 >> 5) + 1] = (uint32_t)(m_in >> 32);
+        }
+        base_a += s_a[0] + s_a[1] + s_a[2] + s_a[3];
+        base_e += s_e[0] + s_e[1] + s_e[2] + s_e[3];
+    }
+}
+
+// Fetch ahead of a placement: max_rows rows with the largest counts go to a staging area in HBM on
+// the gather stream, and the next placement's cache fill takes every row it finds there from HBM.
 extern "C" int tier_prefetch(tier_ctx *ctx, const uint32_t *counts, int64_t max_rows)
 {
     if (!ctx || (!counts && ctx->n_nodes > 0) || max_rows < 0) return TIER_EINVAL;
@@ -426,20 +609,26 @@ extern "C" int tier_prefetch(tier_ctx *ctx, const uint32_t *counts, int64_t max_
     ctx->fill_pending = false;
     ctx->staged_rows = 0;
     if (max_rows == 0) return TIER_OK;
-    sort_bufs &b = ctx->sort;
-    int32_t *order = nullptr;
-    int rc = sort_by_count(ctx, counts, b, &order);
-    if (rc == TIER_OK) rc = tier_ensure(ctx, (void **)&ctx->staged_ids, &ctx->staged_ids_cap, (size_t)max_rows * sizeof(int32_t));
+    int rc = tier_ensure(ctx, (void **)&ctx->staged_ids, &ctx->staged_ids_cap, (size_t)max_rows * sizeof(int32_t));
     if (rc == TIER_OK) rc = tier_ensure(ctx, (void **)&ctx->staged_of, &ctx->staged_of_cap, (size_t)n * sizeof(int32_t));
     if (rc == TIER_OK)
         rc = tier_ensure(ctx, (void **)&ctx->staged_bits, &ctx->staged_bits_cap, (size_t)((n + 31) / 32) * sizeof(uint32_t));
     if (rc == TIER_OK)
         rc = tier_ensure(ctx, (void **)&ctx->staging, &ctx->staging_cap, (size_t)max_rows * (size_t)ctx->row_bytes);
+    if (rc == TIER_OK) rc = tier_ensure(ctx, (void **)&ctx->select, &ctx->select_cap, sizeof(select_t));
     if (rc != TIER_OK) return rc;
-    // the order lives in the sort's scratch, which the next sort overwrites: keep the part that is fetched
-    TIER_HIP(ctx, hipMemcpyAsync(ctx->staged_ids, order, (size_t)max_rows * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
-    k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n, max_rows, ctx->staged_of);
-    k_hot_bits<<<grid_for((n + 31) / 32, 256, 4096), 256, 0, st>>>(ctx->staged_of, n, ctx->staged_bits);
+    select_t *sel = (select_t *)ctx->select;
+    const int grid = grid_for(n, 256, kSelectBlocks);
+    const int64_t share = ((n + grid - 1) / grid + 255) / 256 * 256;     // nodes per block of the last two passes
+    const int n_blocks = (int)((n + share - 1) / share);                 // <= grid
+    k_select_init<<<1, 256, 0, st>>>(sel, (unsigned long long)max_rows);
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        k_select_hist<<<grid, 256, 0, st>>>(counts, n, shift, sel);
+        k_select_digit<<<1, 256, 0, st>>>(sel, shift);
+    }
+    k_select_count<<<n_blocks, 256, 0, st>>>(counts, n, share, sel);
+    k_select_scan<<<1, 1024, 0, st>>>(sel, n_blocks);
+    k_select_take<<<n_blocks, 256, 0, st>>>(counts, n, share, max_rows, sel, ctx->staged_ids, ctx->staged_of, ctx->staged_bits);
     TIER_HIP(ctx, hipGetLastError());
     if (gs != st) {
         TIER_HIP(ctx, hipEventRecord(ctx->ev_place, st));

@@ -113,6 +113,8 @@ struct tier_ctx {
     size_t staged_of_cap;
     uint32_t *staged_bits;   // ceil(n_nodes / 32): bit v set <=> staged_of[v] >= 0
     size_t staged_bits_cap;
+    void *select;            // device scratch of tier_prefetch's search for the rows to stage
+    size_t select_cap;
     bool placed;
     bool boundary;           // true: rows are in rank order, hot <=> id < n_hot (no slot map)
     // sampler scratch

@@ -687,7 +687,7 @@ def test_prefetch_leaves_the_placement_as_it_is(own_stream):
         tier.tier_prefetch(w.ctx, first, 2500)
         torch.cuda.synchronize()
         order = np.lexsort((np.arange(w.n), -first.cpu().numpy().view(np.uint32).astype(np.int64)))
-        staged = np.zeros(w.n, bool); staged[order[:2500]] = True
+        staged = np.zeros(w.n, bool); staged[order[:2500]] = True       # count descending, id ascending
         orig = w.feat.clone()
         w.feat += 1.0
         slot, n_hot = tier.tier_place(w.ctx, counts, 6000 * w.row_bytes)
