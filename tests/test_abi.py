@@ -60,3 +60,15 @@ def test_missing_library_raises(tmp_path, monkeypatch):
     monkeypatch.setattr(tier, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         tier._load()
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C header: it compiles as C11 on its own (no HIP, no C++, no torch)."""
+    import subprocess
+    src = tmp_path / "use_tier.c"
+    src.write_text('#include "tier.h"\n'
+                   "int probe(void) { tier_gather_stats s; tier_csr g; tier_feat f; (void)s; (void)g; (void)f;\n"
+                   "  return TIER_OK + TIER_MAX_LAYERS + TIER_MAX_FANOUT + TIER_MAX_BATCHES + (int)sizeof(tier_blocks_batch); }\n")
+    r = subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
