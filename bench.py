@@ -335,14 +335,26 @@ def main():
                 epoch(grec, groups=gg)
             hits, links = epoch_stats(gg)
             cold = grec["rows"] - hits
+            alone = []
+            for _ in range(2):                     # the same calls with no gather beside them
+                torch.cuda.synchronize()
+                a, b_ = ev(), ev()
+                a.record()
+                for g in gg:
+                    sample_group(g)
+                b_.record(); torch.cuda.synchronize()
+                alone.append(a.elapsed_time(b_))
             group_table[str(size)] = {
+                "sample_alone_ms": round(min(alone), 3),
+                "sampled_edges_per_s": round(grec["edges"] / (min(alone) * 1e-3)),
                 "epoch_wall_ms": round(min(grec["epoch_wall_ms"]), 3), "gather_ms": round(min(grec["gather_ms"]), 3),
                 "sample_ms": round(min(grec["sample_ms"]), 3),
                 "cold_requests_crossing_the_link": round(links / cold, 4) if cold else 1.0,
                 "output_rows_held": grec["most_rows_per_call"], "output_bytes_held": grec["most_rows_per_call"] * R,
                 "gather_launches": grec["gather_launches"]}
         group_table["note"] = ("same placement, whole epoch sampled and gathered `size` mini-batches per call (best of 2); "
-                               "a larger call shares more cold rows and holds that many mini-batches' output rows at once")
+                               "a larger call shares more cold rows and holds that many mini-batches' output rows at once; "
+                               "sample_alone_ms / sampled_edges_per_s: the epoch's sampling calls with the GPU to themselves")
 
     # hit / miss rows of the measured epoch (outside the timed region: asking for them waits per batch)
     hit_rows, link_rows = epoch_stats(groups)

@@ -138,8 +138,8 @@ int tier_blocks_bounds(int64_t n_graph_nodes, int64_t n_seeds, const int32_t *fa
  * 0.26 - 0.41 bytes per node for each mini-batch that can be sampled at once (as many,
  * up to TIER_MAX_BATCHES, as fit in 8 GiB).  The first sampling call adds the sampler's
  * index (8 bytes per node of the largest frontier that can draw, per mini-batch slot) and,
- * above 32 M nodes, 16 bytes per edge of the bound on the last hop's edges for every
- * mini-batch of the call (its new nodes are sorted, not marked in a bitmap). */
+ * above 32 M nodes, 16 bytes per edge of the bound on the largest hop's edges for every
+ * mini-batch of the call (new nodes are sorted there, not marked in a bitmap). */
 int tier_create(tier_ctx **out, const tier_csr *csr, const tier_feat *feat, void *stream);
 void tier_destroy(tier_ctx *ctx);
 
@@ -307,7 +307,7 @@ int tier_max_batches(const tier_ctx *ctx);
  * bitmap by segments of `words` 32-bit words, one flag byte per segment: 1 (the default up
  * to 32 M nodes: 0.4 bytes of scratch per node and mini-batch slot) or 32 (the default
  * above: 0.26 bytes, tier_presample keeps its frontiers in the sampler's index instead
- * of a second bitmap, and the last hop of a block call sorts its new nodes into buckets of
+ * of a second bitmap, and block calls sort every hop's new nodes into buckets of
  * consecutive ids instead of marking them).  Waits for the context's stream; TIER_EINVAL
  * for any other value. */
 int tier_set_segment_words(tier_ctx *ctx, int32_t words);

@@ -52,10 +52,11 @@
 // A segment is one bitmap word on graphs of up to 32 M nodes and 32 words above, so
 // the kernels that read the bitmap walk one byte per 32 or 1024 nodes and touch only
 // the words of flagged segments: their cost follows the mini-batch, not the graph.
-// With 32 words per segment nearly every new node of the last hop, where most of a
-// mini-batch's nodes are found, would sit alone in its 128-byte line; there the last
-// hop of a block call does without the bitmap and sorts its new neighbours into
-// buckets of consecutive ids instead (k_part_*, further down).
+// With 32 words per segment nearly every new node would sit alone in its 128-byte line
+// (an atomic, then the line read again to count, to list, to relabel, to clear); there
+// block calls do without the bitmap and sort every hop's new neighbours into buckets
+// of consecutive ids instead (k_part_*, further down), and the bitmap serves
+// tier_presample only.
 //
 // tier_presample runs the same chains without materialising blocks (no offsets, no
 // edge ids, no relabel).  Up to 32 M nodes it keeps the frontier itself in two bitmaps
@@ -78,7 +79,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kXcds = 8;             // XCDs of an MI355X; workgroup i of a launch runs on XCD i % 8
-constexpr int kPartBlocks = 16;      // blocks per slot that sort the last hop's new neighbours into buckets (best of 8 .. 64)
+constexpr int kPartBlocks = 16;      // blocks per slot that sort a hop's new neighbours into buckets (best of 8 .. 64, at 16 to 64 slots)
 
 enum { MODE_BLOCKS = 0, MODE_COUNT_SMALL = 1, MODE_COUNT_LARGE = 2 };
 
@@ -670,8 +671,9 @@ __device__ inline int64_t emit_word(const slot_view &v, int table_log2, int64_t 
 // The nodes reached at hop `layer`, ascending, appended to the frontier.  keep == 0: they will
 // draw at the next hop, so they enter the frontier index (k_settle settles contested cells)
 // and the segment's bits and flag are cleared for the next hop (MODE_COUNT_LARGE: the bits move
-// on into `all`).  keep != 0 (last hop of a block call): nothing draws from them; the segment's
-// start position is recorded for k_relabel and the bits stay until k_finish.
+// on into `all`).  keep != 0 (last hop of a block call, one word per segment only: with 32 the
+// block calls go by buckets): nothing draws from them; the word's start position is recorded for
+// k_relabel and the bits stay until k_finish.
 template <int MODE>
 __global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer, int keep, int64_t cap_next)
 {
@@ -732,25 +734,20 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer,
             const uint4 piece = lines[seg * 8 + lane8];
             const int before = s_before[q];
             const int ahead = group8_excl_scan(popc4(piece));
-            if (lane8 == 0) {
-                if (keep) v.segbase[seg] = before;
-                else v.flag[seg] = 0;
-            }
+            if (lane8 == 0) v.flag[seg] = 0;
             if (piece.x | piece.y | piece.z | piece.w) {
-                if (!keep) {
-                    lines[seg * 8 + lane8] = make_uint4(0u, 0u, 0u, 0u);
-                    if (MODE == MODE_COUNT_LARGE) {                      // this lane alone owns the piece here
-                        uint4 a = lines_all[seg * 8 + lane8];
-                        a.x |= piece.x; a.y |= piece.y; a.z |= piece.z; a.w |= piece.w;
-                        lines_all[seg * 8 + lane8] = a;
-                    }
+                lines[seg * 8 + lane8] = make_uint4(0u, 0u, 0u, 0u);
+                if (MODE == MODE_COUNT_LARGE) {                          // this lane alone owns the piece here
+                    uint4 a = lines_all[seg * 8 + lane8];
+                    a.x |= piece.x; a.y |= piece.y; a.z |= piece.z; a.w |= piece.w;
+                    lines_all[seg * 8 + lane8] = a;
                 }
                 const int64_t word = (seg << 5) + lane8 * 4;
                 int64_t pos = base + before + ahead;
-                pos = emit_word(v, w.table_log2, cap_next, word, piece.x, pos, keep);
-                pos = emit_word(v, w.table_log2, cap_next, word + 1, piece.y, pos, keep);
-                pos = emit_word(v, w.table_log2, cap_next, word + 2, piece.z, pos, keep);
-                emit_word(v, w.table_log2, cap_next, word + 3, piece.w, pos, keep);
+                pos = emit_word(v, w.table_log2, cap_next, word, piece.x, pos, 0);
+                pos = emit_word(v, w.table_log2, cap_next, word + 1, piece.y, pos, 0);
+                pos = emit_word(v, w.table_log2, cap_next, word + 2, piece.z, pos, 0);
+                emit_word(v, w.table_log2, cap_next, word + 3, piece.w, pos, 0);
             }
         }
         carry += tot & 0xfffff;
@@ -783,22 +780,24 @@ __global__ __launch_bounds__(kBlock) void k_settle(wide_t w, int gx, const OffT 
     }
 }
 
-// ---- last hop of a block call on the large-graph layout: buckets instead of the bitmap ----------
-// Nothing draws from the nodes reached at the last hop, but they are most of a mini-batch, and on a
-// graph of 10^8 nodes every one of them sits alone in its 128-byte line of `fresh`: an atomic to set
-// the bit, then the line read again to count, to list, to relabel and to clear.  Instead
-// k_hop_sample leaves ~node in col[] (as it does anyway) and sets nothing, and the edges whose
-// neighbour is new are sorted by node id into buckets of 2^bucket_log2 consecutive ids (at most
-// 8192 buckets, a few dozen records each), with LDS atomics only:
+// ---- block calls on the large-graph layout: buckets instead of the bitmap ------------------------
+// On a graph of 10^8 nodes nearly every node that a hop reaches sits alone in its 128-byte line of
+// `fresh`: an atomic to set the bit, then the line read again to count, to list, to relabel and to
+// clear, and a walk over every segment's flag on top.  Instead k_hop_sample leaves ~node in col[]
+// (as it does anyway) and sets nothing, and the hop's edges whose neighbour is new are sorted by
+// node id into buckets of 2^bucket_log2 consecutive ids (at most 8192 buckets, a few dozen records
+// each), with LDS atomics only:
 //   k_part_hist     each of kPartBlocks blocks per slot counts its share of the edges per bucket
 //   k_part_cols     per bucket: records of the blocks before each block, and of all blocks
 //   k_part_scan     first record of every bucket
 //   k_part_scatter  records (node, edge) to their bucket's range (order inside a bucket: any)
-//   k_part_bucket   one wave per bucket: the bucket's nodes as a bitmap in LDS -> distinct nodes,
-//                   ascending, and the rank of every record's node among them
-//   k_part_scan     distinct nodes before every bucket; size of the final frontier
-//   k_part_final    col[] of the records' edges and the new nodes appended to the frontier
-// A slot's records, counts and lists stay in its XCD's L2 like the frontier index.
+//   k_part_bucket   one wave sorts a window of whole buckets across its lanes -> distinct nodes,
+//                   ascending, and the rank of every record's node among its bucket's
+//   k_part_scan     distinct nodes before every bucket; size of the next frontier
+//   k_part_final    final col[] of the records' edges (no k_relabel), the new nodes appended to
+//                   the frontier and, unless it is the last hop, entered into the frontier index
+// A slot's records, counts and lists stay in its XCD's L2 like the frontier index.  Measured on
+// 111 M nodes, per new node: 32 ns this way, 190 ns through the bitmap.
 
 __global__ __launch_bounds__(kBlock) void k_part_hist(wide_t w, int layer, layer_out_t o)
 {
@@ -1049,7 +1048,9 @@ __global__ __launch_bounds__(64) void k_part_bucket(wide_t w, int gx, int n_word
 
 // One thread per record: col[] of its edge, and (the first `distinct` records of a bucket) one of the
 // bucket's nodes to its place in the frontier.
-__global__ __launch_bounds__(kBlock) void k_part_final(wide_t w, int gx, int layer, int64_t cap_next, layer_out_t o)
+// insert != 0 (not the last hop): the nodes will draw, so they enter the frontier index as in k_bm_emit
+// (a plain store into an empty home cell; k_settle settles contested cells).
+__global__ __launch_bounds__(kBlock) void k_part_final(wide_t w, int gx, int layer, int64_t cap_next, int insert, layer_out_t o)
 {
     spot_t p;
     if (!my_spot(w, gx, p)) return;
@@ -1063,7 +1064,14 @@ __global__ __launch_bounds__(kBlock) void k_part_final(wide_t w, int gx, int lay
         const int64_t place = hop_base + v.bk_before[q];
         col[(uint32_t)rec] = (int32_t)(place + v.lrank[r]);
         const int64_t i = r - v.bk_start[q];
-        if (i < v.bk_cnt[q] && place + i < cap_next) v.nodes[place + i] = v.stage[r];
+        if (i < v.bk_cnt[q] && place + i < cap_next) {
+            const int32_t u = v.stage[r];
+            v.nodes[place + i] = u;
+            if (insert) {
+                const uint32_t h = home_of((uint32_t)u, w.table_log2);
+                if (v.table[h] == 0u) v.table[h] = (uint32_t)(place + i) + 1u;   // may lose to another store: k_settle
+            }
+        }
     }
 }
 
@@ -1175,20 +1183,19 @@ __global__ __launch_bounds__(kBlock) void k_count_columns(wide_t w, int large, u
         atomicAdd((unsigned long long *)&w.meta[META_TOTAL_ROWS], (unsigned long long)tot);
 }
 
-// col[e] of the sampled neighbours that were not in the frontier when they were drawn (k_hop_sample
-// left ~node there).  New at a hop that is not the last: the node has entered the index since.  New
-// at the last hop: its position is the frontier size before the hop + the new nodes listed before
-// its segment + the bits below its own in the segment (the bitmap still holds the hop's bits).
-// With 32 words per segment those bits are one 128-byte line: the 8 lanes of a group take the
-// group's edges one at a time, each lane 16 bytes of the line.
-__global__ __launch_bounds__(kBlock) void k_relabel(wide_t w, int gx, relabel_t r, int n_layers)
+// Block calls by the bitmap (one word per segment): col[e] of the sampled neighbours that were not
+// in the frontier when they were drawn (k_hop_sample left ~node there).  New at a hop that is not
+// the last: the node has entered the index since.  New at the last hop: its position is the
+// frontier size before the hop + the new nodes listed before its word + the bits below its own
+// (the bitmap still holds the hop's bits).
+__global__ __launch_bounds__(kBlock) void k_relabel(wide_t w, int gx, relabel_t r)
 {
     spot_t p;
     if (!my_spot(w, gx, p)) return;
     const slot_view v = view_of(w, p.slot);
     const int64_t stride = (int64_t)gx * kBlock;
     const int64_t t = (int64_t)p.bx * kBlock + threadIdx.x;
-    for (int l = 0; l < n_layers; ++l) {                          // n_layers < r.n_layers: k_part_final has done the last
+    for (int l = 0; l < r.n_layers; ++l) {
         int32_t *col = r.col[l] + (int64_t)p.slot * r.stride[l];
         const int64_t n = v.meta[META_NEDGES + l];
         const bool last = l == r.n_layers - 1;
@@ -1198,7 +1205,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel(wide_t w, int gx, relabel_t 
                 const int32_t c = col[e];
                 if (c < 0) col[e] = index_of(v.table, w.table_log2, v.nodes, ~c);
             }
-        } else if (w.seg_log2 == 0) {
+        } else {
             for (int64_t e = t; e < n; e += stride) {
                 const int32_t c = col[e];
                 if (c >= 0) continue;
@@ -1206,49 +1213,14 @@ __global__ __launch_bounds__(kBlock) void k_relabel(wide_t w, int gx, relabel_t 
                 const int64_t word = (uint32_t)u >> 5;
                 col[e] = before_hop + v.segbase[word] + __popc(v.fresh[word] & ((1u << (u & 31)) - 1u));
             }
-        } else {
-            const int lane8 = threadIdx.x & 7;
-            const uint4 *lines = (const uint4 *)v.fresh;                 // a segment = 8 pieces of 16 bytes
-            for (int64_t e0 = t - threadIdx.x; e0 < n; e0 += stride) {   // the whole block takes every step
-                const int64_t e = e0 + threadIdx.x;
-                const int32_t c = e < n ? col[e] : 0;
-                const int32_t start = c < 0 ? before_hop + v.segbase[(uint32_t)~c >> 10] : 0;
-                int32_t ci[8];
-                uint4 piece[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {                             // the eight lines of the group's edges, all in flight
-                    ci[i] = __shfl(c, i, 8);
-                    piece[i] = make_uint4(0u, 0u, 0u, 0u);
-                    if (ci[i] < 0) piece[i] = lines[(int64_t)((uint32_t)~ci[i] >> 10) * 8 + lane8];
-                }
-                int32_t mine = 0;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const uint32_t u = (uint32_t)~ci[i];
-                    const int word_in_seg = (u >> 5) & 31;
-                    const uint32_t words[4] = {piece[i].x, piece[i].y, piece[i].z, piece[i].w};
-                    int rank = 0;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int wi = lane8 * 4 + j;
-                        const uint32_t below = wi < word_in_seg ? 0xffffffffu : (wi == word_in_seg ? (1u << (u & 31)) - 1u : 0u);
-                        rank += __popc(words[j] & below);
-                    }
-                    rank = group8_sum(rank);
-                    if (lane8 == i) mine = rank;
-                }
-                if (c < 0) col[e] = start + mine;
-            }
         }
     }
 }
 
-// End of a mini-batch: the frontier index back to all empty, and (block calls) the bits and flags
-// that the last hop left in place for k_relabel.
+// End of a mini-batch: the frontier index back to all empty, and (block calls by the bitmap, one
+// word per segment) the bits and flags that the last hop left in place for k_relabel.
 __global__ __launch_bounds__(kBlock) void k_finish(wide_t w, int gx, int clear_fresh)
 {
-    __shared__ int s_wave[kBlock / 64];
-    __shared__ int s_list[kSegTile];
     spot_t p;
     if (!my_spot(w, gx, p)) return;
     const slot_view v = view_of(w, p.slot);
@@ -1258,31 +1230,11 @@ __global__ __launch_bounds__(kBlock) void k_finish(wide_t w, int gx, int clear_f
     const int64_t n_cells4 = (1ll << w.table_log2) / 4;
     for (int64_t i = t; i < n_cells4; i += stride) cells[i] = make_uint4(0u, 0u, 0u, 0u);
     if (!clear_fresh) return;
-    if (w.seg_log2 == 0) {
-        for (int64_t i = t; i < w.n_seg; i += stride)
-            if (v.flag[i]) {
-                v.flag[i] = 0;
-                v.fresh[i] = 0u;
-            }
-        return;
-    }
-    int64_t lo, hi;
-    block_range(p, w.n_seg, lo, hi);
-    const int g = threadIdx.x >> 3, lane8 = threadIdx.x & 7;
-    uint4 *lines = (uint4 *)v.fresh;
-    for (int64_t tile = lo; tile < hi; tile += kSegTile) {
-        const int64_t i = tile + threadIdx.x;
-        const int f = (i < hi && v.flag[i] != 0) ? 1 : 0;
-        int n_f;
-        const int at = block_excl_scan(f, n_f, s_wave);
-        if (f) {
-            s_list[at] = threadIdx.x;
+    for (int64_t i = t; i < w.n_seg; i += stride)
+        if (v.flag[i]) {
             v.flag[i] = 0;
+            v.fresh[i] = 0u;
         }
-        __syncthreads();
-        for (int q = g; q < n_f; q += kSegGroups) lines[(tile + s_list[q]) * 8 + lane8] = make_uint4(0u, 0u, 0u, 0u);
-        __syncthreads();
-    }
 }
 
 __global__ void k_fill_u32(uint32_t *__restrict__ p, int64_t n, uint32_t value)
@@ -1367,12 +1319,13 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
     }
     const int seg_gx = clamp_grid(w.n_seg, kBlock, TIER_SCAN_BLOCKS);
     const int flat_gx = clamp_grid(w.n_words, 4 * kBlock, TIER_SCAN_BLOCKS);
-    const bool by_buckets = MODE == MODE_BLOCKS && w.n_buckets > 0;      // the last hop's new nodes: k_part_*
+    // block calls on the large-graph layout list every hop's new nodes by buckets (k_part_*), not by the bitmap
+    const bool by_buckets = MODE == MODE_BLOCKS && w.n_buckets > 0;
     for (int l = 0; l < n_layers; ++l) {
         const bool last = l == n_layers - 1;
-        launch_hop<MODE>(c, w, cap_nodes[l], l, fanouts[l], last, !(last && by_buckets), o);
+        launch_hop<MODE>(c, w, cap_nodes[l], l, fanouts[l], last, !by_buckets, o);
         if (MODE != MODE_BLOCKS && last) break;               // counted from the bitmaps, never listed
-        if (last && by_buckets) {
+        if (by_buckets) {
             const int nb = w.n_buckets;
             const size_t bins = (size_t)nb * sizeof(int);
             const int n_words = w.bucket_log2 > 5 ? 1 << (w.bucket_log2 - 5) : 1;
@@ -1386,10 +1339,8 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
             k_part_bucket<<<grid_of(bucket_gx, slots), 64, 2 * (size_t)n_words * sizeof(uint32_t), st>>>(w, bucket_gx, n_words);
             k_part_scan<<<grid_of(1, slots), kScanThreads, 0, st>>>(w, 1, l, cap_nodes[l + 1]);
             const int final_gx = clamp_grid(cap_edges[l], kBlock, kLoopBlocks);
-            k_part_final<<<grid_of(final_gx, slots), kBlock, 0, st>>>(w, final_gx, l, cap_nodes[l + 1], o.layer[l]);
-            break;
-        }
-        if (MODE == MODE_COUNT_SMALL) {
+            k_part_final<<<grid_of(final_gx, slots), kBlock, 0, st>>>(w, final_gx, l, cap_nodes[l + 1], last ? 0 : 1, o.layer[l]);
+        } else if (MODE == MODE_COUNT_SMALL) {
             k_bm_partial_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx);
             k_bm_emit_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx, l, cap_nodes[l + 1]);
         } else {
@@ -1405,14 +1356,13 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
         relabel_t r = {};
         r.n_layers = n_layers;
         int64_t most = 1;
-        const int relabelled = by_buckets ? n_layers - 1 : n_layers;       // k_part_final has done the last hop's col[]
         for (int l = 0; l < n_layers; ++l) {
             r.col[l] = o.layer[l].col;
             r.stride[l] = o.layer[l].edge_stride;
-            if (l < relabelled && cap_edges[l] > most) most = cap_edges[l];
+            if (cap_edges[l] > most) most = cap_edges[l];
         }
         const int gx = clamp_grid(most, kBlock, kLoopBlocks);
-        if (relabelled > 0) k_relabel<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, r, relabelled);
+        if (!by_buckets) k_relabel<<<grid_of(gx, slots), kBlock, 0, st>>>(w, gx, r);      // k_part_final writes final col[]
     } else {
         // tier_presample_draws has counted on the way: only the bitmaps are cleared
         k_count_columns<<<clamp_grid(c->n_words, kBlock, 1 << 22), kBlock, 0, st>>>(w, MODE == MODE_COUNT_LARGE ? 1 : 0,
@@ -1586,7 +1536,9 @@ int tier_sample_minibatches(tier_ctx *ctx, const int32_t *seeds, int64_t n_seeds
         w.key1[s] = (uint32_t)(batch_seeds[s] >> 32);
     }
     if (large_graph(ctx)) {
-        rc = ensure_buckets(ctx, &w, cap_edges[n_layers - 1], n_batches);
+        int64_t most_edges = 0;                                  // any hop may go by buckets
+        for (int l = 0; l < n_layers; ++l) most_edges = cap_edges[l] > most_edges ? cap_edges[l] : most_edges;
+        rc = ensure_buckets(ctx, &w, most_edges, n_batches);
         if (rc) return rc;
     }
     rc = enqueue_wide<MODE_BLOCKS>(ctx, w, fanouts, n_layers, cap_nodes, cap_edges, o);
