@@ -302,14 +302,14 @@ int tier_sample_minibatches(tier_ctx *ctx, const int32_t *seeds, int64_t n_seeds
 /* Mini-batches one call can take with this context's scratch memory (1..TIER_MAX_BATCHES). */
 int tier_max_batches(const tier_ctx *ctx);
 
-/* Layout of the sampler's scratch (tuning and testing; results never depend on it).  The
- * sampler marks the nodes first reached at a hop in a bitmap over all nodes and walks that
- * bitmap by segments of `words` 32-bit words, one flag byte per segment: 1 (the default up
- * to 32 M nodes: 0.4 bytes of scratch per node and mini-batch slot) or 32 (the default
- * above: 0.26 bytes, tier_presample keeps its frontiers in the sampler's index instead
- * of a second bitmap, and block calls sort every hop's new nodes into buckets of
- * consecutive ids instead of marking them).  Waits for the context's stream; TIER_EINVAL
- * for any other value. */
+/* Layout of the sampler's scratch (tuning and testing; results never depend on it).
+ * words = 1, the default up to 32 M nodes: the nodes first reached at a hop are marked in a
+ * bitmap over all nodes, one flag byte per 32-bit word of it tells the kernels that list
+ * them where to look, and tier_presample keeps its frontiers in bitmaps (0.4 bytes of
+ * scratch per node and mini-batch slot).  words = 32, the default above: the new nodes of
+ * a hop are sorted into buckets of consecutive ids instead, and tier_presample keeps its
+ * frontiers in the sampler's index (0.26 bytes per node and slot).  Waits for the
+ * context's stream; TIER_EINVAL for any other value. */
 int tier_set_segment_words(tier_ctx *ctx, int32_t words);
 
 /* Tiered gather (Sec. 4.1, Listing 1).  out[i, :] = feature row of ids[i], read from

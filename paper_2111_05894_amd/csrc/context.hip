@@ -153,6 +153,7 @@ void tier_destroy(tier_ctx *ctx)
     (void)hipFree(ctx->partial_hop);
     (void)hipFree(ctx->partial_bm);
     (void)hipFree(ctx->ps_nodes);
+    (void)hipFree(ctx->ps_col);
     (void)hipFree(ctx->pulled);
     (void)hipFree(ctx->scan_partial);
     (void)hipGetLastError();

@@ -12,22 +12,19 @@
 //   k_hop_sample    a group of G lanes per dst draws its neighbours: lane i owns
 //                   draw i, the Floyd collision rule is resolved with in-group
 //                   shuffles; a neighbour already in the frontier gets its frontier
-//                   index at once, any other sets its bit in `fresh`, a bitmap over
-//                   all nodes, and the byte flag of the bit's segment
-//   k_bm_partial    popcounts of the flagged segments
-//   k_bm_emit       flagged segments -> ascending list of new nodes appended to the
-//                   frontier (dedup and sort in one pass)
+//                   index at once, any other is new at this hop
+//   (new nodes)     deduplicated, listed in ascending order behind the frontier, and
+//                   every edge that led to one gets its index: one of the two ways below
 //   k_settle        the new nodes' adjacency offsets and degrees, listed beside the
 //                   frontier (every later hop reads them in order instead of chasing
 //                   indptr[] again), and the second half of entering them into the
 //                   frontier index
-//   k_relabel       once per mini-batch: col[e] of the neighbours that were new at
-//                   their hop
 //   k_finish        leaves the slot's scratch clean for the next mini-batch
 //
 // What the design is built around, measured on MI355X: an atomic of any kind and
-// scope runs at ~27 G/s for the whole chip, a random 4-byte read from HBM at ~50 G/s,
-// and a random read or plain store that stays in one XCD's 4 MB L2 at ~240 G/s.  So
+// scope runs at ~27 G/s for the whole chip, a random 4-byte read from HBM at ~50 G/s
+// (and costs HBM a whole 128-byte line), and a random read or plain store that stays in
+// one XCD's 4 MB L2 at ~240 G/s.  So
 //   - every kernel maps workgroups to slots by XCD (workgroup i runs on XCD i % 8; a
 //     slot is served by one XCD only and the slots of an XCD one after the other), so
 //     that a slot's small structures live in that XCD's L2; nothing depends on this
@@ -36,38 +33,39 @@
 //     bytes per cell, key checked against nodes[]) sized for the largest frontier that
 //     ever draws (a few MB at most for the usual fanouts), not an array over all nodes:
 //     membership test and index are one lookup in L2;
-//   - nodes enter the table without atomics: k_bm_emit stores into an empty home cell
-//     with a plain store, k_settle (next kernel) checks who won a contested cell and
-//     moves only the losers on, by compare-and-swap;
+//   - nodes enter the table without atomics: the kernel that lists them stores into an
+//     empty home cell with a plain store, k_settle (next kernel) checks who won a
+//     contested cell and moves only the losers on, by compare-and-swap;
 //   - a dst node's work is a chain of dependent reads (offsets, neighbour id, index cell,
 //     key), and with every wave slot taken the chain's latency, not any throughput, set
 //     the pace: k_hop_sample therefore works on four dst nodes per lane group at a time,
 //     issuing each stage's reads for all four before it uses any;
 //   - the nodes reached at the last hop never enter the table (nothing is drawn from
-//     them): their frontier index is the segment's start position (written by
-//     k_bm_emit) plus the rank of their bit inside the segment;
-//   - the only atomic per sampled edge left is the bit in `fresh`, which dedups and
-//     sorts the new nodes; the flag of the segment is a plain byte store.
+//     them).
 //
-// A segment is one bitmap word on graphs of up to 32 M nodes and 32 words above, so
-// the kernels that read the bitmap walk one byte per 32 or 1024 nodes and touch only
-// the words of flagged segments: their cost follows the mini-batch, not the graph.
-// With 32 words per segment nearly every new node would sit alone in its 128-byte line
-// (an atomic, then the line read again to count, to list, to relabel, to clear); there
-// block calls do without the bitmap and sort every hop's new neighbours into buckets
-// of consecutive ids instead (k_part_*, further down), and the bitmap serves
-// tier_presample only.
+// The new nodes of a hop, two ways (the layout of a context: tier_set_segment_words):
+//   - bitmap, graphs of up to 32 M nodes: k_hop_sample sets the node's bit in `fresh`, a
+//     bitmap over all nodes (the one atomic per sampled edge), and a flag byte for the
+//     bitmap word; k_bm_partial / k_bm_emit walk the flags (a byte per 32 nodes) and turn
+//     the flagged words into the ascending list; k_relabel, once per mini-batch, gives the
+//     edges that led to new nodes their index (index lookup, or for the last hop the
+//     word's start position + the rank of the bit).  The whole bitmap sits in the
+//     last-level cache.
+//   - buckets, above: there nearly every new node would sit alone in its 128-byte line
+//     of the bitmap (an atomic, then the line read again to count, to list, to relabel,
+//     to clear).  Instead the hop's new neighbours are sorted into buckets of consecutive
+//     ids (k_part_*, further down): no global atomics, no relabel pass.
 //
 // tier_presample runs the same chains without materialising blocks (no offsets, no
-// edge ids, no relabel).  Up to 32 M nodes it keeps the frontier itself in two bitmaps
-// per slot (`seen` = frontier + reached at this hop, `prev` = frontier before the
-// hop; membership is one bit of `prev`, which stays in cache) and needs no index at
-// all; above, it uses the table for membership and a second bitmap `all` that
-// collects the whole frontier (the last hop marks it directly).  Either way a slot
-// ends with the bitmap of its mini-batch's final frontier, and one pass adds the
-// slots' bitmaps column by column (k_count_columns: no atomics; the nodes of the last
-// hop are never listed).  Within a mini-batch the frontier nodes are distinct, so no
-// counter is a hot spot that LDS staging could absorb.
+// edge ids).  On the bitmap layout it keeps the frontier itself in two bitmaps per slot
+// (`seen` = frontier + reached at this hop, `prev` = frontier before the hop;
+// membership is one bit of `prev`, which stays in cache) and needs no index at all; on
+// the other it uses the table for membership, buckets for the hops before the last, and
+// a bitmap `all` that collects the whole frontier (the last hop marks it directly).
+// Either way a slot ends with the bitmap of its mini-batch's final frontier, and one
+// pass adds the slots' bitmaps column by column (k_count_columns: no atomics; the nodes
+// of the last hop are never listed).  Within a mini-batch the frontier nodes are
+// distinct, so no counter is a hot spot that LDS staging could absorb.
 //
 // tier_presample_draws counts by the other reading (every seed and every drawn neighbour adds
 // one): the same chains, k_hop_sample<.., DRAWS> adding as it draws, through a small table per
@@ -90,7 +88,7 @@ struct wide_t {
     int32_t batch_size;
     int32_t n_slots;
     int32_t count_edges;         // != 0: add the sampled edges to META_TOTAL_EDGES (costs an atomic per block)
-    int32_t seg_log2;            // log2 of the bitmap words per segment (0 or 5)
+    int32_t seg_log2;            // 0: bitmap layout; 5: bucket layout (large graphs)
     int64_t n_nodes;             // graph nodes
     int64_t n_words;             // bitmap words that cover the graph
     int64_t bm_stride;           // bitmap words per slot (n_words rounded up to whole 128-byte lines; the rest stays zero)
@@ -444,6 +442,8 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const i
     const int s = p.slot;
     const int32_t *row_ptr = MODE == MODE_BLOCKS ? o.row_ptr + (int64_t)s * o.row_ptr_stride : nullptr;
     int32_t *col = MODE == MODE_BLOCKS ? o.col + (int64_t)s * o.edge_stride : nullptr;
+    // access counting on the large-graph layout, not the last hop: k entries per dst node for the k_part_* kernels
+    int32_t *dense_col = (MODE == MODE_COUNT_LARGE && o.col) ? o.col + (int64_t)s * o.edge_stride : nullptr;
     int64_t *eid = MODE == MODE_BLOCKS ? o.eid + (int64_t)s * o.edge_stride : nullptr;
     const uint32_t key0 = w.key0[s], key1 = w.key1[s];
     const int lane = threadIdx.x % G;
@@ -532,6 +532,8 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const i
         // stage 5: results
 #pragma unroll
         for (int j = 0; j < kAtOnce; ++j) {
+            if (MODE == MODE_COUNT_LARGE && dense_col && !take[j] && lane < k && i0 + j * sweep < n)
+                dense_col[(i0 + j * sweep) * k + lane] = 0;      // no draw here
             if (!take[j]) continue;
             int32_t at = -1;
             if (cell[j]) {
@@ -548,15 +550,16 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const i
             }
             if (MODE == MODE_BLOCKS) {
                 eid[rp[j] + lane] = beg[j] + pos[j];
-                col[rp[j] + lane] = at >= 0 ? at : ~u[j];        // negative: new at this hop, k_relabel finds its place
+                col[rp[j] + lane] = at >= 0 ? at : ~u[j];        // negative: new at this hop; its place comes later
             }
+            if (MODE == MODE_COUNT_LARGE && dense_col) dense_col[(i0 + j * sweep) * k + lane] = at >= 0 ? 0 : ~u[j];
             if (at < 0 && mark) {                                // mark == 0: the k_part_* kernels read ~node from col[]
                 const uint32_t word = (uint32_t)u[j] >> 5, bit = 1u << (u[j] & 31);
                 if (MODE == MODE_COUNT_LARGE && last) {
                     atomicOr(&v.aux[word], bit);                 // nobody lists the last hop's nodes: straight into `all`
                 } else {
                     atomicOr(&v.fresh[word], bit);
-                    v.flag[word >> w.seg_log2] = 1;
+                    v.flag[word] = 1;
                 }
             }
         }
@@ -573,77 +576,22 @@ __global__ __launch_bounds__(kBlock) void k_hop_sample(wide_t w, int gx, const i
     }
 }
 
-// ---- walking the flagged segments ---------------------------------------------------------------
-// A block takes its share of the segments 256 at a time: thread t reads the flag of segment
-// tile + t (consecutive bytes), the flagged ones are compacted, in order, into a list in LDS.
-// With one word per segment the thread then simply handles its own word.  With 32 words per
-// segment (one 128-byte line) a thread per segment would have every lane of a load on a
-// different line and a quarter of the bytes in flight that HBM needs; instead a group of 8
-// lanes takes one listed segment at a time, each lane 16 bytes of the line.
-constexpr int kSegTile = kBlock;
-constexpr int kSegGroups = kBlock / 8;
+// ---- walking the flagged words (bitmap layout: graphs of up to 32 M nodes) -----------------------
+// A flag byte per bitmap word says whether the hop set a bit in it, so the kernels below read one
+// byte per 32 nodes and touch only flagged words: their cost follows the mini-batch, not the graph.
 
-__device__ inline int popc4(const uint4 &x) { return __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w); }
-
-// Sum of x over the 8 lanes of a group, returned to every lane.
-__device__ inline int group8_sum(int x)
-{
-    x += __shfl_xor(x, 4, 8);
-    x += __shfl_xor(x, 2, 8);
-    x += __shfl_xor(x, 1, 8);
-    return x;
-}
-
-// Exclusive prefix of x over the 8 lanes of a group.
-__device__ inline int group8_excl_scan(int x)
-{
-    const int l = threadIdx.x & 7;
-    int incl = x;
-#pragma unroll
-    for (int d = 1; d < 8; d <<= 1) {
-        int y = __shfl_up(incl, d, 8);
-        if (l >= d) incl += y;
-    }
-    return incl - x;
-}
-
-// Popcounts of the flagged segments: their sum per block (for the scan over blocks) and, with 32
-// words per segment, each segment's own count in segbase[] (k_bm_emit reads it back, so that it
-// fetches every line only once).
+// Popcounts of the flagged words, summed per block (for the scan over blocks).
 __global__ __launch_bounds__(kBlock) void k_bm_partial(wide_t w, int gx)
 {
     __shared__ int s_wave[kBlock / 64];
-    __shared__ int s_list[kSegTile];
     spot_t p;
     if (!my_spot(w, gx, p)) return;
     const slot_view v = view_of(w, p.slot);
     int64_t lo, hi;
     block_range(p, w.n_seg, lo, hi);
     int sum = 0;
-    if (w.seg_log2 == 0) {
-        for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock)
-            if (v.flag[i]) sum += __popc(v.fresh[i]);
-    } else {
-        const int g = threadIdx.x >> 3, lane8 = threadIdx.x & 7;
-        const uint4 *lines = (const uint4 *)v.fresh;             // a slot's bitmap is whole lines
-        for (int64_t tile = lo; tile < hi; tile += kSegTile) {
-            const int64_t i = tile + threadIdx.x;
-            const int f = (i < hi && v.flag[i] != 0) ? 1 : 0;
-            int n_f;
-            const int at = block_excl_scan(f, n_f, s_wave);
-            if (f) s_list[at] = threadIdx.x;
-            __syncthreads();
-            for (int q = g; q < n_f; q += kSegGroups) {
-                const int64_t seg = tile + s_list[q];
-                const int c = group8_sum(popc4(lines[seg * 8 + lane8]));
-                if (lane8 == 0) {
-                    v.segbase[seg] = c;
-                    sum += c;
-                }
-            }
-            __syncthreads();
-        }
-    }
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock)
+        if (v.flag[i]) sum += __popc(v.fresh[i]);
     int tot = block_sum(sum, s_wave);
     if (threadIdx.x == 0) v.partial_bm[p.bx] = tot;
 }
@@ -670,16 +618,12 @@ __device__ inline int64_t emit_word(const slot_view &v, int table_log2, int64_t 
 
 // The nodes reached at hop `layer`, ascending, appended to the frontier.  keep == 0: they will
 // draw at the next hop, so they enter the frontier index (k_settle settles contested cells)
-// and the segment's bits and flag are cleared for the next hop (MODE_COUNT_LARGE: the bits move
-// on into `all`).  keep != 0 (last hop of a block call, one word per segment only: with 32 the
-// block calls go by buckets): nothing draws from them; the word's start position is recorded for
-// k_relabel and the bits stay until k_finish.
-template <int MODE>
+// and the word's bits and flag are cleared for the next hop.  keep != 0 (last hop): nothing
+// draws from them; the word's start position is recorded for k_relabel and the bits stay until
+// k_finish.
 __global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer, int keep, int64_t cap_next)
 {
     __shared__ int s_wave[kBlock / 64];
-    __shared__ int s_list[kSegTile];
-    __shared__ int s_before[kSegTile];
     spot_t p;
     if (!my_spot(w, gx, p)) return;
     const slot_view v = view_of(w, p.slot);
@@ -691,67 +635,22 @@ __global__ __launch_bounds__(kBlock) void k_bm_emit(wide_t w, int gx, int layer,
     // cap_next = the bound of tier_blocks_bounds on the next frontier; only repeated seeds (an error
     // the call reports) can take the sum beyond it
     if (p.bx == 0 && threadIdx.x == 0) v.meta[META_NFRONT + layer + 1] = base + all < cap_next ? base + all : cap_next;
-    if (w.seg_log2 == 0) {
-        for (int64_t tile = lo; tile < hi; tile += kBlock) {
-            const int64_t i = tile + threadIdx.x;
-            const bool live = i < hi && v.flag[i] != 0;
-            const uint32_t bits = live ? v.fresh[i] : 0u;
-            int tot;
-            const int before = carry + block_excl_scan(__popc(bits), tot, s_wave);
-            carry += tot;
-            if (live) {
-                if (keep) {
-                    v.segbase[i] = before;
-                } else {
-                    v.flag[i] = 0;
-                    v.fresh[i] = 0u;
-                    if (MODE == MODE_COUNT_LARGE) v.aux[i] |= bits;      // this thread alone owns the word here
-                }
-                emit_word(v, w.table_log2, cap_next, i, bits, base + before, keep);
-            }
-        }
-        return;
-    }
-    const int g = threadIdx.x >> 3, lane8 = threadIdx.x & 7;
-    uint4 *lines = (uint4 *)v.fresh;                             // a slot's bitmap is whole lines
-    uint4 *lines_all = (uint4 *)v.aux;
-    for (int64_t tile = lo; tile < hi; tile += kSegTile) {
-        // one scan gives both the place of a flagged segment in the list (high bits) and the number of
-        // new nodes before it (low bits: a tile holds at most 2^18 nodes)
+    for (int64_t tile = lo; tile < hi; tile += kBlock) {
         const int64_t i = tile + threadIdx.x;
         const bool live = i < hi && v.flag[i] != 0;
-        const int x = live ? ((1 << 20) | v.segbase[i]) : 0;      // k_bm_partial left the segment's count there
+        const uint32_t bits = live ? v.fresh[i] : 0u;
         int tot;
-        const int ex = block_excl_scan(x, tot, s_wave);
+        const int before = carry + block_excl_scan(__popc(bits), tot, s_wave);
+        carry += tot;
         if (live) {
-            s_list[ex >> 20] = threadIdx.x;
-            s_before[ex >> 20] = carry + (ex & 0xfffff);
-        }
-        __syncthreads();
-        const int n_f = tot >> 20;
-        for (int q = g; q < n_f; q += kSegGroups) {
-            const int64_t seg = tile + s_list[q];
-            const uint4 piece = lines[seg * 8 + lane8];
-            const int before = s_before[q];
-            const int ahead = group8_excl_scan(popc4(piece));
-            if (lane8 == 0) v.flag[seg] = 0;
-            if (piece.x | piece.y | piece.z | piece.w) {
-                lines[seg * 8 + lane8] = make_uint4(0u, 0u, 0u, 0u);
-                if (MODE == MODE_COUNT_LARGE) {                          // this lane alone owns the piece here
-                    uint4 a = lines_all[seg * 8 + lane8];
-                    a.x |= piece.x; a.y |= piece.y; a.z |= piece.z; a.w |= piece.w;
-                    lines_all[seg * 8 + lane8] = a;
-                }
-                const int64_t word = (seg << 5) + lane8 * 4;
-                int64_t pos = base + before + ahead;
-                pos = emit_word(v, w.table_log2, cap_next, word, piece.x, pos, 0);
-                pos = emit_word(v, w.table_log2, cap_next, word + 1, piece.y, pos, 0);
-                pos = emit_word(v, w.table_log2, cap_next, word + 2, piece.z, pos, 0);
-                emit_word(v, w.table_log2, cap_next, word + 3, piece.w, pos, 0);
+            if (keep) {
+                v.segbase[i] = before;
+            } else {
+                v.flag[i] = 0;
+                v.fresh[i] = 0u;
             }
+            emit_word(v, w.table_log2, cap_next, i, bits, base + before, keep);
         }
-        carry += tot & 0xfffff;
-        __syncthreads();
     }
 }
 
@@ -799,7 +698,9 @@ __global__ __launch_bounds__(kBlock) void k_settle(wide_t w, int gx, const OffT 
 // A slot's records, counts and lists stay in its XCD's L2 like the frontier index.  Measured on
 // 111 M nodes, per new node: 32 ns this way, 190 ns through the bitmap.
 
-__global__ __launch_bounds__(kBlock) void k_part_hist(wide_t w, int layer, layer_out_t o)
+// dense_k != 0 (access counting, which keeps no edge offsets): col[] holds dense_k entries for every
+// dst node of the hop, ~node where a new node was drawn and 0 elsewhere.
+__global__ __launch_bounds__(kBlock) void k_part_hist(wide_t w, int layer, int dense_k, layer_out_t o)
 {
     extern __shared__ int s_bins[];
     spot_t p;
@@ -809,7 +710,7 @@ __global__ __launch_bounds__(kBlock) void k_part_hist(wide_t w, int layer, layer
     for (int i = threadIdx.x; i < w.n_buckets; i += kBlock) s_bins[i] = 0;
     __syncthreads();
     int64_t lo, hi;
-    block_range(p, v.meta[META_NEDGES + layer], lo, hi);
+    block_range(p, dense_k ? v.meta[META_NFRONT + layer] * dense_k : v.meta[META_NEDGES + layer], lo, hi);
     for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += 4 * kBlock) {
         int32_t c[4];
 #pragma unroll
@@ -887,7 +788,7 @@ __global__ __launch_bounds__(kScanThreads) void k_part_scan(wide_t w, int which,
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_part_scatter(wide_t w, int layer, layer_out_t o)
+__global__ __launch_bounds__(kBlock) void k_part_scatter(wide_t w, int layer, int dense_k, layer_out_t o)
 {
     extern __shared__ int s_bins[];
     spot_t p;
@@ -898,7 +799,7 @@ __global__ __launch_bounds__(kBlock) void k_part_scatter(wide_t w, int layer, la
     for (int i = threadIdx.x; i < w.n_buckets; i += kBlock) s_bins[i] = v.bk_start[i] + row[i];
     __syncthreads();
     int64_t lo, hi;
-    block_range(p, v.meta[META_NEDGES + layer], lo, hi);          // the same share as in k_part_hist
+    block_range(p, dense_k ? v.meta[META_NFRONT + layer] * dense_k : v.meta[META_NEDGES + layer], lo, hi);   // as in k_part_hist
     for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += 4 * kBlock) {
         int32_t c[4];
 #pragma unroll
@@ -1050,7 +951,9 @@ __global__ __launch_bounds__(64) void k_part_bucket(wide_t w, int gx, int n_word
 // bucket's nodes to its place in the frontier.
 // insert != 0 (not the last hop): the nodes will draw, so they enter the frontier index as in k_bm_emit
 // (a plain store into an empty home cell; k_settle settles contested cells).
-__global__ __launch_bounds__(kBlock) void k_part_final(wide_t w, int gx, int layer, int64_t cap_next, int insert, layer_out_t o)
+// counting != 0 (access counting): col[] is scratch and stays as it is, and the new nodes join `all`.
+__global__ __launch_bounds__(kBlock) void k_part_final(wide_t w, int gx, int layer, int64_t cap_next, int insert, int counting,
+                                                     layer_out_t o)
 {
     spot_t p;
     if (!my_spot(w, gx, p)) return;
@@ -1062,11 +965,12 @@ __global__ __launch_bounds__(kBlock) void k_part_final(wide_t w, int gx, int lay
         const unsigned long long rec = v.rec[r];
         const uint32_t q = (uint32_t)(rec >> 32) >> w.bucket_log2;
         const int64_t place = hop_base + v.bk_before[q];
-        col[(uint32_t)rec] = (int32_t)(place + v.lrank[r]);
+        if (!counting) col[(uint32_t)rec] = (int32_t)(place + v.lrank[r]);
         const int64_t i = r - v.bk_start[q];
         if (i < v.bk_cnt[q] && place + i < cap_next) {
             const int32_t u = v.stage[r];
             v.nodes[place + i] = u;
+            if (counting) atomicOr(&v.aux[(uint32_t)u >> 5], 1u << (u & 31));
             if (insert) {
                 const uint32_t h = home_of((uint32_t)u, w.table_log2);
                 if (v.table[h] == 0u) v.table[h] = (uint32_t)(place + i) + 1u;   // may lose to another store: k_settle
@@ -1282,10 +1186,10 @@ void launch_hop_sample(tier_ctx *c, const wide_t &w, int64_t cap_dst, int layer,
     const int gx = clamp_grid(cap_dst, (kBlock / G) * kAtOnce, kLoopBlocks);
     if (MODE != MODE_BLOCKS && w.draws)
         k_hop_sample<G, MODE == MODE_BLOCKS ? MODE_COUNT_SMALL : MODE, true><<<grid_of(gx, w.n_slots), kBlock, 0, c->stream>>>(
-            w, gx, c->indices, layer, k, last ? 1 : 0, mark ? 1 : 0, layer_out_t{});
+            w, gx, c->indices, layer, k, last ? 1 : 0, mark ? 1 : 0, o.layer[layer]);
     else
         k_hop_sample<G, MODE, false><<<grid_of(gx, w.n_slots), kBlock, 0, c->stream>>>(
-            w, gx, c->indices, layer, k, last ? 1 : 0, mark ? 1 : 0, MODE == MODE_BLOCKS ? o.layer[layer] : layer_out_t{});
+            w, gx, c->indices, layer, k, last ? 1 : 0, mark ? 1 : 0, o.layer[layer]);
 }
 
 template <int MODE>
@@ -1319,33 +1223,36 @@ int enqueue_wide_t(tier_ctx *c, const wide_t &w, const int32_t *fanouts, int n_l
     }
     const int seg_gx = clamp_grid(w.n_seg, kBlock, TIER_SCAN_BLOCKS);
     const int flat_gx = clamp_grid(w.n_words, 4 * kBlock, TIER_SCAN_BLOCKS);
-    // block calls on the large-graph layout list every hop's new nodes by buckets (k_part_*), not by the bitmap
-    const bool by_buckets = MODE == MODE_BLOCKS && w.n_buckets > 0;
+    // on the large-graph layout the new nodes of a hop are listed by buckets (k_part_*), not by the bitmap
+    const bool by_buckets = MODE != MODE_COUNT_SMALL && w.n_buckets > 0;
+    const bool counting = MODE != MODE_BLOCKS;
     for (int l = 0; l < n_layers; ++l) {
         const bool last = l == n_layers - 1;
-        launch_hop<MODE>(c, w, cap_nodes[l], l, fanouts[l], last, !by_buckets, o);
+        launch_hop<MODE>(c, w, cap_nodes[l], l, fanouts[l], last, !by_buckets || (counting && last), o);
         if (MODE != MODE_BLOCKS && last) break;               // counted from the bitmaps, never listed
         if (by_buckets) {
+            const int dense_k = counting ? fanouts[l] : 0;
             const int nb = w.n_buckets;
             const size_t bins = (size_t)nb * sizeof(int);
             const int n_words = w.bucket_log2 > 5 ? 1 << (w.bucket_log2 - 5) : 1;
             const unsigned part_grid = grid_of(kPartBlocks, slots);
-            k_part_hist<<<part_grid, kBlock, bins, st>>>(w, l, o.layer[l]);
+            k_part_hist<<<part_grid, kBlock, bins, st>>>(w, l, dense_k, o.layer[l]);
             const int cols_gx = clamp_grid(nb, kBlock, 1 << 16);
             k_part_cols<<<grid_of(cols_gx, slots), kBlock, 0, st>>>(w, cols_gx);
             k_part_scan<<<grid_of(1, slots), kScanThreads, 0, st>>>(w, 0, l, cap_nodes[l + 1]);
-            k_part_scatter<<<part_grid, kBlock, bins, st>>>(w, l, o.layer[l]);
+            k_part_scatter<<<part_grid, kBlock, bins, st>>>(w, l, dense_k, o.layer[l]);
             const int bucket_gx = clamp_grid(nb, kBucketsPerWave, kBucketBlocks);
             k_part_bucket<<<grid_of(bucket_gx, slots), 64, 2 * (size_t)n_words * sizeof(uint32_t), st>>>(w, bucket_gx, n_words);
             k_part_scan<<<grid_of(1, slots), kScanThreads, 0, st>>>(w, 1, l, cap_nodes[l + 1]);
             const int final_gx = clamp_grid(cap_edges[l], kBlock, kLoopBlocks);
-            k_part_final<<<grid_of(final_gx, slots), kBlock, 0, st>>>(w, final_gx, l, cap_nodes[l + 1], last ? 0 : 1, o.layer[l]);
+            k_part_final<<<grid_of(final_gx, slots), kBlock, 0, st>>>(w, final_gx, l, cap_nodes[l + 1], last ? 0 : 1,
+                                                                      counting ? 1 : 0, o.layer[l]);
         } else if (MODE == MODE_COUNT_SMALL) {
             k_bm_partial_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx);
             k_bm_emit_flat<<<grid_of(flat_gx, slots), kBlock, 0, st>>>(w, flat_gx, l, cap_nodes[l + 1]);
         } else {
             k_bm_partial<<<grid_of(seg_gx, slots), kBlock, 0, st>>>(w, seg_gx);
-            k_bm_emit<MODE><<<grid_of(seg_gx, slots), kBlock, 0, st>>>(w, seg_gx, l, last ? 1 : 0, cap_nodes[l + 1]);
+            k_bm_emit<<<grid_of(seg_gx, slots), kBlock, 0, st>>>(w, seg_gx, l, last ? 1 : 0, cap_nodes[l + 1]);
         }
         if (!last) {
             const int gx = clamp_grid(cap_nodes[l + 1], kBlock, kLoopBlocks);
@@ -1595,8 +1502,12 @@ static int presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, i
     if (rc) return rc;
     const bool large = large_graph(ctx);
     int table_log2 = 10;
+    int64_t dense_edges = 0;        // large-graph layout: the hops before the last list their new nodes by buckets
     if (large) {
         rc = ensure_table(ctx, cap_nodes[n_layers - 1], &table_log2);
+        for (int l = 0; l + 1 < n_layers; ++l) dense_edges = cap_edges[l] > dense_edges ? cap_edges[l] : dense_edges;
+        if (rc == TIER_OK && dense_edges > 0)
+            rc = tier_ensure(ctx, (void **)&ctx->ps_col, &ctx->ps_col_cap, (size_t)dense_edges * ctx->n_slots * sizeof(int32_t));
         if (rc) return rc;
     }
 
@@ -1605,6 +1516,11 @@ static int presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, i
     k_clear_totals<<<1, 1, 0, ctx->stream>>>(ctx->meta);
     wide_out o = {};
     o.counts = counts;
+    if (dense_edges > 0)
+        for (int l = 0; l + 1 < n_layers; ++l) {
+            o.layer[l].col = ctx->ps_col;       // fanout entries per dst node: ~node where a new node was drawn
+            o.layer[l].edge_stride = dense_edges;
+        }
     const int64_t all_batches = (n_train + batch_size - 1) / batch_size;
     const int64_t n_batches = n_run < all_batches - first_batch ? first_batch + n_run : all_batches;   // end of the range
     for (int e = 0; e < epochs; ++e) {
@@ -1615,6 +1531,10 @@ static int presample(tier_ctx *ctx, const int32_t *train_ids, int64_t n_train, i
                                  stride);
             w.count_edges = total_edges != nullptr;
             w.draws = draws ? counts : nullptr;
+            if (dense_edges > 0) {
+                rc = ensure_buckets(ctx, &w, dense_edges, slots);
+                if (rc) return rc;
+            }
             for (int s = 0; s < slots; ++s) {
                 const uint64_t bs = tier_batch_seed(seed, (uint32_t)e, (uint32_t)(b + s));
                 w.key0[s] = (uint32_t)bs;

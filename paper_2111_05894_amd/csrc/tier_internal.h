@@ -69,12 +69,14 @@ struct tier_ctx {
     int n_slots;
     uint32_t *fresh;         // [n_slots][bm_stride]; bits of the nodes first reached at the current hop
     uint32_t *aux;           // [n_slots][bm_stride]; access counting only: the frontier so far
-    uint8_t *flag;           // [n_slots][flag_stride]; != 0: the segment holds a bit of `fresh`
-    int32_t *segbase;        // [n_slots][n_seg]; start position of a segment's new nodes (last hop of a block call)
+    uint8_t *flag;           // [n_slots][flag_stride]; bitmap layout: != 0: the bitmap word holds a bit of `fresh`
+    int32_t *segbase;        // [n_slots][n_seg]; bitmap layout: start position of a word's new nodes (last hop of a block call)
     int64_t n_words;         // ceil(n_nodes / 32)
     int64_t bm_stride;       // bitmap words per slot: n_words rounded up to whole 128-byte lines
-    int seg_log2;            // a segment is 1 << seg_log2 bitmap words: 0 up to 32 M nodes, 5 above
-    int64_t n_seg;           // segments per slot
+    int seg_log2;            // 0: bitmap layout (up to 32 M nodes), a flag and a start position per bitmap word; 5: bucket
+                             // layout (above), where the sampler lists new nodes by sorting and leaves `fresh`, `flag`
+                             // and `segbase` alone (flags and positions are then sized per 32 words)
+    int64_t n_seg;           // flags per slot: n_words >> seg_log2, rounded up
     int64_t flag_stride;     // n_seg rounded up to a multiple of 16
     int64_t *f_beg;          // [n_slots][nodes that draw in the current call]: indptr[node] beside the frontier
     size_t f_beg_cap;        // bytes
@@ -124,6 +126,8 @@ struct tier_ctx {
     int32_t *partial_bm;     // [n_slots][TIER_SCAN_BLOCKS]
     int32_t *ps_nodes;       // frontier buffers used by tier_presample
     int64_t cap_ps_nodes;
+    int32_t *ps_col;         // tier_presample on the large-graph layout: per dst node and draw, ~node of a new node or 0
+    size_t ps_col_cap;       // bytes
     // scratch of the score functions and of the graph reordering, kept between calls
     double *pulled;          // n_nodes sums of one round of tier_score_wrpr
     size_t pulled_cap;       // bytes
