@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for profiler byte counters)")
     ap.add_argument("--cpu-batches", type=int, default=192, help="mini-batches in the CPU baseline's sample")
+    ap.add_argument("--sampler-part", choices=("both", "counts", "blocks"), default="both",
+                    help="with --sampler-only: presampling only, the epoch's blocks only, or both (for kernel profiles by part)")
     ap.add_argument("--sampler-only", action="store_true",
                     help="run only the sampler (presampling epoch, then the measured epoch's blocks, no gathers) and print "
                          "its own JSON line: a clean subject for rocprofv3 runs on the sampling kernels")
@@ -249,17 +251,24 @@ def main():
                 e += sum(sum(blk.n_edges[i]) for i in range(len(g)))
             return e
         pre, smp = [], []
+        edges_e = 0
         for it in range(args.warmup + max(args.steps, 1)):
-            _, t_pre = timed_ms(lambda: tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts))
-            edges_e, t_smp = timed_ms(sample_epoch)
+            t_pre = t_smp = float("inf")
+            if args.sampler_part != "blocks":
+                _, t_pre = timed_ms(lambda: tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts))
+            if args.sampler_part != "counts":
+                edges_e, t_smp = timed_ms(sample_epoch)
             if it >= args.warmup:
                 pre.append(t_pre); smp.append(t_smp)
-        _, rows_p, edges_p = tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts, want_totals=True)
+        rows_p = edges_p = 0
+        if args.sampler_part != "blocks":
+            _, rows_p, edges_p = tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts, want_totals=True)
         print(json.dumps({"workload": wl.name, "mini_batches": n_batches, "mini_batches_per_call": B,
-                          "presample_ms": round(min(pre), 3), "presample_rows": rows_p, "presample_edges": edges_p,
-                          "presample_edges_per_s": round(edges_p / (min(pre) * 1e-3)),
-                          "sample_epoch_ms": round(min(smp), 3), "sample_epoch_edges": edges_e,
-                          "sampled_edges_per_s": round(edges_e / (min(smp) * 1e-3)),
+                          "sampler_part": args.sampler_part,
+                          "presample_ms": round(min(pre), 3) if edges_p else None, "presample_rows": rows_p, "presample_edges": edges_p,
+                          "presample_edges_per_s": round(edges_p / (min(pre) * 1e-3)) if edges_p else None,
+                          "sample_epoch_ms": round(min(smp), 3) if edges_e else None, "sample_epoch_edges": edges_e,
+                          "sampled_edges_per_s": round(edges_e / (min(smp) * 1e-3)) if edges_e else None,
                           "note": "presampling = one epoch in counting mode (up to 64 mini-batches per chain, no blocks); "
                                   "sample_epoch = the measured epoch's blocks, mini_batches_per_call per call; best of steps"}), flush=True)
         ctx.close()
