@@ -32,7 +32,8 @@ constexpr int kBlock = 256;
 constexpr int kRowsInFlight = 4;        // measured best of 2 / 4 / 8 on MI355X
 constexpr int kLinkBlocks = 64;         // blocks of a launch that reads host rows only (best of 32 .. 512, full grid)
 constexpr int kClaimRowBits = 40;       // claim = stamp << 40 | output row of the winning request
-constexpr int kDeferBlock = 64;         // deferred copies are reserved 64 entries at a time
+constexpr int kDeferBlock = 512;        // deferred copies are reserved 512 entries at a time
+constexpr int kUnitsPerGrab = 8;        // a cold worker's wave takes up to 8 units of 64 requests off the counter at a time
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // The id lists one launch serves (blockIdx.y picks one): a mini-batch each.
@@ -63,9 +64,11 @@ __device__ inline int is_cold(int32_t id, const uint32_t *__restrict__ hot_bits,
 
 // The cold workers of a split launch: the first `workers` blocks of grid row 0.  The
 // requests are numbered in units of 64 (list by list); a wave takes the next unit off a
-// counter, which makes the waves finish together whatever the mix of hot and cold in
-// their units, and appends the unit's cold requests (one ballot) to a small queue of its
-// own in LDS.  Whenever the queue holds a full pass - kRowsInFlight rows for each group of
+// counter, or in a large call the next few (atomics on one address run at ~26 M/s for the
+// whole chip: one per unit would cost a 100 M-request call 60 ms; in a small call a wave that
+// is left with several units at the end would keep the others waiting), which makes the waves
+// finish together whatever the mix of hot and cold in their units, and appends each unit's
+// cold requests (one ballot) to a small queue of its own in LDS.  Whenever the queue holds a full pass - kRowsInFlight rows for each group of
 // LPR lanes - the wave copies one, so the bytes it keeps in flight on the host link do not
 // depend on how many of the requests are cold.  Four stages run ahead of that, a unit
 // each: the counter, the ids, the slot lookups and (shared misses) the claims, so the
@@ -99,10 +102,24 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
         int32_t id;       // this lane's request, -1 beyond the list or the call
         int fetch;        // this lane's request is cold (after the claim stage: and is the one that reads the row)
     };
-    // the counter's value arrives in lane 0; it is broadcast only where it is needed, an
-    // iteration later, so that the atomic's latency hides behind the work in between
+    // the counter's value arrives in lane 0; it is broadcast only where it is needed, an iteration
+    // or more later, so that the atomic's latency hides behind the work in between
     auto grab = [&]() -> unsigned long long { return lane64 == 0 ? atomicAdd(next, 1ull) : 0ull; };
     auto bcast = [&](unsigned long long raw) -> int64_t { return (int64_t)__shfl(raw, 0); };
+    int64_t run = bcast(grab());                      // the run of units this wave is in
+    unsigned long long raw = grab();                  // the run after it, on its way
+    // units per run: 1 until every wave has 128 runs to take, then more, up to kUnitsPerGrab
+    const int64_t fit = total / ((int64_t)n_waves * 128);
+    const int per = fit < 1 ? 1 : fit > kUnitsPerGrab ? kUnitsPerGrab : (int)fit;
+    int sub = 0;
+    auto next_unit = [&]() -> int64_t {
+        if (sub == per) {
+            run = bcast(raw);
+            raw = grab();
+            sub = 0;
+        }
+        return run * per + sub++;
+    };
     auto load_ids = [&](unit_t &u) {
         u.row0 = 0;
         u.id = -1;
@@ -127,7 +144,8 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
     int def_used = kDeferBlock;
     int fetched = 0;                                  // rows this lane sent over the link
     auto pad_deferred = [&]() {                       // unused entries of the current block
-        if (def_base >= 0 && def_used + lane64 < kDeferBlock) cold.deferred[2 * (def_base + def_used + lane64)] = -1;
+        if (def_base < 0) return;
+        for (int e = def_used + lane64; e < kDeferBlock; e += 64) cold.deferred[2 * (def_base + e)] = -1;
     };
     auto claim = [&](unit_t &u) {
         if (!DEDUP) return;
@@ -151,15 +169,16 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
         const unsigned long long losers = __ballot(lose);
         if (losers) {
             const int n = __popcll(losers);
-            if (def_used + n > kDeferBlock) {         // wave-uniform: a fresh block of entries
-                pad_deferred();
+            const int64_t old_base = def_base;
+            if (def_used + n > kDeferBlock) {         // wave-uniform: the entries run over into a fresh block
                 unsigned long long base = 0;
                 if (lane64 == 0) base = atomicAdd((unsigned long long *)&meta[META_DEFER_N], (unsigned long long)kDeferBlock);
                 def_base = (int64_t)__shfl(base, 0);
-                def_used = 0;
+                def_used -= kDeferBlock;              // < 0: that many entries still go to the old block
             }
             if (lose) {
-                const int64_t e = def_base + def_used + __popcll(losers & ((1ull << lane64) - 1ull));
+                const int at = def_used + __popcll(losers & ((1ull << lane64) - 1ull));
+                const int64_t e = at < 0 ? old_base + kDeferBlock + at : def_base + at;
                 cold.deferred[2 * e] = u.row0 + lane64;
                 cold.deferred[2 * e + 1] = from;
                 u.fetch = 0;
@@ -200,11 +219,10 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
 
     unsigned head = 0, waiting = 0;                   // wave-uniform state of the queue
     unit_t u0, u1, u2, u3;
-    u0.q = bcast(grab());
-    u1.q = bcast(grab());
-    u2.q = bcast(grab());
-    u3.q = bcast(grab());
-    unsigned long long raw = grab();
+    u0.q = next_unit();
+    u1.q = next_unit();
+    u2.q = next_unit();
+    u3.q = next_unit();
     load_ids(u0);
     load_ids(u1);
     load_ids(u2);
@@ -212,7 +230,6 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
     classify(u1);
     claim(u0);
     while (u0.q < total) {
-        const unsigned long long raw_next = grab();
         load_ids(u3);
         classify(u2);
         claim(u1);
@@ -236,8 +253,7 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
         u0 = u1;
         u1 = u2;
         u2 = u3;
-        u3.q = bcast(raw);
-        raw = raw_next;
+        u3.q = next_unit();
     }
     if (waiting) copy_pass(head, (int)waiting);       // fewer than a pass left
     if (DEDUP) {
@@ -540,9 +556,9 @@ static int gather_call(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int6
     const bool any_cold = n_total > 0 && ctx->n_hot < ctx->n_nodes;     // nothing to split off otherwise
     ctx->last_deduped = dedup_applies(ctx, lists, n_lists, n_total);
     if (ctx->last_deduped) {
-        // deferred entries: at most one block of kDeferBlock per unit of 64 requests, plus one per worker wave
+        // deferred entries: one per request at most, plus the block that each worker wave leaves part empty
         const int64_t workers = ctx->link_blocks > 0 ? ctx->link_blocks : kLinkBlocks;
-        const int64_t entries = n_total + (int64_t)kDeferBlock * (n_lists + workers * (kBlock / 64) + 1);
+        const int64_t entries = n_total + (int64_t)kDeferBlock * (workers * (kBlock / 64) + 1);
         int rc = tier_ensure(ctx, (void **)&ctx->deferred, &ctx->deferred_cap, (size_t)entries * 2 * sizeof(int64_t));
         if (rc != TIER_OK) return rc;
         if (++ctx->claim_stamp >= (1u << (64 - kClaimRowBits))) {     // stamps used up: start over on a clean table
