@@ -59,6 +59,11 @@ def main():
                     help="mini-batches per sampling / gather call (at most what the context takes, up to 64); a larger "
                          "group shares more cold rows per call and holds that many mini-batches' rows in HBM at once.  "
                          "0: 16, or 64 on the miss-dominated cfg5, where the rows held are small next to the cache")
+    ap.add_argument("--sample-group", type=int, default=0,
+                    help="mini-batches per sampling call (a multiple of --group; the blocks of one sampling call are "
+                         "gathered --group at a time).  0: as many as the context takes, up to 64: blocks are small "
+                         "(7 MB per mini-batch on cfg3) and the sampler's many short kernels fill the chip better "
+                         "with more mini-batches side by side")
     ap.add_argument("--no-groups", action="store_true", help="skip the comparison of group sizes 16 / 32 / 64")
     ap.add_argument("--no-budget-sweep", action="store_true",
                     help="skip the placement + epoch at the other HBM budgets of the workload (cfg3: 5 % and 20 %)")
@@ -132,6 +137,8 @@ def main():
         return [list(range(g, min(g + size, n_batches))) for g in range(0, n_batches, size)]
 
     groups = grouping(B)
+    S = args.sample_group if args.sample_group > 0 else 64
+    per_sample = max(1, min(B_max, S) // B)        # gather groups per sampling call
     bseed = [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in range(n_batches)]
     # three sets of block buffers: while up to two groups of mini-batches wait for or run their
     # gather (gather stream, host-link bound) the next group is sampled (main stream, latency bound)
@@ -153,23 +160,27 @@ def main():
         return tier.tier_sample_minibatches(ctx, epoch_ids[lo:hi], bs, [bseed[b] for b in g], wl.fanouts,
                                             into if into is not None else blocks)
 
-    def timed_gather(blk, nb):
-        """One gather launch (all nb mini-batches of a group) bracketed by events on its stream."""
-        rows = sum(blk.n_nodes[i][L] for i in range(nb))
+    def sample_span(span, into=None):
+        """One sampling call for the mini-batches of consecutive groups."""
+        return sample_group([b for g in span for b in g], into)
+
+    def timed_gather(blk, nb, first=0):
+        """One gather launch (nb mini-batches of the blocks, from mini-batch `first` on) bracketed by events on its stream."""
+        rows = sum(blk.n_nodes[first + i][L] for i in range(nb))
         if rows > out_buf[0].shape[0]:             # grows during warm-up only
             torch.cuda.synchronize()
             out_buf[0] = torch.empty((int(rows * 1.1), wl.dim), dtype=dtype, device=dev)
         with torch.cuda.stream(gs):
             a, b_ = ev(), ev()
             a.record()
-            tier.tier_gather_minibatches(ctx, blk, nb, out_buf[0])
+            tier.tier_gather_minibatches(ctx, blk, nb, out_buf[0], first_batch=first)
             b_.record()
         return a, b_, rows
 
-    def epoch(record, begin=None, groups=groups):
-        """The measured epoch: every group of mini-batches sampled (main stream) and gathered (gather
-        stream).  begin: event on the gather stream from which the epoch's wall time counts (the end
-        of the cache fill, which the first sampling calls overlap); default: now."""
+    def epoch(record, begin=None, groups=groups, per=per_sample):
+        """The measured epoch: the mini-batches sampled `per` groups per call (main stream) and gathered
+        a group per call (gather stream).  begin: event on the gather stream from which the epoch's wall
+        time counts (the end of the cache fill, which the first sampling calls overlap); default: now."""
         if begin is None:
             torch.cuda.synchronize()
             with torch.cuda.stream(gs):
@@ -178,20 +189,24 @@ def main():
         s_pairs, g_pairs = [], []
         NB = len(blocks2)
         reads_done = [None] * NB                   # last gather that reads blocks2[i]
-        for gi, g in enumerate(groups):
-            # a group's gather is launched as soon as the group is sampled; the host then sits in the
-            # next (synchronous) sampling call while that gather runs, so the gather stream always has
-            # a launch waiting, and the third buffer keeps the host from waiting for a gather to end
-            if reads_done[gi % NB] is not None:
-                reads_done[gi % NB].synchronize()  # its ids are about to be overwritten
+        for si in range(0, len(groups), per):
+            # the gathers of a sampling call's groups are launched as soon as it returns; the host then
+            # sits in the next (synchronous) sampling call while they run, so the gather stream always
+            # has a launch waiting, and the third buffer keeps the host from waiting for a gather to end
+            span, buf = groups[si:si + per], (si // per) % NB
+            if reads_done[buf] is not None:
+                reads_done[buf].synchronize()      # its ids are about to be overwritten
             s0, s1 = ev(), ev()
-            s0.record(); blk = sample_group(g, blocks2[gi % NB]); s1.record()
+            s0.record(); blk = sample_span(span, blocks2[buf]); s1.record()
             s_pairs.append((s0, s1))
-            a, b_, r = timed_gather(blk, len(g))
-            g_pairs.append((a, b_))
-            rows += r; edges += sum(sum(blk.n_edges[i]) for i in range(len(g)))
-            most = max(most, r)
-            reads_done[gi % NB] = b_
+            first = 0
+            for g in span:
+                a, b_, r = timed_gather(blk, len(g), first)
+                g_pairs.append((a, b_))
+                rows += r; edges += sum(sum(blk.n_edges[first + i]) for i in range(len(g)))
+                most = max(most, r)
+                first += len(g)
+            reads_done[buf] = b_
         torch.cuda.synchronize()
         if record is not None:
             record["epoch_wall_ms"].append(begin.elapsed_time(g_pairs[-1][1]) if g_pairs else 0.0)
@@ -251,9 +266,10 @@ def main():
             return r, a.elapsed_time(b_)
         def sample_epoch():
             e = 0
-            for g in groups:
-                blk = sample_group(g)
-                e += sum(sum(blk.n_edges[i]) for i in range(len(g)))
+            for si in range(0, len(groups), per_sample):
+                span = groups[si:si + per_sample]
+                blk = sample_span(span)
+                e += sum(sum(blk.n_edges[i]) for i in range(sum(len(g) for g in span)))
             return e
         pre, smp = [], []
         edges_e = 0
@@ -268,7 +284,7 @@ def main():
         rows_p = edges_p = 0
         if args.sampler_part != "blocks":
             _, rows_p, edges_p = tier.tier_presample(ctx, train, bs, wl.fanouts, 1, synth.PRESAMPLE_SEED, counts, want_totals=True)
-        print(json.dumps({"workload": wl.name, "mini_batches": n_batches, "mini_batches_per_call": B,
+        print(json.dumps({"workload": wl.name, "mini_batches": n_batches, "mini_batches_per_call": B * per_sample,
                           "sampler_part": args.sampler_part,
                           "presample_ms": round(min(pre), 3) if edges_p else None, "presample_rows": rows_p, "presample_edges": edges_p,
                           "presample_edges_per_s": round(edges_p / (min(pre) * 1e-3)) if edges_p else None,
@@ -344,9 +360,9 @@ def main():
         for size in group_sizes:
             gg = grouping(size)
             grec = {"sample_ms": [], "gather_ms": [], "epoch_wall_ms": []}
-            epoch(None, groups=gg)                 # grows the output buffer
+            epoch(None, groups=gg, per=1)          # grows the output buffer
             for _ in range(2):
-                epoch(grec, groups=gg)
+                epoch(grec, groups=gg, per=1)
             hits, links = epoch_stats(gg)
             cold = grec["rows"] - hits
             alone = []
@@ -366,7 +382,7 @@ def main():
                 "cold_requests_crossing_the_link": round(links / cold, 4) if cold else 1.0,
                 "output_rows_held": grec["most_rows_per_call"], "output_bytes_held": grec["most_rows_per_call"] * R,
                 "gather_launches": grec["gather_launches"]}
-        group_table["note"] = ("same placement, whole epoch sampled and gathered `size` mini-batches per call (best of 2); "
+        group_table["note"] = ("same placement, whole epoch sampled and gathered `size` mini-batches per call each (best of 2); "
                                "a larger call shares more cold rows and holds that many mini-batches' output rows at once; "
                                "sample_alone_ms / sampled_edges_per_s: the epoch's sampling calls with the GPU to themselves")
 
@@ -376,8 +392,8 @@ def main():
     torch.cuda.synchronize()
     a, b_ = ev(), ev()
     a.record()
-    for g in groups:
-        sample_group(g)
+    for si in range(0, len(groups), per_sample):
+        sample_span(groups[si:si + per_sample])
     b_.record(); torch.cuda.synchronize()
     sample_alone_ms = a.elapsed_time(b_)
     rows, edges = rec["rows"], rec["edges"]
@@ -550,7 +566,7 @@ def main():
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"{wl.name}{'' if scale == 1.0 else f' at scale {scale:g}'}: {wl.graph} graph, {n} nodes, {indices.numel()} edges, "
                                f"{wl.dim} x {wl.dtype} features, fanout {list(wl.fanouts)}, batch {bs}, "
-                               f"{n_batches} mini-batches per epoch sampled and gathered {B} per call, HBM budget {budget} B ({rec['n_hot']} rows)"},
+                               f"{n_batches} mini-batches per epoch sampled {B * per_sample} and gathered {B} per call, HBM budget {budget} B ({rec['n_hot']} rows)"},
         "sampled_edges_per_s": round(edges / (sample_alone_ms * 1e-3)) if sample_alone_ms else None,
         "sample_alone_ms": round(sample_alone_ms, 3),
         "gather_GBps": round(gathered_bytes / (gather_ms * 1e-3) / 1e9, 2) if gather_ms else None,
@@ -569,7 +585,8 @@ def main():
         "budget_sweep": budget_sweep,
         "prefetch": prefetch,
         "gather_launch": {"link_blocks": args.link_blocks, "min_rows": SPLIT_MIN_ROWS, "shared_misses": shared_on,
-                          "mini_batches_per_call": B, "output_rows_held": rec["most_rows_per_call"],
+                          "mini_batches_per_call": B, "mini_batches_per_sampling_call": B * per_sample,
+                          "output_rows_held": rec["most_rows_per_call"],
                           "groups": group_table,
                           "note": "split launch: the first link_blocks blocks copy the cold rows (host link), all others the "
                                   "hot rows (HBM); uniform_launch_epoch is the same epoch with every block copying both",

@@ -470,11 +470,13 @@ def tier_sample_minibatches(ctx: Context, seeds: torch.Tensor, batch_size: int, 
 
 
 def tier_gather_minibatches(ctx: Context, blocks: "BlocksBatch", n_batches: int, out: torch.Tensor = None,
-                            want_stats: bool = False):
-    """Rows of the final frontiers of the first n_batches mini-batches of ``blocks`` in one
-    launch, packed back to back.  Returns (out, row_offsets) or (out, row_offsets, hit, miss)."""
+                            want_stats: bool = False, first_batch: int = 0):
+    """Rows of the final frontiers of n_batches mini-batches of ``blocks``, from mini-batch first_batch
+    on, in one launch, packed back to back.  Returns (out, row_offsets) or (out, row_offsets, hit, miss)."""
     L = len(blocks.fanouts)
-    n_rows = [blocks.n_nodes[b][L] for b in range(n_batches)]
+    if first_batch < 0 or n_batches < 1 or first_batch + n_batches > blocks.n_batches:
+        raise ValueError("mini-batches outside the blocks")
+    n_rows = [blocks.n_nodes[first_batch + b][L] for b in range(n_batches)]
     offs = [0] * n_batches
     for b in range(1, n_batches):
         offs[b] = offs[b - 1] + n_rows[b - 1]
@@ -485,8 +487,8 @@ def tier_gather_minibatches(ctx: Context, blocks: "BlocksBatch", n_batches: int,
         raise TypeError("out: contiguous device tensor of sum(n_rows) * row_bytes bytes")
     nr = (C.c_int64 * n_batches)(*n_rows); of = (C.c_int64 * n_batches)(*offs)
     st = _Stats()
-    rc = _load().tier_gather_minibatches(ctx.handle, C.c_void_p(blocks.nodes.data_ptr()), blocks.nodes.shape[1], nr, of,
-                                         n_batches, C.c_void_p(out.data_ptr()), C.byref(st) if want_stats else None)
+    rc = _load().tier_gather_minibatches(ctx.handle, C.c_void_p(blocks.nodes[first_batch].data_ptr()), blocks.nodes.shape[1],
+                                         nr, of, n_batches, C.c_void_p(out.data_ptr()), C.byref(st) if want_stats else None)
     _check(rc, "tier_gather_minibatches")
     if want_stats:
         ctx.last_link_rows = st.link_rows

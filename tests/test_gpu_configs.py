@@ -101,6 +101,21 @@ def run_config(name, check_batches, budget_fraction=None, host_threads=16, fallb
             rows_got = out[:m].view(torch.uint8).cpu().numpy().reshape(m, R)
             assert np.array_equal(rows_got, feat[want["nodes"]])       # = the oracle's gather (pinned to indexing)
             say(f"{name}: batch {b}: {m} rows ({hit} hot), {sum(got.n_edges)} edges match ({time.time() - t0:.0f}s)")
+        # the sampling call as bench.py makes it: 64 mini-batches side by side (fewer if the epoch or
+        # the context has fewer); some of them against the oracle, element by element
+        ns = min(64, n_batches, tier.tier_max_batches(ctx))
+        big = tier.tier_sample_minibatches(ctx, ep[: ns * bs], bs, [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in range(ns)], fan)
+        for b in sorted({0, ns // 2 + 1 if ns > 2 else 0, ns - 1}):
+            want = orc.sample_minibatch(ip, ix, epn[b * bs:(b + 1) * bs], fan, tier.tier_batch_seed(synth.EPOCH_SEED, 0, b), local_idx=li)
+            assert big.n_nodes[b] == want["n_nodes"].tolist() and big.n_edges[b] == want["n_edges"].tolist()
+            assert np.array_equal(big.frontier(b).cpu().numpy(), want["nodes"])
+            for l in range(len(fan)):
+                nd, ne = big.n_nodes[b][l], big.n_edges[b][l]
+                assert np.array_equal(big.row_ptr[l][b][: nd + 1].cpu().numpy(), want["row_ptr"][l])
+                assert np.array_equal(big.eid[l][b][:ne].cpu().numpy(), want["eid"][l])
+                assert np.array_equal(big.col[l][b][:ne].cpu().numpy(), want["col"][l])
+        say(f"{name}: {ns} mini-batches in one sampling call: blocks of 3 of them match ({time.time() - t0:.0f}s)")
+        del big
         # one split launch for several mini-batches, shared misses on: same rows, and the rows
         # read over the host link are exactly the distinct cold ids of the call
         # (cfg5: 16 mini-batches, 28 M rows, which the library serves in four launches, each copying
