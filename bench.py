@@ -142,7 +142,7 @@ def main():
     bseed = [tier.tier_batch_seed(synth.EPOCH_SEED, 0, b) for b in range(n_batches)]
     # three sets of block buffers: while up to two groups of mini-batches wait for or run their
     # gather (gather stream, host-link bound) the next group is sampled (main stream, latency bound)
-    blocks2 = [tier.BlocksBatch(n, bs, wl.fanouts, max(group_sizes), dev) for _ in range(3)]
+    blocks2 = [tier.BlocksBatch(n, bs, wl.fanouts, max(max(group_sizes), B * per_sample), dev) for _ in range(3)]
     blocks = blocks2[0]
     out_buf = [torch.empty((blocks.cap_nodes[-1], wl.dim), dtype=dtype, device=dev)]
     counts = torch.empty(n, dtype=torch.int32, device=dev)
