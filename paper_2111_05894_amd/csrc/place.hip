@@ -321,24 +321,29 @@ static int emit_rank(tier_ctx *ctx, const int32_t *ord, int32_t *rank, int32_t *
     return TIER_OK;
 }
 
-// slot map + HBM cache from an order (rank -> node, in the context's sort scratch).  The map
-// is written on the context's stream, the cache filled on the gather stream behind it; the
-// call does not wait for either.
-static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget_bytes, int32_t *slot_map,
-                            int64_t *n_hot_out)
+static int64_t rows_within(const tier_ctx *ctx, uint64_t budget_bytes)
 {
-    const int64_t n = ctx->n_nodes;
-    hipStream_t st = ctx->stream, gs = ctx->gather_stream;
-    int64_t n_hot = (int64_t)(budget_bytes / (uint64_t)ctx->row_bytes);
-    if (n_hot > n) n_hot = n;
-    if (gs != st) TIER_HIP(ctx, hipStreamSynchronize(gs));   // no gather may still read the old map or cache
+    const int64_t n_hot = (int64_t)(budget_bytes / (uint64_t)ctx->row_bytes);
+    return n_hot > ctx->n_nodes ? ctx->n_nodes : n_hot;
+}
+
+// Before a placement writes the slot map: no gather may still read the old map or cache.
+static int begin_place(tier_ctx *ctx)
+{
+    if (ctx->gather_stream != ctx->stream) TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
     ctx->placed = false;
     ctx->boundary = false;
     ctx->n_hot = 0;
-    if (n > 0) {
-        k_slot_map<<<grid_for(n, 256, 4096), 256, 0, st>>>(order, n, n_hot, ctx->slot);
-        k_hot_bits<<<grid_for((n + 31) / 32, 256, 4096), 256, 0, st>>>(ctx->slot, n, ctx->hot_bits);
-    }
+    return TIER_OK;
+}
+
+// The HBM cache for a slot map that is already on its way on the context's stream: order =
+// rank -> node for the first n_hot ranks (in the context's sort scratch).  The cache is filled
+// on the gather stream behind the map; the call does not wait for either.
+static int finish_place(tier_ctx *ctx, const int32_t *order, int64_t n_hot, int32_t *slot_map, int64_t *n_hot_out)
+{
+    const int64_t n = ctx->n_nodes;
+    hipStream_t st = ctx->stream, gs = ctx->gather_stream;
     TIER_HIP(ctx, hipGetLastError());
 
     // (re)build the HBM cache: cache row r = feature row of the node of rank r
@@ -368,6 +373,20 @@ static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget
     return TIER_OK;
 }
 
+// slot map + HBM cache from a complete order (rank -> node, in the context's sort scratch).
+static int place_from_order(tier_ctx *ctx, const int32_t *order, uint64_t budget_bytes, int32_t *slot_map,
+                            int64_t *n_hot_out)
+{
+    const int64_t n = ctx->n_nodes, n_hot = rows_within(ctx, budget_bytes);
+    int rc = begin_place(ctx);
+    if (rc != TIER_OK) return rc;
+    if (n > 0) {
+        k_slot_map<<<grid_for(n, 256, 4096), 256, 0, ctx->stream>>>(order, n, n_hot, ctx->slot);
+        k_hot_bits<<<grid_for((n + 31) / 32, 256, 4096), 256, 0, ctx->stream>>>(ctx->slot, n, ctx->hot_bits);
+    }
+    return finish_place(ctx, order, n_hot, slot_map, n_hot_out);
+}
+
 extern "C" int tier_rank(tier_ctx *ctx, const uint32_t *counts, int32_t *rank, int32_t *order)
 {
     if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
@@ -386,17 +405,6 @@ extern "C" int tier_rank_scores(tier_ctx *ctx, const double *scores, int32_t *ra
     int rc = sort_by_score(ctx, scores, b, &ord);
     if (rc != TIER_OK) return rc;
     return emit_rank(ctx, ord, rank, order);
-}
-
-extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes, int32_t *slot_map,
-                          int64_t *n_hot_out)
-{
-    if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
-    sort_bufs &b = ctx->sort;
-    int32_t *order = nullptr;
-    int rc = sort_by_count(ctx, counts, b, &order);
-    if (rc != TIER_OK) return rc;
-    return place_from_order(ctx, order, budget_bytes, slot_map, n_hot_out);
 }
 
 extern "C" int tier_place_scores(tier_ctx *ctx, const double *scores, uint64_t budget_bytes, int32_t *slot_map,
@@ -544,10 +552,12 @@ __global__ __launch_bounds__(1024) void k_select_scan(select_t *sel, int n_block
 
 // staged_of[v] = place of v's row in the staging area, or -1; staged_ids[place] = v; staged_bits as
 // k_hot_bits would make them.  Places go by node id: first the nodes above t, then, as long as rows
-// are missing, those on it.  A wave takes 64 consecutive nodes at a time.
+// are missing, those on it.  A wave takes 64 consecutive nodes at a time.  keys_out (may be null):
+// keys_out[place] = ~count, the sort key of the placement.
 __global__ __launch_bounds__(256) void k_select_take(const uint32_t *__restrict__ counts, int64_t n, int64_t share,
                                                       int64_t max_rows, const select_t *sel, int32_t *__restrict__ staged_ids,
-                                                      int32_t *__restrict__ staged_of, uint32_t *__restrict__ staged_bits)
+                                                      int32_t *__restrict__ staged_of, uint32_t *__restrict__ staged_bits,
+                                                      uint32_t *__restrict__ keys_out)
 {
     __shared__ int s_a[4], s_e[4];
     const uint32_t t = sel->prefix;
@@ -583,7 +593,10 @@ __global__ __launch_bounds__(256) void k_select_take(const uint32_t *__restrict_
         }
         if (v < hi) {
             staged_of[v] = (int32_t)place;
-            if (place >= 0) staged_ids[place] = (int32_t)v;
+            if (place >= 0) {
+                staged_ids[place] = (int32_t)v;
+                if (keys_out) keys_out[place] = ~key;
+            }
         }
         const unsigned long long m_in = __ballot(place >= 0);
         const int64_t w0 = v0 + 64 * wave;                           // this wave's first node
@@ -594,6 +607,33 @@ __global__ __launch_bounds__(256) void k_select_take(const uint32_t *__restrict_
         base_a += s_a[0] + s_a[1] + s_a[2] + s_a[3];
         base_e += s_e[0] + s_e[1] + s_e[2] + s_e[3];
     }
+}
+
+// The passes that find t and the per-block places (everything but k_select_take), on the context's stream.
+struct select_shape {
+    int64_t share;     // nodes per block of the last passes
+    int n_blocks;
+};
+
+static int select_threshold(tier_ctx *ctx, const uint32_t *counts, int64_t max_rows, select_shape *shape)
+{
+    const int64_t n = ctx->n_nodes;
+    hipStream_t st = ctx->stream;
+    int rc = tier_ensure(ctx, (void **)&ctx->select, &ctx->select_cap, sizeof(select_t));
+    if (rc != TIER_OK) return rc;
+    select_t *sel = (select_t *)ctx->select;
+    const int grid = grid_for(n, 256, kSelectBlocks);
+    shape->share = ((n + grid - 1) / grid + 255) / 256 * 256;
+    shape->n_blocks = (int)((n + shape->share - 1) / shape->share);      // <= grid
+    k_select_init<<<1, 256, 0, st>>>(sel, (unsigned long long)max_rows);
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        k_select_hist<<<grid, 256, 0, st>>>(counts, n, shift, sel);
+        k_select_digit<<<1, 256, 0, st>>>(sel, shift);
+    }
+    k_select_count<<<shape->n_blocks, 256, 0, st>>>(counts, n, shape->share, sel);
+    k_select_scan<<<1, 1024, 0, st>>>(sel, shape->n_blocks);
+    TIER_HIP(ctx, hipGetLastError());
+    return TIER_OK;
 }
 
 // Fetch ahead of a placement: max_rows rows with the largest counts go to a staging area in HBM on
@@ -615,20 +655,11 @@ extern "C" int tier_prefetch(tier_ctx *ctx, const uint32_t *counts, int64_t max_
         rc = tier_ensure(ctx, (void **)&ctx->staged_bits, &ctx->staged_bits_cap, (size_t)((n + 31) / 32) * sizeof(uint32_t));
     if (rc == TIER_OK)
         rc = tier_ensure(ctx, (void **)&ctx->staging, &ctx->staging_cap, (size_t)max_rows * (size_t)ctx->row_bytes);
-    if (rc == TIER_OK) rc = tier_ensure(ctx, (void **)&ctx->select, &ctx->select_cap, sizeof(select_t));
+    select_shape sh;
+    if (rc == TIER_OK) rc = select_threshold(ctx, counts, max_rows, &sh);
     if (rc != TIER_OK) return rc;
-    select_t *sel = (select_t *)ctx->select;
-    const int grid = grid_for(n, 256, kSelectBlocks);
-    const int64_t share = ((n + grid - 1) / grid + 255) / 256 * 256;     // nodes per block of the last two passes
-    const int n_blocks = (int)((n + share - 1) / share);                 // <= grid
-    k_select_init<<<1, 256, 0, st>>>(sel, (unsigned long long)max_rows);
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        k_select_hist<<<grid, 256, 0, st>>>(counts, n, shift, sel);
-        k_select_digit<<<1, 256, 0, st>>>(sel, shift);
-    }
-    k_select_count<<<n_blocks, 256, 0, st>>>(counts, n, share, sel);
-    k_select_scan<<<1, 1024, 0, st>>>(sel, n_blocks);
-    k_select_take<<<n_blocks, 256, 0, st>>>(counts, n, share, max_rows, sel, ctx->staged_ids, ctx->staged_of, ctx->staged_bits);
+    k_select_take<<<sh.n_blocks, 256, 0, st>>>(counts, n, sh.share, max_rows, (const select_t *)ctx->select, ctx->staged_ids,
+                                               ctx->staged_of, ctx->staged_bits, nullptr);
     TIER_HIP(ctx, hipGetLastError());
     if (gs != st) {
         TIER_HIP(ctx, hipEventRecord(ctx->ev_place, st));
@@ -641,6 +672,58 @@ extern "C" int tier_prefetch(tier_ctx *ctx, const uint32_t *counts, int64_t max_
     if (rc != TIER_OK) return rc;
     ctx->staged_rows = max_rows;
     return TIER_OK;
+}
+
+// Placement by access count (Sec. 3.2, Sec. 4.1).  Only the n_hot first ranks matter, so when they
+// are at most half the nodes the order is not made for all of them: the n_hot nodes are selected as
+// in tier_prefetch (above the n_hot-th largest count, then on it, by ascending id), which also writes
+// slot = -1 for everyone else and the hot bits, and only those n_hot (key ~count, node) pairs are
+// sorted, all four digits, stable from their id order: the same ranks as the full sort gives
+// (111 M nodes, 10 % hot: 2 ms instead of 5.5), and nothing here waits for the set of varying digits.
+extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes, int32_t *slot_map,
+                          int64_t *n_hot_out)
+{
+    if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
+    sort_bufs &b = ctx->sort;
+    const int64_t n = ctx->n_nodes, n_hot = rows_within(ctx, budget_bytes);
+    if (n_hot <= 0 || 2 * n_hot > n) {
+        int32_t *order = nullptr;
+        int rc = sort_by_count(ctx, counts, b, &order);
+        if (rc != TIER_OK) return rc;
+        return place_from_order(ctx, order, budget_bytes, slot_map, n_hot_out);
+    }
+    hipStream_t st = ctx->stream;
+    int64_t share = (n_hot + kMaxShares - 1) / kMaxShares;
+    if (share < 16 * kWave) share = 16 * kWave;
+    share = (share + kWave - 1) / kWave * kWave;
+    const int n_shares = (int)((n_hot + share - 1) / share);
+    const int64_t n_hist = (int64_t)kDigits * n_shares;
+    const int scan_grid = grid_for(n_hist, 4 * kScanBlock, 1024);
+    int rc = release_sort_bufs(ctx);
+    for (int i = 0; i < 2 && rc == TIER_OK; ++i) {
+        rc = tier_ensure(ctx, &b.keys[i], &b.keys_cap[i], (size_t)n_hot * sizeof(uint32_t));
+        if (rc == TIER_OK) rc = tier_ensure(ctx, (void **)&b.vals[i], &b.vals_cap[i], (size_t)n_hot * sizeof(int32_t));
+    }
+    if (rc == TIER_OK) rc = tier_ensure(ctx, (void **)&b.hist, &b.hist_cap, (size_t)n_hist * sizeof(uint32_t));
+    if (rc != TIER_OK) return rc;
+    if (!b.partial) TIER_HIP(ctx, hipMalloc(&b.partial, 1024 * sizeof(uint32_t)));
+    select_shape sh;
+    rc = select_threshold(ctx, counts, n_hot, &sh);
+    if (rc == TIER_OK) rc = begin_place(ctx);
+    if (rc != TIER_OK) return rc;
+    uint32_t *keys[2] = {(uint32_t *)b.keys[0], (uint32_t *)b.keys[1]};
+    k_select_take<<<sh.n_blocks, 256, 0, st>>>(counts, n, sh.share, n_hot, (const select_t *)ctx->select, b.vals[0], ctx->slot,
+                                               ctx->hot_bits, keys[0]);
+    for (int j = 0; j < 4; ++j) {                  // an even number of passes: the order ends up in vals[0]
+        const int src = j % 2, dst = (j + 1) % 2;
+        k_radix_hist<uint32_t><<<n_shares, kWave, 0, st>>>(keys[src], n_hot, share, 8 * j, b.hist, n_shares);
+        k_scan_partial<<<scan_grid, kScanBlock, 0, st>>>(b.hist, n_hist, b.partial);
+        k_scan_apply<<<scan_grid, kScanBlock, 0, st>>>(b.hist, n_hist, b.partial);
+        k_radix_scatter<uint32_t><<<n_shares, kWave, 0, st>>>(keys[src], b.vals[src], n_hot, share, 8 * j, b.hist, n_shares,
+                                                              j == 3 ? nullptr : keys[dst], b.vals[dst]);
+    }
+    k_slot_map<<<grid_for(n_hot, 256, 4096), 256, 0, st>>>(b.vals[0], n_hot, n_hot, ctx->slot);     // ranks of the chosen
+    return finish_place(ctx, b.vals[0], n_hot, slot_map, n_hot_out);
 }
 
 // Placement for a graph and table already ordered by rank (Sec. 3.2 second method,

@@ -325,7 +325,7 @@ def test_draw_counts_on_a_hub():
 # placement and gather
 # ------------------------------------------------------------------------------
 @pytest.mark.parametrize("n,max_count", [(1, 3), (64, 0), (1000, 1), (4097, 200), (100_003, 300), (250_000, 70_000),
-                                         (70_001, 2**24 + 5)])
+                                         (70_001, 2**24 + 5), (5000, 2**32 - 1)])
 def test_slot_map_matches_oracle(n, max_count):
     say("place", n, max_count)
     rng = np.random.default_rng(n)
@@ -335,13 +335,16 @@ def test_slot_map_matches_oracle(n, max_count):
     ip = torch.zeros(n + 1, dtype=torch.int64); ix = torch.zeros(0, dtype=torch.int32)
     w = World(ip, ix, dim=4)
     try:
-        cd = torch.from_numpy(counts.view(np.int32)).to(DEV)
-        for rows in (0, 1, n // 3, n, n + 10):
-            budget = rows * w.row_bytes + 7
-            slot, n_hot = tier.tier_place(w.ctx, cd, budget)
-            rank, want, want_hot = orc.place(counts, w.row_bytes, budget)
-            assert n_hot == want_hot == min(rows, n)
-            assert np.array_equal(slot.cpu().numpy(), want)
+        sparse = counts * (rng.random(n) < 0.15).astype(np.uint32)          # fewer nodes with a count than rows asked for
+        for cnt in (counts, sparse):
+            cd = torch.from_numpy(cnt.view(np.int32)).to(DEV)
+            # up to half the nodes the library selects the rows and sorts only those; beyond, it sorts all nodes
+            for rows in (0, 1, 2, n // 3, n // 2, n // 2 + 1, n, n + 10):
+                budget = rows * w.row_bytes + 7
+                slot, n_hot = tier.tier_place(w.ctx, cd, budget)
+                rank, want, want_hot = orc.place(cnt, w.row_bytes, budget)
+                assert n_hot == want_hot == min(rows, n)
+                assert np.array_equal(slot.cpu().numpy(), want), (n, max_count, rows)
     finally:
         w.close()
 
