@@ -674,19 +674,22 @@ extern "C" int tier_prefetch(tier_ctx *ctx, const uint32_t *counts, int64_t max_
     return TIER_OK;
 }
 
-// Placement by access count (Sec. 3.2, Sec. 4.1).  Only the n_hot first ranks matter, so when they
-// are at most half the nodes the order is not made for all of them: the n_hot nodes are selected as
-// in tier_prefetch (above the n_hot-th largest count, then on it, by ascending id), which also writes
-// slot = -1 for everyone else and the hot bits, and only those n_hot (key ~count, node) pairs are
-// sorted, all four digits, stable from their id order: the same ranks as the full sort gives
-// (111 M nodes, 10 % hot: 2 ms instead of 5.5), and nothing here waits for the set of varying digits.
+// Placement by access count (Sec. 3.2, Sec. 4.1).  Only the n_hot first ranks matter, so on a large
+// graph, when they are at most half the nodes, the order is not made for all of them: the n_hot nodes
+// are selected as in tier_prefetch (above the n_hot-th largest count, then on it, by ascending id),
+// which also writes slot = -1 for everyone else and the hot bits, and only those n_hot (key ~count,
+// node) pairs are sorted, all four digits, stable from their id order: the same ranks as the full
+// sort gives (111 M nodes, 10 % hot: 3 ms instead of 5.5), and nothing here waits for the set of
+// varying digits.  It takes ~30 launches where the full sort of small counts takes ~10: below
+// 16 M nodes the full sort is faster (2.4 M nodes: 0.2 ms against 0.65).
+constexpr int64_t kSelectMinNodes = 1 << 24;
 extern "C" int tier_place(tier_ctx *ctx, const uint32_t *counts, uint64_t budget_bytes, int32_t *slot_map,
                           int64_t *n_hot_out)
 {
     if (!ctx || (!counts && ctx->n_nodes > 0)) return TIER_EINVAL;
     sort_bufs &b = ctx->sort;
     const int64_t n = ctx->n_nodes, n_hot = rows_within(ctx, budget_bytes);
-    if (n_hot <= 0 || 2 * n_hot > n) {
+    if (n < kSelectMinNodes || n_hot <= 0 || 2 * n_hot > n) {
         int32_t *order = nullptr;
         int rc = sort_by_count(ctx, counts, b, &order);
         if (rc != TIER_OK) return rc;

@@ -349,6 +349,39 @@ def test_slot_map_matches_oracle(n, max_count):
         w.close()
 
 
+def test_slot_map_of_a_large_graph():
+    """From 2^24 nodes on, a placement of at most half the nodes selects its rows and sorts only those:
+    same slot map as the oracle's full order, with ties at the cut, with fewer counted nodes than rows,
+    and on the other side of the half (where all nodes are sorted)."""
+    n = (1 << 24) + 12_345
+    say("place large", n)
+    rng = np.random.default_rng(24)
+    dense = (rng.integers(0, 301, n) * (rng.random(n) < 0.6)).astype(np.uint32)
+    dense[rng.integers(0, n)] = 70_000
+    sparse = dense * (rng.random(n) < 0.2).astype(np.uint32)
+    ip = torch.zeros(n + 1, dtype=torch.int64); ix = torch.zeros(0, dtype=torch.int32)
+    w = World(ip, ix, dim=4)
+    try:
+        for cnt, rows_list in ((dense, (n // 10, n // 2, n // 2 + 1)), (sparse, (1, n // 3))):
+            cd = torch.from_numpy(cnt.view(np.int32)).to(DEV)
+            for rows in rows_list:
+                budget = rows * w.row_bytes + 5
+                slot, n_hot = tier.tier_place(w.ctx, cd, budget)
+                _, want, want_hot = orc.place(cnt, w.row_bytes, budget)
+                assert n_hot == want_hot == rows
+                assert np.array_equal(slot.cpu().numpy(), want), rows
+                ids = torch.from_numpy(rng.integers(0, n, 300_000).astype(np.int32)).to(DEV)
+                tier.tier_set_gather_split(w.ctx, 16, 0)             # the cold workers go by the hot bits
+                out, hit, miss = tier.tier_gather_features(w.ctx, ids, want_stats=True)
+                tier.tier_set_gather_split(w.ctx, 0, 0)
+                idn = ids.cpu().numpy()
+                assert hit == int((want[idn] >= 0).sum()) and hit + miss == len(idn)
+                assert np.array_equal(out.view(torch.uint8).cpu().numpy().reshape(len(idn), -1), w.feat_bytes[idn])
+                say("place large", rows, "rows,", hit, "hits of", len(idn))
+    finally:
+        w.close()
+
+
 def test_rank_example_from_paper():
     ip = torch.zeros(5, dtype=torch.int64); ix = torch.zeros(0, dtype=torch.int32)
     w = World(ip, ix, dim=4)
