@@ -366,6 +366,8 @@ def test_slot_map_of_a_large_graph():
             cd = torch.from_numpy(cnt.view(np.int32)).to(DEV)
             for rows in rows_list:
                 budget = rows * w.row_bytes + 5
+                if rows == n // 10:                                  # some rows fetched ahead, by other counts
+                    tier.tier_prefetch(w.ctx, torch.from_numpy(sparse.view(np.int32)).to(DEV), n // 20)
                 slot, n_hot = tier.tier_place(w.ctx, cd, budget)
                 _, want, want_hot = orc.place(cnt, w.row_bytes, budget)
                 assert n_hot == want_hot == rows
