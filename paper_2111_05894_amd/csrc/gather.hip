@@ -553,6 +553,7 @@ static int gather_call(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int6
 {
     const int mode = ctx->boundary ? GATHER_BOUNDARY : GATHER_SLOT;
     hipStream_t st = ctx->gather_stream;
+    ctx->maps_in_use = true;
     const bool any_cold = n_total > 0 && ctx->n_hot < ctx->n_nodes;     // nothing to split off otherwise
     ctx->last_deduped = dedup_applies(ctx, lists, n_lists, n_total);
     if (ctx->last_deduped) {

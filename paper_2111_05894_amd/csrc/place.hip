@@ -327,10 +327,12 @@ static int64_t rows_within(const tier_ctx *ctx, uint64_t budget_bytes)
     return n_hot > ctx->n_nodes ? ctx->n_nodes : n_hot;
 }
 
-// Before a placement writes the slot map: no gather may still read the old map or cache.
+// Before a placement writes the slot map: no gather may still read the old map or cache.  (A copy
+// of rows fetched ahead that is still running reads neither: the placement queues up behind it.)
 static int begin_place(tier_ctx *ctx)
 {
-    if (ctx->gather_stream != ctx->stream) TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+    if (ctx->gather_stream != ctx->stream && ctx->maps_in_use) TIER_HIP(ctx, hipStreamSynchronize(ctx->gather_stream));
+    ctx->maps_in_use = false;
     ctx->placed = false;
     ctx->boundary = false;
     ctx->n_hot = 0;
@@ -646,6 +648,7 @@ extern "C" int tier_prefetch(tier_ctx *ctx, const uint32_t *counts, int64_t max_
     if (max_rows > n) max_rows = n;
     // an earlier fill may still read the staging area and its maps
     if (gs != st) TIER_HIP(ctx, hipStreamSynchronize(gs));
+    ctx->maps_in_use = false;
     ctx->fill_pending = false;
     ctx->staged_rows = 0;
     if (max_rows == 0) return TIER_OK;

@@ -46,6 +46,8 @@ struct tier_ctx {
     int64_t *gmeta_host;         // pinned mirror
     // shared misses (tier_set_gather_dedup): state of the gather stream
     bool dedup;
+    bool maps_in_use;            // a gather enqueued since the library last waited for the gather stream may still read
+                                 //   the slot map, the hot bits or the cache
     bool last_deduped;           // the last gather call ran with claims (its link rows are in META_LINK_ROWS)
     unsigned long long *claim;   // n_nodes; stamp << 40 | output row of the request that fetches the id in that call
     uint32_t claim_stamp;        // stamp of the last call that claimed (24 bits, then the table is cleared)
