@@ -184,8 +184,9 @@ uint64_t tier_batch_seed(uint64_t seed, uint32_t epoch, uint32_t batch);
  * copied into an HBM cache owned by the context (cache row = rank) and the
  * node->slot map becomes slot[v] = rank[v] if rank[v] < n_hot, else -1.  Replaces
  * any earlier placement.  counts: (device) n_nodes entries.  slot_map (device,
- * optional): receives a copy of the map.  n_hot (host, optional).  Waits once inside
- * the sort (and first for gathers still running on the gather stream), then returns with
+ * optional): receives a copy of the map.  n_hot (host, optional).  Waits for gathers
+ * still running on the gather stream and, on graphs below 2^24 nodes or with more than
+ * half the nodes hot (where all nodes are sorted), once inside the sort; then returns with
  * the map enqueued on the context's stream and the cache fill enqueued on the gather
  * stream (tier_set_gather_stream), ahead of every later gather: the caller may go on
  * sampling while the hot rows cross the host link.  The host table must not change
