@@ -455,18 +455,29 @@ __global__ __launch_bounds__(256) void k_select_hist(const uint32_t *__restrict_
     __syncthreads();
     const uint32_t prefix = sel->prefix;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
-        const uint32_t key = counts[v];
-        const bool in = shift == 24 || (key >> (shift + 8)) == (prefix >> (shift + 8));
-        const uint32_t digit = (key >> shift) & 255u;
-        // counts are small numbers: most lanes of a wave hold the same digit, so one lane adds for all of them
-        unsigned long long todo = __ballot(in);
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const uint32_t d = (uint32_t)__shfl((int)digit, leader);
-            const unsigned long long same = __ballot(in && digit == d);
-            if ((threadIdx.x & 63) == leader) atomicAdd(&s_h[d], (uint32_t)__popcll(same));
-            todo &= ~same;
+    constexpr int kAhead = 4;                        // loads in flight per lane
+    // (the whole wave takes every step: the first index is the same for all its lanes' steps)
+    for (int64_t v0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v0 - threadIdx.x < n; v0 += kAhead * stride) {
+        uint32_t keys[kAhead];
+#pragma unroll
+        for (int j = 0; j < kAhead; ++j) {
+            const int64_t v = v0 + j * stride;
+            keys[j] = v < n ? counts[v] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < kAhead; ++j) {
+            const uint32_t key = keys[j];
+            const bool in = v0 + j * stride < n && (shift == 24 || (key >> (shift + 8)) == (prefix >> (shift + 8)));
+            const uint32_t digit = (key >> shift) & 255u;
+            // counts are small numbers: most lanes of a wave hold the same digit, so one lane adds for all of them
+            unsigned long long todo = __ballot(in);
+            while (todo) {
+                const int leader = __ffsll((long long)todo) - 1;
+                const uint32_t d = (uint32_t)__shfl((int)digit, leader);
+                const unsigned long long same = __ballot(in && digit == d);
+                if ((threadIdx.x & 63) == leader) atomicAdd(&s_h[d], (uint32_t)__popcll(same));
+                todo &= ~same;
+            }
         }
     }
     __syncthreads();
