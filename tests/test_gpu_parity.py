@@ -258,6 +258,68 @@ def test_last_hop_crowded_and_sparse_id_ranges(seg_words):
         w.close()
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_random_worlds_match_oracle(case):
+    """Seeded random worlds: graph size and density, isolated nodes, hubs, depth, fanouts, batch
+    size, number of mini-batches side by side and the scratch layout all drawn at random; blocks
+    of every mini-batch, both kinds of access counts, the placement and the gathered rows must be
+    the oracle's."""
+    rng = np.random.default_rng(1000 + case)
+    n = int(rng.integers(50, 20_000))
+    m = int(n * rng.uniform(0.5, 30))
+    dst = rng.integers(0, n, m); src = rng.integers(0, n, m)
+    if case % 2:                                                     # a few hubs, as sources and as destinations
+        hubs = rng.integers(0, n, 3)
+        src[rng.random(m) < 0.2] = rng.choice(hubs); dst[rng.random(m) < 0.05] = rng.choice(hubs)
+    order = np.lexsort((rng.random(m), dst)); dst, src = dst[order], src[order]
+    indptr = np.zeros(n + 1, np.int64); np.add.at(indptr, dst + 1, 1); indptr = np.cumsum(indptr)
+    L = int(rng.integers(1, 5))
+    fanouts = tuple(int(k) for k in rng.integers(1, 12, L))
+    bs = int(rng.integers(1, 300))
+    seg_words = [None, 32][int(rng.integers(0, 2))]
+    say("random world", case, "n", n, "m", m, "fanouts", fanouts, "batch", bs, "layout", seg_words)
+    w = World(torch.from_numpy(indptr), torch.from_numpy(src.astype(np.int32)), dim=int(rng.choice([4, 12, 100])),
+              seg_words=seg_words)
+    try:
+        train = rng.choice(n, int(rng.integers(1, max(2, n // 2))), replace=False).astype(np.int32)
+        train_d = torch.from_numpy(train).to(DEV)
+        seed = int(rng.integers(1, 2**40))
+        wantc, wrows, wedges = orc.presample(w.indptr, w.indices, train, bs, fanouts, 1, seed, threads=2)
+        gotc, rows, edges = tier.tier_presample(w.ctx, train_d, bs, fanouts, 1, seed, want_totals=True)
+        assert np.array_equal(gotc.cpu().numpy().view(np.uint32), wantc) and (rows, edges) == (wrows, wedges)
+        wantd, wdraws = orc.presample_draws(w.indptr, w.indices, train, bs, fanouts, 1, seed, threads=2)
+        gotd, draws = tier.tier_presample_draws(w.ctx, train_d, bs, fanouts, 1, seed, want_total=True)
+        assert np.array_equal(gotd.cpu().numpy().view(np.uint32), wantd) and draws == wdraws
+        budget = int(rng.integers(0, n + 1)) * w.row_bytes
+        slot, n_hot = tier.tier_place(w.ctx, gotc, budget)
+        _, oslot, ohot = orc.place(wantc, w.row_bytes, budget)
+        assert n_hot == ohot and np.array_equal(slot.cpu().numpy(), oslot)
+        cache = orc.fill_cache(w.feat_bytes, oslot, ohot)
+        B = int(min(tier.tier_max_batches(w.ctx), rng.integers(1, 20), -(-len(train) // bs)))
+        bseeds = [tier.tier_batch_seed(seed, 1, b) for b in range(B)]
+        got = tier.tier_sample_minibatches(w.ctx, train_d[: B * bs], bs, bseeds, fanouts)
+        tier.tier_set_gather_split(w.ctx, int(rng.choice([0, 2, 64])), 0)
+        tier.tier_set_gather_dedup(w.ctx, bool(rng.integers(0, 2)))
+        rows_d, offs, hit, miss = tier.tier_gather_minibatches(w.ctx, got, B, want_stats=True)
+        whit = wmiss = 0
+        for b in range(B):
+            want = orc.sample_minibatch(w.indptr, w.indices, train[b * bs:(b + 1) * bs], fanouts, bseeds[b], local_idx=w.local_idx)
+            assert got.n_nodes[b] == want["n_nodes"].tolist() and got.n_edges[b] == want["n_edges"].tolist(), b
+            assert np.array_equal(got.frontier(b).cpu().numpy(), want["nodes"])
+            for l in range(L):
+                nd, ne = got.n_nodes[b][l], got.n_edges[b][l]
+                assert np.array_equal(got.row_ptr[l][b][: nd + 1].cpu().numpy(), want["row_ptr"][l]), (b, l)
+                assert np.array_equal(got.col[l][b][:ne].cpu().numpy(), want["col"][l]), (b, l)
+                assert np.array_equal(got.eid[l][b][:ne].cpu().numpy(), want["eid"][l]), (b, l)
+            wout, h, mi = orc.gather(w.feat_bytes, cache, oslot, want["nodes"])
+            whit += h; wmiss += mi
+            m_b = len(want["nodes"])
+            assert np.array_equal(rows_d[offs[b]: offs[b] + m_b].view(torch.uint8).cpu().numpy().reshape(m_b, -1), wout), b
+        assert (hit, miss) == (whit, wmiss)
+    finally:
+        w.close()
+
+
 # ------------------------------------------------------------------------------
 # access counts
 # ------------------------------------------------------------------------------
