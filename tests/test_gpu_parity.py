@@ -316,6 +316,17 @@ def test_random_worlds_match_oracle(case):
             m_b = len(want["nodes"])
             assert np.array_equal(rows_d[offs[b]: offs[b] + m_b].view(torch.uint8).cpu().numpy().reshape(m_b, -1), wout), b
         assert (hit, miss) == (whit, wmiss)
+        # the next rows on the same world: scores, ranking, Alg. 2 on lists that are neither sorted nor free of repeats
+        assert np.array_equal(tier.tier_score_degree(w.ctx).cpu().numpy().view(np.uint32), orc.score_degree(w.indptr, w.indices))
+        gots = tier.tier_score_wrpr(w.ctx, train_d, 3, 0.85).cpu().numpy()
+        wants = orc.score_wrpr(w.indptr, w.indices, train, 3, 0.85)
+        assert np.allclose(gots, wants, rtol=1e-12, atol=0)
+        rank, order = tier.tier_rank(w.ctx, gotc)
+        orank, _, _ = orc.place(wantc, w.row_bytes, 0)
+        assert np.array_equal(rank.cpu().numpy(), orank)
+        ip2, ix2 = tier.tier_reorder_graph(w.ctx, rank, order)
+        ond, oedg = orc.reorder_graph(w.indptr, w.indices, orank)
+        assert np.array_equal(ip2.cpu().numpy().astype(np.int64), ond) and np.array_equal(ix2.cpu().numpy(), oedg)
     finally:
         w.close()
 
