@@ -32,7 +32,7 @@ constexpr int kBlock = 256;
 constexpr int kRowsInFlight = 4;        // measured best of 2 / 4 / 8 on MI355X
 constexpr int kLinkBlocks = 64;         // blocks of a launch that reads host rows only (best of 32 .. 512, full grid)
 constexpr int kClaimRowBits = 40;       // claim = stamp << 40 | output row of the winning request
-constexpr int kDeferBlock = 512;        // deferred copies are reserved 512 entries at a time
+constexpr int kDeferBlock = 512;        // deferred copies are reserved up to 512 entries at a time
 constexpr int kUnitsPerGrab = 8;        // a cold worker's wave takes up to 8 units of 64 requests off the counter at a time
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -141,11 +141,14 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
     // shared misses: the first request of an id in this call fetches the row, the others
     // get a deferred copy from that request's output row
     int64_t def_base = -1;                            // wave-uniform: current block of deferred entries
-    int def_used = kDeferBlock;
+    // entries are reserved in blocks: large ones in a large call (fewer atomics on the one counter), small ones
+    // otherwise (what a wave leaves unused of its last block, the copy kernel still has to look through)
+    const int defer_block = per > 1 ? kDeferBlock : 64;
+    int def_used = defer_block;
     int fetched = 0;                                  // rows this lane sent over the link
     auto pad_deferred = [&]() {                       // unused entries of the current block
         if (def_base < 0) return;
-        for (int e = def_used + lane64; e < kDeferBlock; e += 64) cold.deferred[2 * (def_base + e)] = -1;
+        for (int e = def_used + lane64; e < defer_block; e += 64) cold.deferred[2 * (def_base + e)] = -1;
     };
     auto claim = [&](unit_t &u) {
         if (!DEDUP) return;
@@ -170,15 +173,15 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
         if (losers) {
             const int n = __popcll(losers);
             const int64_t old_base = def_base;
-            if (def_used + n > kDeferBlock) {         // wave-uniform: the entries run over into a fresh block
+            if (def_used + n > defer_block) {         // wave-uniform: the entries run over into a fresh block
                 unsigned long long base = 0;
-                if (lane64 == 0) base = atomicAdd((unsigned long long *)&meta[META_DEFER_N], (unsigned long long)kDeferBlock);
+                if (lane64 == 0) base = atomicAdd((unsigned long long *)&meta[META_DEFER_N], (unsigned long long)defer_block);
                 def_base = (int64_t)__shfl(base, 0);
-                def_used -= kDeferBlock;              // < 0: that many entries still go to the old block
+                def_used -= defer_block;              // < 0: that many entries still go to the old block
             }
             if (lose) {
                 const int at = def_used + __popcll(losers & ((1ull << lane64) - 1ull));
-                const int64_t e = at < 0 ? old_base + kDeferBlock + at : def_base + at;
+                const int64_t e = at < 0 ? old_base + defer_block + at : def_base + at;
                 cold.deferred[2 * e] = u.row0 + lane64;
                 cold.deferred[2 * e + 1] = from;
                 u.fetch = 0;
