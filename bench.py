@@ -53,8 +53,9 @@ def main():
     ap.add_argument("--link-blocks", type=int, default=-1,
                     help="blocks of the cold-row launch of the split gather (0: one uniform launch per call; default: 48, "
                          "which leaves the sampling calls beside the gathers a third more room than 64 at the same gather "
-                         "time, and 128 on cfg5: nine of ten cold requests there are repeats within the call, and it takes "
-                         "that many blocks to look through them as fast as the link delivers the others)")
+                         "time, and 192 on cfg5: nine of ten cold requests there are repeats within the call, and it takes "
+                         "that many blocks to look through them, and to write every fetched row to all its requests, "
+                         "as fast as the link delivers)")
     ap.add_argument("--group", type=int, default=0,
                     help="mini-batches per sampling / gather call (at most what the context takes, up to 64); a larger "
                          "group shares more cold rows per call and holds that many mini-batches' rows in HBM at once.  "
@@ -86,7 +87,7 @@ def main():
                          "its own JSON line: a clean subject for rocprofv3 runs on the sampling kernels")
     args = ap.parse_args()
     if args.link_blocks < 0:
-        args.link_blocks = 128 if args.workload == "cfg5" else 48
+        args.link_blocks = 192 if args.workload == "cfg5" else 48
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)

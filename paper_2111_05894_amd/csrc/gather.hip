@@ -24,6 +24,14 @@
 // short second kernel copies those rows inside HBM (k_copy_deferred).  A claim is the
 // call's stamp and the winner's output row in one 64-bit word, so the table needs no
 // clearing between calls.
+//
+// Shared misses with most requests repeating an id (a call that asks for at least twice as
+// many rows as the graph has nodes): the copies afterwards would move most of the call's
+// bytes through HBM a second time, behind the host link's back.  Instead a first kernel
+// (k_link) threads the cold requests of every id into a list (claim = the last request to
+// arrive, every request remembers the one before it and its own output row), and the cold
+// workers fetch a row where they meet the head of its list and write it to every request on
+// the list straight from their registers: no second kernel, no row read back from HBM.
 #include "tier_internal.h"
 
 namespace {
@@ -33,6 +41,7 @@ constexpr int kRowsInFlight = 4;        // measured best of 2 / 4 / 8 on MI355X
 constexpr int kLinkBlocks = 64;         // blocks of a launch that reads host rows only (best of 32 .. 512, full grid)
 constexpr int kClaimRowBits = 40;       // claim = stamp << 40 | output row of the winning request
 constexpr int kDeferBlock = 512;        // deferred copies are reserved up to 512 entries at a time
+constexpr int kFanPieces = 4;           // lists of requests: a lane holds up to 4 pieces of 16 bytes of each row in flight
 constexpr int kUnitsPerGrab = 8;        // a cold worker's wave takes up to 8 units of 64 requests off the counter at a time
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -41,6 +50,7 @@ struct id_lists_t {
     const int32_t *ids[TIER_MAX_BATCHES];
     int64_t n[TIER_MAX_BATCHES];
     int64_t out_row[TIER_MAX_BATCHES];   // first output row of the list
+    int64_t first_req[TIER_MAX_BATCHES]; // requests of the lists before it (number of a request = this + its place in the list)
 };
 
 // What the cold workers of a split launch need beyond the lists.
@@ -49,6 +59,7 @@ struct cold_t {
     unsigned long long stamp;            // shared misses: this call's stamp, already shifted; 0 = off
     unsigned long long *claim;           // [n_nodes]
     int64_t *deferred;                   // pairs (output row, output row to copy from); first < 0: unused
+                                         // (lists of requests: pairs (request before this one or -1, output row), by request)
 };
 
 // An id outside the graph is nobody's cold row: the blocks that copy hot rows write its row of zeros.
@@ -74,7 +85,8 @@ __device__ inline int is_cold(int32_t id, const uint32_t *__restrict__ hot_bits,
 // each: the counter, the ids, the slot lookups and (shared misses) the claims, so the
 // copies never wait for any of them.  The last wave to run dry leaves both counters at
 // zero for the next launch on the stream.
-template <int LPR, int MODE, bool DEDUP>
+// SHARE: 0 every cold request reads its row; 1 claims and deferred copies; 2 lists of requests.
+template <int LPR, int MODE, int SHARE>
 __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, const uint32_t *__restrict__ hot_bits,
                                       int64_t n_nodes, int64_t n_hot, const cold_t &cold,
                                       const uint4 *__restrict__ host, uint4 *__restrict__ out_base, int cpr,
@@ -98,7 +110,7 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
 
     struct unit_t {
         int64_t q;        // number of the unit (wave-uniform)
-        int64_t row0;     // output row of its first request (wave-uniform)
+        int64_t row0;     // output row of its first request (wave-uniform); SHARE == 2: number of its first request
         int32_t id;       // this lane's request, -1 beyond the list or the call
         int fetch;        // this lane's request is cold (after the claim stage: and is the one that reads the row)
     };
@@ -132,7 +144,7 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
             if (c < nu) break;
             c -= nu;
         }
-        u.row0 = lists.out_row[b] + c * 64;
+        u.row0 = (SHARE == 2 ? lists.first_req[b] : lists.out_row[b]) + c * 64;
         const int64_t i = c * 64 + lane64;
         if (i < lists.n[b]) u.id = lists.ids[b][i];
     };
@@ -151,7 +163,14 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
         for (int e = def_used + lane64; e < defer_block; e += 64) cold.deferred[2 * (def_base + e)] = -1;
     };
     auto claim = [&](unit_t &u) {
-        if (!DEDUP) return;
+        if (SHARE == 0) return;
+        if (SHARE == 2) {                             // the head of an id's list fetches for the whole list
+            if (u.fetch) {
+                const unsigned long long cur = cold.claim[u.id];
+                u.fetch = (int64_t)(cur & ((1ull << kClaimRowBits) - 1ull)) == u.row0 + lane64;
+            }
+            return;
+        }
         int lose = 0;
         int64_t from = 0;
         if (u.fetch) {
@@ -190,7 +209,69 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
         }
     };
     // copy the n (<= kPerPass) requests at the head of the queue
+    // lists of requests: the n (<= kPerPass) rows at the head of the queue, each read once from the host
+    // and written to every request on its id's list (q_dst holds the number of the list's head).  A
+    // list ends at -1 and every entry points to a request that arrived before it: the walk ends.
+    auto fan_out_pass = [&](unsigned head, int n) {
+        const uint4 *src[kRowsInFlight];
+        int64_t at[kRowsInFlight];
+        uint4 v[kRowsInFlight][kFanPieces];
+#pragma unroll
+        for (int j = 0; j < kRowsInFlight; ++j) {
+            const int k = g * kRowsInFlight + j;
+            src[j] = nullptr;
+            at[j] = -1;
+            if (k < n) {
+                const unsigned e = (head + (unsigned)k) % kQueue;
+                src[j] = host + (int64_t)q_src[e] * cpr;
+                at[j] = q_dst[e];
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < kFanPieces; ++p) {
+            const int cc = lane + p * LPR;
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j) {
+                v[j][p] = make_uint4(0, 0, 0, 0);
+                if (src[j] && cc < cpr) v[j][p] = src[j][cc];
+            }
+        }
+        bool more = true;
+        while (more) {                                // the lanes of a group walk together
+            more = false;
+            int64_t next[kRowsInFlight], row[kRowsInFlight];
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j) {
+                next[j] = -1;
+                row[j] = -1;
+                if (at[j] >= 0) {
+                    next[j] = cold.deferred[2 * at[j]];
+                    row[j] = cold.deferred[2 * at[j] + 1];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j) {
+                if (row[j] >= 0) {
+                    uint4 *dst = out_base + row[j] * cpr;
+#pragma unroll
+                    for (int p = 0; p < kFanPieces; ++p) {
+                        const int cc = lane + p * LPR;
+                        if (cc < cpr) {
+                            u32x4 t4 = {v[j][p].x, v[j][p].y, v[j][p].z, v[j][p].w};
+                            __builtin_nontemporal_store(t4, (u32x4 *)&dst[cc]);
+                        }
+                    }
+                }
+                at[j] = next[j];
+                more = more || next[j] >= 0;
+            }
+        }
+    };
     auto copy_pass = [&](unsigned head, int n) {
+        if (SHARE == 2) {
+            fan_out_pass(head, n);
+            return;
+        }
         const uint4 *src[kRowsInFlight];
         uint4 *dst[kRowsInFlight];
 #pragma unroll
@@ -259,8 +340,8 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
         u3.q = next_unit();
     }
     if (waiting) copy_pass(head, (int)waiting);       // fewer than a pass left
-    if (DEDUP) {
-        pad_deferred();
+    if (SHARE) {
+        if (SHARE == 1) pad_deferred();
         if (count_rows) {
             for (int off = 32; off > 0; off >>= 1) fetched += __shfl_down(fetched, off);
             if (lane64 == 0 && fetched)
@@ -283,8 +364,8 @@ __device__ inline void scan_cold_rows(const id_lists_t &lists, int n_lists, cons
 //       GATHER_HOST     every row from host memory: the untiered copy that fills the HBM
 //                       cache at placement time
 // SPLIT:  grid row 0 holds the cold workers (scan_cold_rows), list b is served by grid row b + 1
-//         and skips its cold rows.  DEDUP: the workers fetch every distinct cold row once.
-template <int LPR, int MODE, bool SPLIT, bool DEDUP>
+//         and skips its cold rows.  SHARE != 0: the workers fetch every distinct cold row once.
+template <int LPR, int MODE, bool SPLIT, int SHARE>
 __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32_t *__restrict__ slot,
                                                    const uint32_t *__restrict__ hot_bits,
                                                    const uint4 *__restrict__ cache,
@@ -295,7 +376,7 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
 {
     constexpr int kGroups = kBlock / LPR;
     if (SPLIT && blockIdx.y == 0) {
-        scan_cold_rows<LPR, MODE, DEDUP>(lists, (int)gridDim.y - 1, hot_bits, n_nodes, n_hot, cold, host, out_base, cpr,
+        scan_cold_rows<LPR, MODE, SHARE>(lists, (int)gridDim.y - 1, hot_bits, n_nodes, n_hot, cold, host, out_base, cpr,
                                          meta, count_hits);
         return;
     }
@@ -368,6 +449,28 @@ __global__ __launch_bounds__(kBlock) void k_gather(id_lists_t lists, const int32
                 atomicAdd((unsigned long long *)&meta[META_HIT_ROWS + ((blockIdx.x + blockIdx.y) & (META_HIT_STRIPES - 1))],
                           (unsigned long long)t);
         }
+    }
+}
+
+// Lists of requests, first step: every cold request of the call enters the list of its id.  claim[id] =
+// stamp | number of the last request that arrived; the pair of a request = (the one that was last before
+// it, or -1 if the claim was not of this call; its output row).  Grid row b serves list b.
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void k_link(id_lists_t lists, const uint32_t *__restrict__ hot_bits, int64_t n_nodes,
+                                                 int64_t n_hot, unsigned long long *__restrict__ claim,
+                                                 unsigned long long stamp, int64_t *__restrict__ pairs)
+{
+    const int b = blockIdx.y;
+    const int32_t *__restrict__ ids = lists.ids[b];
+    const int64_t n = lists.n[b], stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+        const int32_t id = ids[i];
+        if (!is_cold<MODE>(id, hot_bits, n_nodes, n_hot)) continue;
+        const int64_t req = lists.first_req[b] + i;
+        const unsigned long long old = atomicExch(&claim[id], stamp | (unsigned long long)req);
+        const bool mine = (old >> kClaimRowBits) == (stamp >> kClaimRowBits);
+        pairs[2 * req] = mine ? (int64_t)(old & ((1ull << kClaimRowBits) - 1ull)) : -1;
+        pairs[2 * req + 1] = lists.out_row[b] + i;
     }
 }
 
@@ -447,7 +550,8 @@ int lanes_per_row(int cpr)
 }  // namespace
 
 // One k_gather launch on stream st, bookkeeping words in meta.  split: with cold workers;
-// dedup (with split only): they fetch every distinct cold row of the launch once.
+// share (with split only): they fetch every distinct cold row of the launch once, by claims and
+// deferred copies (1) or by lists of requests (2: k_link first, no copies afterwards).
 // The hot tier a launch reads: the context's placement, or the rows staged ahead of one.
 struct hot_tier_t {
     const int32_t *slot;
@@ -457,7 +561,7 @@ struct hot_tier_t {
 };
 
 static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int64_t n_max, int mode, void *out,
-                        bool count_hits, hipStream_t st, int64_t *meta, bool split = false, bool dedup = false,
+                        bool count_hits, hipStream_t st, int64_t *meta, bool split = false, int share = 0,
                         const hot_tier_t *other_tier = nullptr, int link_blocks_cap = 0)
 {
     const hot_tier_t hot = other_tier ? *other_tier : hot_tier_t{ctx->slot, ctx->hot_bits, ctx->cache, ctx->n_hot};
@@ -478,11 +582,22 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
     if (split) {
         const int want = ctx->link_blocks > 0 ? ctx->link_blocks : kLinkBlocks;
         cold.workers = (int)(want < blocks ? want : blocks);
-        if (dedup) {
+        if (share) {
             cold.stamp = (unsigned long long)ctx->claim_stamp << kClaimRowBits;
             cold.claim = ctx->claim;
             cold.deferred = ctx->deferred;
         }
+    }
+    if (split && share == 2) {
+        int64_t lb = (n_max + kBlock - 1) / kBlock;
+        if (lb > 4096) lb = 4096;
+        const dim3 lgrid((unsigned)lb, (unsigned)n_lists);
+        if (mode == GATHER_BOUNDARY)
+            k_link<GATHER_BOUNDARY><<<lgrid, kBlock, 0, st>>>(lists, hot.hot_bits, ctx->n_nodes, hot.n_hot, ctx->claim, cold.stamp,
+                                                              ctx->deferred);
+        else
+            k_link<GATHER_SLOT><<<lgrid, kBlock, 0, st>>>(lists, hot.hot_bits, ctx->n_nodes, hot.n_hot, ctx->claim, cold.stamp,
+                                                          ctx->deferred);
     }
     const dim3 grid((unsigned)blocks, (unsigned)(n_lists + (split ? 1 : 0)));
 #define GATHER_LAUNCH(L, M, P, D)                                                                    \
@@ -491,13 +606,15 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
                                                   ctx->n_nodes, hot.n_hot, meta, count_hits ? 1 : 0, cold)
 #define GATHER_CASE(L)                                                                               \
     case L:                                                                                          \
-        if (mode == GATHER_SLOT && split && dedup) GATHER_LAUNCH(L, GATHER_SLOT, true, true);        \
-        else if (mode == GATHER_BOUNDARY && split && dedup) GATHER_LAUNCH(L, GATHER_BOUNDARY, true, true); \
-        else if (mode == GATHER_SLOT && split) GATHER_LAUNCH(L, GATHER_SLOT, true, false);           \
-        else if (mode == GATHER_BOUNDARY && split) GATHER_LAUNCH(L, GATHER_BOUNDARY, true, false);   \
-        else if (mode == GATHER_SLOT) GATHER_LAUNCH(L, GATHER_SLOT, false, false);                   \
-        else if (mode == GATHER_BOUNDARY) GATHER_LAUNCH(L, GATHER_BOUNDARY, false, false);           \
-        else GATHER_LAUNCH(L, GATHER_HOST, false, false);                                            \
+        if (mode == GATHER_SLOT && split && share == 2) GATHER_LAUNCH(L, GATHER_SLOT, true, 2);      \
+        else if (mode == GATHER_BOUNDARY && split && share == 2) GATHER_LAUNCH(L, GATHER_BOUNDARY, true, 2); \
+        else if (mode == GATHER_SLOT && split && share) GATHER_LAUNCH(L, GATHER_SLOT, true, 1);      \
+        else if (mode == GATHER_BOUNDARY && split && share) GATHER_LAUNCH(L, GATHER_BOUNDARY, true, 1); \
+        else if (mode == GATHER_SLOT && split) GATHER_LAUNCH(L, GATHER_SLOT, true, 0);               \
+        else if (mode == GATHER_BOUNDARY && split) GATHER_LAUNCH(L, GATHER_BOUNDARY, true, 0);       \
+        else if (mode == GATHER_SLOT) GATHER_LAUNCH(L, GATHER_SLOT, false, 0);                       \
+        else if (mode == GATHER_BOUNDARY) GATHER_LAUNCH(L, GATHER_BOUNDARY, false, 0);               \
+        else GATHER_LAUNCH(L, GATHER_HOST, false, 0);                                                \
         break;
     switch (lpr) {
         GATHER_CASE(8)
@@ -508,7 +625,7 @@ static int launch_lists(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int
 #undef GATHER_CASE
 #undef GATHER_LAUNCH
     TIER_HIP(ctx, hipGetLastError());
-    if (split && dedup) {
+    if (split && share == 1) {
         const dim3 dgrid(1024);
         switch (lpr) {
         case 8: k_copy_deferred<8><<<dgrid, kBlock, 0, st>>>(ctx->deferred, meta, (uint4 *)out, cpr); break;
@@ -569,7 +686,16 @@ static int gather_call(tier_ctx *ctx, const id_lists_t &lists, int n_lists, int6
             k_zero_claims<<<4096, kBlock, 0, st>>>(ctx->claim, ctx->n_nodes);
             ctx->claim_stamp = 1;
         }
-        return launch_lists(ctx, lists, n_lists, n_max, mode, out, count_hits, st, ctx->gmeta, true, true);
+        // a call that asks for at least twice as many rows as there are nodes repeats most of its ids: lists of
+        // requests instead of copies afterwards (rows of up to kFanPieces x 64 x 16 bytes: a lane holds the pieces)
+        const bool by_lists = n_total >= 2 * ctx->n_nodes && ctx->row_bytes <= kFanPieces * 64 * 16;
+        id_lists_t numbered = lists;
+        int64_t before = 0;
+        for (int b = 0; b < n_lists; ++b) {
+            numbered.first_req[b] = before;
+            before += lists.n[b];
+        }
+        return launch_lists(ctx, numbered, n_lists, n_max, mode, out, count_hits, st, ctx->gmeta, true, by_lists ? 2 : 1);
     }
     const bool split = ctx->link_blocks > 0 && any_cold && n_total >= ctx->split_min_rows;
     return launch_lists(ctx, lists, n_lists, n_max, mode, out, count_hits, st, ctx->gmeta, split);
