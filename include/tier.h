@@ -352,12 +352,15 @@ int tier_set_gather_split(tier_ctx *ctx, int32_t link_blocks, int64_t min_rows);
  * option implies for every call with cold rows; link_blocks as set by
  * tier_set_gather_split, else 64) claim a cold id in a table over all nodes before they
  * fetch it, the requests that find it claimed are served by a second, short kernel that
- * copies the row inside HBM from the output row of the request that fetched it.  Results
- * are the same; it pays when the mini-batches of one tier_gather_minibatches call overlap
- * in their cold rows and costs one atomic per cold request and that second kernel
- * otherwise.  Scratch owned by the context: 8 n_nodes bytes for the claims (allocated
- * here) and 16 bytes per request of the largest call.  Off by default.  Waits for the
- * gather stream. */
+ * copies the row inside HBM from the output row of the request that fetched it.  (A call
+ * that asks for at least twice as many rows as the graph has nodes, of at most 4096 bytes
+ * each, is served another way: a first kernel threads the cold requests of every id into
+ * a list, and the worker that fetches a row writes it to every request on its list; no
+ * second kernel.)  Results are the same; it pays when the mini-batches of one
+ * tier_gather_minibatches call overlap in their cold rows and costs one atomic per cold
+ * request and that second kernel otherwise.  Scratch owned by the context: 8 n_nodes
+ * bytes for the claims (allocated here) and 16 bytes per request of the largest call.
+ * Off by default.  Waits for the gather stream. */
 int tier_set_gather_dedup(tier_ctx *ctx, int on);
 
 /* Put the gathers of this context on a stream of their own (NULL = back to the stream of
