@@ -528,11 +528,15 @@ def test_batched_gather_equals_per_batch_gathers(small):
     assert offs1 == [0] and torch.equal(out1, out[: blk.n_nodes[0][2]])
 
 
-@pytest.mark.parametrize("dim,boundary", [(32, False), (100, False), (8, True)])
+@pytest.mark.parametrize("dim,boundary", [(32, False), (100, False), (8, True), (256, False), (384, False), (1000, False),
+                                          (1100, False)])
 def test_shared_misses_give_the_same_rows(dim, boundary):
     """With tier_set_gather_dedup every distinct cold row crosses the host link once; the rows
     delivered, the hit/miss counts and the oracle's gather are unchanged, and the rows read
-    over the link are exactly the distinct cold ids of the call."""
+    over the link are exactly the distinct cold ids of the call.  The call of all mini-batches asks
+    for many times more rows than the graph has nodes and goes by lists of requests (rows of one to
+    four 16-byte pieces per lane; the 4400-byte rows are too long for that and keep the claims, as
+    the small single-list call at the end does)."""
     ip, ix = synth.rmat_csr(6000, 80_000, 5, "cpu")
     w = World(ip, ix, dim=dim)
     try:
